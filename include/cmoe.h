@@ -1,0 +1,165 @@
+/*
+ * cmoe.h - C ABI of libcmoe: a dense SwiGLU FFN restructured analytically into shared +
+ * routed experts, and its forward pass on one MI355X (gfx950).
+ *
+ * Vocabulary follows the paper (arXiv 2502.04416):
+ *   d      model width                      d_h   FFN hidden width (d_ff here)
+ *   N      experts, m = d_h / N neurons each (Sec. 4.1)
+ *   N_s    shared (always-active) experts   N_r = N - N_s routed experts
+ *   N_k    routed experts selected per token (Eq. 4)
+ *   K_a    how many top-|h| neurons count as "active" per calibration token (App. A.2)
+ *   R_j    representative neuron of routed expert j (Eq. 7); the router is the pair of
+ *          columns R_j of W_gate / W_up (Eq. 8)
+ *   u, b   learnable gate scale and load-balance bias of Eq. 9 (both default to 0)
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative CMOE_E* code; cmoe_last_error()
+ *     returns a thread-local message for the last failure.  Nothing aborts or throws
+ *     across this boundary.  On failure output handles are left untouched.
+ *   - "host" pointers are ordinary CPU memory, read during the call and not retained.
+ *     "device" pointers are HIP device memory owned by the caller; they must stay valid
+ *     until the work enqueued on the stream has finished.  The library owns only the
+ *     opaque handle and its host-side metadata; the forward calls never allocate.
+ *   - Matrices are row-major in the paper's orientation: W_gate, W_up are [d, d_h]
+ *     (column i belongs to neuron i), W_down is [d_h, d] (row i belongs to neuron i),
+ *     token batches are [T, d].
+ *   - dtype CMOE_BF16: host weights arrive as fp32 and are rounded once to bf16
+ *     (round-to-nearest-even); x and y on the device are bf16; products accumulate in fp32;
+ *     router scores are fp32.  dtype CMOE_F32: everything is fp32.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Forward
+ *     calls only enqueue work; they do not synchronise.
+ *   - Same inputs give bit-identical outputs from run to run (no floating-point atomics).
+ */
+#ifndef CMOE_H
+#define CMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CMOE_OK       0
+#define CMOE_EINVAL  -1   /* bad argument: null pointer, shape, workspace too small ...   */
+#define CMOE_ENOMEM  -2   /* host allocation failed                                       */
+#define CMOE_EHIP    -3   /* a HIP runtime call failed (message holds hipGetErrorString)  */
+#define CMOE_ESTATE  -4   /* call out of order (e.g. forward before upload)               */
+
+#define CMOE_F32   0
+#define CMOE_BF16  1
+
+typedef struct cmoe_layer cmoe_layer;   /* one restructured FFN (opaque)                       */
+typedef struct cmoe_hier  cmoe_hier;    /* an MoE layer whose experts were each restructured   */
+
+typedef struct {
+  int32_t d_model;       /* d                                                               */
+  int32_t d_ff;          /* d_h; must be a multiple of n_experts (m = d_h / N, Sec. 4.1)    */
+  int32_t n_experts;     /* N                                                               */
+  int32_t n_shared;      /* N_s, 0 <= N_s < N                                               */
+  int32_t top_k;         /* N_k, 1 <= N_k <= N_r; N_r <= 64                                 */
+  int32_t k_act;         /* K_a (the paper uses 10); only used by cmoe_build                */
+  int32_t kmeans_iters;  /* assignment + centroid-update rounds, >= 1; only cmoe_build      */
+  int32_t dtype;         /* CMOE_F32 or CMOE_BF16                                           */
+  int32_t dist_mode;     /* 0: L2 distance with the square root (App. A.3 as printed),
+                            1: squared L2 (= Hamming for binary vectors); only cmoe_build   */
+  int32_t score_mode;    /* 0: rank experts by the signed score s of Eq. 8, 1: by |s|       */
+} cmoe_config;
+
+/* ---- construction (host side; Sec. 4.1-4.2, App. A.2-A.4) ------------------------------- */
+
+/* build_moe: profile the calibration tokens (H, ATopK matrix A, rates mu), take the N_s*m
+ * neurons of highest rate as the shared expert, cluster the rest into N_r balanced groups
+ * (exact balanced assignment against the current centroids, then the mean update), pick the
+ * representative neuron of each group (Eq. 7) and slice the experts and the router out of
+ * the dense matrices.  All pointers are host fp32; calib_x is [q, d].  Ties go to the lowest
+ * index everywhere.  *out receives a new handle (free with cmoe_destroy). */
+int cmoe_build(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
+               const float* calib_x, int64_t q, cmoe_layer** out);
+
+/* Same slicing and packing, but from a given partition instead of profiling:
+ * neuron_order [d_h] lists dense neuron ids, the N_s*m shared ones first, then routed expert
+ * 0, 1, ... with m ids each; rep_neuron [N_r] holds the dense neuron id R_j of each routed
+ * expert (Eq. 7/8).  neuron_order must be a permutation of 0..d_h-1. */
+int cmoe_build_from_partition(const cmoe_config* cfg, const float* w_gate, const float* w_up,
+                              const float* w_down, const int32_t* neuron_order,
+                              const int32_t* rep_neuron, cmoe_layer** out);
+
+/* Copy the partition out: neuron_order [d_h], rep_neuron [N_r], mu [d_h] (activation rates;
+ * zeros when the layer came from cmoe_build_from_partition).  Any pointer may be NULL.
+ * cost (may be NULL) receives the objective of the last balanced assignment (App. A.3). */
+int cmoe_export_partition(const cmoe_layer* layer, int32_t* neuron_order, int32_t* rep_neuron,
+                          float* mu, double* cost);
+
+/* Gate parameters of Eq. 9: u [N_r] (NULL = zeros), b [N_r] (NULL = zeros), host fp32.
+ * With both zero the gate is the binary gate of Eq. 4 and no softmax is evaluated.
+ * May be called before or after cmoe_upload; takes effect at the next forward. */
+int cmoe_set_gate_params(cmoe_layer* layer, const float* u, const float* b);
+
+/* Bytes of device memory cmoe_upload needs for the packed weights (expert-sliced copy for the
+ * MoE forward, an unpadded copy for the dense baseline, and the router columns). */
+size_t cmoe_packed_bytes(const cmoe_layer* layer);
+
+/* Bytes of device workspace a forward call with up to max_tokens tokens needs. */
+size_t cmoe_workspace_bytes(const cmoe_layer* layer, int64_t max_tokens);
+
+/* Pack the weights (per-expert slices, gate/up rows interleaved, expert widths padded with
+ * zero neurons to the MFMA tile) and copy them into dev_weights (>= cmoe_packed_bytes, 256-byte
+ * aligned).  Synchronises the stream before returning (the host staging buffer is freed). */
+int cmoe_upload(cmoe_layer* layer, void* dev_weights, void* hip_stream);
+
+/* moe_ffn_forward (Eq. 4 with the router of Eq. 8 and the gate of Eq. 9):
+ *   y[t] = E^s(x[t]) + sum over the N_k selected routed experts of g * E^r_j(x[t]).
+ * x_dev, y_dev: device [T, d] in the layer's dtype.  Optional device outputs (NULL to skip):
+ *   topk_idx_dev [T, N_k] int32  selected routed experts, descending key, ties to lowest id
+ *   scores_dev   [T, N_r] fp32   router scores s of Eq. 8
+ *   counts_dev   [N_r]    int32  tokens routed to each expert in this batch
+ * T = 0 is a no-op.  Errors: CMOE_EINVAL (null x/y/workspace, T < 0, workspace_bytes too small),
+ * CMOE_ESTATE (not uploaded), CMOE_EHIP (launch failure). */
+int cmoe_forward(cmoe_layer* layer, const void* x_dev, int64_t T, void* y_dev,
+                 int32_t* topk_idx_dev, float* scores_dev, int32_t* counts_dev,
+                 void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* The dense FFN F(x) of Eq. 3 on the same layer, with kernels of the same quality as the MoE
+ * path (one group, all tokens, all d_h neurons, no expert padding).  Same argument rules. */
+int cmoe_dense_forward(cmoe_layer* layer, const void* x_dev, int64_t T, void* y_dev,
+                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+void cmoe_destroy(cmoe_layer* layer);
+
+/* ---- hierarchical case (Sec. 4.4, Eq. 10) ------------------------------------------------ */
+
+/* An existing MoE layer with n_outer experts and a linear top-`outer_top_k` router
+ * (logits = x W_router + logit_offset, weights = softmax over the selected logits, ties to the
+ * lowest id), each of whose experts has been restructured into a cmoe_layer with the same
+ * cmoe_config.  `experts` [n_outer] are handles built by cmoe_build / _from_partition; the
+ * hierarchy borrows them (they must outlive it and must not be uploaded separately).
+ * w_router: host fp32 [d, n_outer]; logit_offset: host fp32 [n_outer] or NULL. */
+int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_top_k,
+                     const float* w_router, const float* logit_offset, cmoe_hier** out);
+size_t cmoe_hier_packed_bytes(const cmoe_hier* h);
+size_t cmoe_hier_workspace_bytes(const cmoe_hier* h, int64_t max_tokens);
+int cmoe_hier_upload(cmoe_hier* h, void* dev_weights, void* hip_stream);
+
+/* y[t] = sum over the selected outer experts e of w_e * (E^s_e(x) + sum_j g'_{e,j} E^r_{e,j}(x)).
+ * Optional device outputs: outer_idx_dev [T, outer_top_k] int32; sub_idx_dev
+ * [T, outer_top_k, N_k] int32 (sub-experts chosen inside each selected outer expert). */
+int cmoe_hier_forward(cmoe_hier* h, const void* x_dev, int64_t T, void* y_dev,
+                      int32_t* outer_idx_dev, int32_t* sub_idx_dev,
+                      void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* The un-restructured MoE layer (every outer expert evaluated densely), the baseline of the
+ * hierarchical case. */
+int cmoe_hier_dense_forward(cmoe_hier* h, const void* x_dev, int64_t T, void* y_dev,
+                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+void cmoe_hier_destroy(cmoe_hier* h);
+
+/* ---- misc -------------------------------------------------------------------------------- */
+
+const char* cmoe_last_error(void);   /* thread-local, never NULL */
+const char* cmoe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CMOE_H */

@@ -1,0 +1,393 @@
+"""ctypes binding of libcmoe.so (the C ABI declared in include/cmoe.h).
+
+Argument marshalling only: every step of the forward pass runs in the library's HIP kernels.
+PyTorch supplies device memory (torch.empty on cuda) and the current HIP stream, nothing else.
+There is no CPU fallback: if the library is missing, or was not built, every call raises.
+
+The module-level functions carry the C names (cmoe_build, cmoe_forward, ...) and take/return raw
+handles; `Layer` and `Hierarchy` wrap them for the tests and the bench.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcmoe.so")
+_lib = None
+
+CMOE_F32, CMOE_BF16 = 0, 1
+
+
+class CmoeError(RuntimeError):
+    pass
+
+
+class cmoe_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "d_model", "d_ff", "n_experts", "n_shared", "top_k", "k_act", "kmeans_iters", "dtype",
+        "dist_mode", "score_mode")]
+
+
+EXPORTS = [
+    "cmoe_build", "cmoe_build_from_partition", "cmoe_export_partition", "cmoe_set_gate_params",
+    "cmoe_packed_bytes", "cmoe_workspace_bytes", "cmoe_upload", "cmoe_forward", "cmoe_dense_forward",
+    "cmoe_destroy", "cmoe_hier_create", "cmoe_hier_packed_bytes", "cmoe_hier_workspace_bytes",
+    "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
+    "cmoe_last_error", "cmoe_version",
+]
+
+
+def load():
+    """Load libcmoe.so (built by __graft_entry__.build()).  Raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise CmoeError("libcmoe.so is not built (%s missing): run `python __graft_entry__.py`; "
+                        "there is no fallback path" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p, f32p, i64, sz = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int64, C.c_size_t
+    cfgp = C.POINTER(cmoe_config)
+    lib.cmoe_build.argtypes = [cfgp, f32p, f32p, f32p, f32p, i64, C.POINTER(vp)]
+    lib.cmoe_build_from_partition.argtypes = [cfgp, f32p, f32p, f32p, i32p, i32p, C.POINTER(vp)]
+    lib.cmoe_export_partition.argtypes = [vp, i32p, i32p, f32p, C.POINTER(C.c_double)]
+    lib.cmoe_set_gate_params.argtypes = [vp, f32p, f32p]
+    lib.cmoe_packed_bytes.argtypes = [vp]
+    lib.cmoe_packed_bytes.restype = sz
+    lib.cmoe_workspace_bytes.argtypes = [vp, i64]
+    lib.cmoe_workspace_bytes.restype = sz
+    lib.cmoe_upload.argtypes = [vp, vp, vp]
+    lib.cmoe_forward.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.cmoe_dense_forward.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+    lib.cmoe_destroy.argtypes = [vp]
+    lib.cmoe_destroy.restype = None
+    lib.cmoe_hier_create.argtypes = [C.POINTER(vp), C.c_int32, C.c_int32, f32p, f32p, C.POINTER(vp)]
+    lib.cmoe_hier_packed_bytes.argtypes = [vp]
+    lib.cmoe_hier_packed_bytes.restype = sz
+    lib.cmoe_hier_workspace_bytes.argtypes = [vp, i64]
+    lib.cmoe_hier_workspace_bytes.restype = sz
+    lib.cmoe_hier_upload.argtypes = [vp, vp, vp]
+    lib.cmoe_hier_forward.argtypes = [vp, vp, i64, vp, vp, vp, vp, sz, vp]
+    lib.cmoe_hier_dense_forward.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+    lib.cmoe_hier_destroy.argtypes = [vp]
+    lib.cmoe_hier_destroy.restype = None
+    lib.cmoe_last_error.restype = C.c_char_p
+    lib.cmoe_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise CmoeError("%s failed (%d): %s" % (what, rc, load().cmoe_last_error().decode()))
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _fp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def _ip(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def make_config(cfg, kmeans_iters: int = 1, dist_mode: int = 0, score_mode: int = 0) -> cmoe_config:
+    """cmoe_config from a synth.LayerConfig-like object (d_model, d_ff, n_experts, n_shared, top_k, k_act, dtype)."""
+    return cmoe_config(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.n_shared, cfg.top_k, cfg.k_act, kmeans_iters,
+                       CMOE_BF16 if cfg.dtype == "bf16" else CMOE_F32, dist_mode, score_mode)
+
+
+# ---- C names ------------------------------------------------------------------------------------
+
+def cmoe_build(cfg: cmoe_config, w_gate, w_up, w_down, calib_x) -> int:
+    wg, wu, wd, cx = _f32(w_gate), _f32(w_up), _f32(w_down), _f32(calib_x)
+    h = C.c_void_p()
+    _check(load().cmoe_build(C.byref(cfg), _fp(wg), _fp(wu), _fp(wd), _fp(cx), cx.shape[0], C.byref(h)), "cmoe_build")
+    return h.value
+
+
+def cmoe_build_from_partition(cfg: cmoe_config, w_gate, w_up, w_down, neuron_order, rep_neuron) -> int:
+    wg, wu, wd = _f32(w_gate), _f32(w_up), _f32(w_down)
+    no, rn = _i32(neuron_order), _i32(rep_neuron)
+    h = C.c_void_p()
+    _check(load().cmoe_build_from_partition(C.byref(cfg), _fp(wg), _fp(wu), _fp(wd), _ip(no), _ip(rn), C.byref(h)),
+           "cmoe_build_from_partition")
+    return h.value
+
+
+def cmoe_export_partition(layer: int, d_ff: int, n_routed: int) -> Dict[str, np.ndarray]:
+    order = np.empty(d_ff, dtype=np.int32)
+    reps = np.empty(n_routed, dtype=np.int32)
+    mu = np.empty(d_ff, dtype=np.float32)
+    cost = C.c_double()
+    _check(load().cmoe_export_partition(layer, _ip(order), _ip(reps), _fp(mu), C.byref(cost)), "cmoe_export_partition")
+    return {"neuron_order": order, "rep_neuron": reps, "mu": mu, "cost": cost.value}
+
+
+def cmoe_set_gate_params(layer: int, u, b) -> None:
+    uu = None if u is None else _f32(u)
+    bb = None if b is None else _f32(b)
+    _check(load().cmoe_set_gate_params(layer, _fp(uu), _fp(bb)), "cmoe_set_gate_params")
+
+
+def cmoe_packed_bytes(layer: int) -> int:
+    return load().cmoe_packed_bytes(layer)
+
+
+def cmoe_workspace_bytes(layer: int, max_tokens: int) -> int:
+    return load().cmoe_workspace_bytes(layer, max_tokens)
+
+
+def cmoe_upload(layer: int, dev_weights_ptr: int, stream: int = 0) -> None:
+    _check(load().cmoe_upload(layer, dev_weights_ptr, stream), "cmoe_upload")
+
+
+def cmoe_forward(layer: int, x_ptr: int, T: int, y_ptr: int, topk_ptr, scores_ptr, counts_ptr, ws_ptr: int,
+                 ws_bytes: int, stream: int = 0) -> None:
+    _check(load().cmoe_forward(layer, x_ptr, T, y_ptr, topk_ptr, scores_ptr, counts_ptr, ws_ptr, ws_bytes, stream),
+           "cmoe_forward")
+
+
+def cmoe_dense_forward(layer: int, x_ptr: int, T: int, y_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(load().cmoe_dense_forward(layer, x_ptr, T, y_ptr, ws_ptr, ws_bytes, stream), "cmoe_dense_forward")
+
+
+def cmoe_destroy(layer: int) -> None:
+    load().cmoe_destroy(layer)
+
+
+def cmoe_hier_create(layers: Sequence[int], outer_top_k: int, w_router, logit_offset) -> int:
+    arr = (C.c_void_p * len(layers))(*layers)
+    wr = _f32(w_router)
+    off = None if logit_offset is None else _f32(logit_offset)
+    h = C.c_void_p()
+    _check(load().cmoe_hier_create(arr, len(layers), outer_top_k, _fp(wr), _fp(off), C.byref(h)), "cmoe_hier_create")
+    return h.value
+
+
+def cmoe_hier_packed_bytes(h: int) -> int:
+    return load().cmoe_hier_packed_bytes(h)
+
+
+def cmoe_hier_workspace_bytes(h: int, max_tokens: int) -> int:
+    return load().cmoe_hier_workspace_bytes(h, max_tokens)
+
+
+def cmoe_hier_upload(h: int, dev_ptr: int, stream: int = 0) -> None:
+    _check(load().cmoe_hier_upload(h, dev_ptr, stream), "cmoe_hier_upload")
+
+
+def cmoe_hier_forward(h: int, x_ptr: int, T: int, y_ptr: int, outer_ptr, sub_ptr, ws_ptr: int, ws_bytes: int,
+                      stream: int = 0) -> None:
+    _check(load().cmoe_hier_forward(h, x_ptr, T, y_ptr, outer_ptr, sub_ptr, ws_ptr, ws_bytes, stream), "cmoe_hier_forward")
+
+
+def cmoe_hier_dense_forward(h: int, x_ptr: int, T: int, y_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(load().cmoe_hier_dense_forward(h, x_ptr, T, y_ptr, ws_ptr, ws_bytes, stream), "cmoe_hier_dense_forward")
+
+
+def cmoe_hier_destroy(h: int) -> None:
+    load().cmoe_hier_destroy(h)
+
+
+def cmoe_version() -> str:
+    return load().cmoe_version().decode()
+
+
+# ---- conveniences for tests and the bench ----------------------------------------------------------
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise CmoeError("no HIP device: the forward pass runs only on the GPU (there is no CPU path)")
+    return torch
+
+
+def _stream_ptr(torch) -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+class _DeviceMixin:
+    """Device buffers (allocated through torch) shared by Layer and Hierarchy."""
+
+    def _alloc(self, nbytes: int):
+        torch = _torch()
+        return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+    def _to_device(self, x):
+        torch = _torch()
+        if isinstance(x, np.ndarray):
+            x = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+        x = x.to(device="cuda", dtype=torch.bfloat16 if self.bf16 else torch.float32).contiguous()
+        return x
+
+    def _ensure_ws(self, T: int):
+        if T > self._ws_tokens:
+            self._ws = None
+            self._ws = self._alloc(self._ws_bytes(T))
+            self._ws_tokens = T
+        return self._ws
+
+
+class Layer(_DeviceMixin):
+    """One restructured FFN on the GPU."""
+
+    def __init__(self, handle: int, cfg):
+        self.h = handle
+        self.cfg = cfg
+        self.bf16 = cfg.dtype == "bf16"
+        self._weights = None
+        self._ws = None
+        self._ws_tokens = -1
+
+    @classmethod
+    def from_partition(cls, cfg, w_gate, w_up, w_down, neuron_order, rep_neuron, score_mode: int = 0, upload=True):
+        h = cmoe_build_from_partition(make_config(cfg, score_mode=score_mode), w_gate, w_up, w_down, neuron_order, rep_neuron)
+        self = cls(h, cfg)
+        if upload:
+            self.upload()
+        return self
+
+    @classmethod
+    def build(cls, cfg, w_gate, w_up, w_down, calib_x, kmeans_iters=1, dist_mode=0, upload=True):
+        h = cmoe_build(make_config(cfg, kmeans_iters, dist_mode), w_gate, w_up, w_down, calib_x)
+        self = cls(h, cfg)
+        if upload:
+            self.upload()
+        return self
+
+    def upload(self):
+        torch = _torch()
+        self._weights = self._alloc(cmoe_packed_bytes(self.h))
+        cmoe_upload(self.h, self._weights.data_ptr(), _stream_ptr(torch))
+
+    def _ws_bytes(self, T):
+        return cmoe_workspace_bytes(self.h, T)
+
+    def export_partition(self):
+        return cmoe_export_partition(self.h, self.cfg.d_ff, self.cfg.n_routed)
+
+    def set_gate_params(self, u, b):
+        cmoe_set_gate_params(self.h, u, b)
+
+    def forward_device(self, x_dev, y_dev, topk=None, scores=None, counts=None):
+        """x_dev, y_dev: torch cuda tensors [T, d] in the layer dtype; enqueues only."""
+        torch = _torch()
+        T = x_dev.shape[0]
+        ws = self._ensure_ws(T)
+        cmoe_forward(self.h, x_dev.data_ptr(), T, y_dev.data_ptr(),
+                     None if topk is None else topk.data_ptr(), None if scores is None else scores.data_ptr(),
+                     None if counts is None else counts.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(torch))
+
+    def dense_forward_device(self, x_dev, y_dev):
+        torch = _torch()
+        T = x_dev.shape[0]
+        ws = self._ensure_ws(T)
+        cmoe_dense_forward(self.h, x_dev.data_ptr(), T, y_dev.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(torch))
+
+    def forward(self, x) -> Dict[str, np.ndarray]:
+        torch = _torch()
+        xd = self._to_device(x)
+        T = xd.shape[0]
+        c = self.cfg
+        y = torch.empty_like(xd)
+        topk = torch.full((max(T, 1), c.top_k), -1, dtype=torch.int32, device="cuda")
+        scores = torch.zeros((max(T, 1), c.n_routed), dtype=torch.float32, device="cuda")
+        counts = torch.zeros((c.n_routed,), dtype=torch.int32, device="cuda")
+        self.forward_device(xd, y, topk, scores, counts)
+        torch.cuda.synchronize()
+        return {"y": y.float().cpu().numpy().astype(np.float64), "topk": topk.cpu().numpy()[:T].astype(np.int64),
+                "scores": scores.cpu().numpy()[:T].astype(np.float64), "counts": counts.cpu().numpy()}
+
+    def dense_forward(self, x) -> np.ndarray:
+        torch = _torch()
+        xd = self._to_device(x)
+        y = torch.empty_like(xd)
+        self.dense_forward_device(xd, y)
+        torch.cuda.synchronize()
+        return y.float().cpu().numpy().astype(np.float64)
+
+    def close(self):
+        if self.h:
+            cmoe_destroy(self.h)
+            self.h = None
+        self._weights = None
+        self._ws = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Hierarchy(_DeviceMixin):
+    """An MoE layer whose experts were each restructured (Sec. 4.4)."""
+
+    def __init__(self, layers: Sequence[Layer], outer_top_k: int, w_router, logit_offset):
+        self.layers = list(layers)
+        self.cfg = layers[0].cfg
+        self.bf16 = self.cfg.dtype == "bf16"
+        self.outer_top_k = outer_top_k
+        self.h = cmoe_hier_create([l.h for l in layers], outer_top_k, w_router, logit_offset)
+        torch = _torch()
+        self._weights = self._alloc(cmoe_hier_packed_bytes(self.h))
+        cmoe_hier_upload(self.h, self._weights.data_ptr(), _stream_ptr(torch))
+        self._ws = None
+        self._ws_tokens = -1
+
+    def _ws_bytes(self, T):
+        return cmoe_hier_workspace_bytes(self.h, T)
+
+    def forward_device(self, x_dev, y_dev, outer=None, sub=None):
+        torch = _torch()
+        T = x_dev.shape[0]
+        ws = self._ensure_ws(T)
+        cmoe_hier_forward(self.h, x_dev.data_ptr(), T, y_dev.data_ptr(), None if outer is None else outer.data_ptr(),
+                          None if sub is None else sub.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(torch))
+
+    def dense_forward_device(self, x_dev, y_dev):
+        torch = _torch()
+        T = x_dev.shape[0]
+        ws = self._ensure_ws(T)
+        cmoe_hier_dense_forward(self.h, x_dev.data_ptr(), T, y_dev.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(torch))
+
+    def forward(self, x) -> Dict[str, np.ndarray]:
+        torch = _torch()
+        xd = self._to_device(x)
+        T = xd.shape[0]
+        y = torch.empty_like(xd)
+        outer = torch.full((T, self.outer_top_k), -1, dtype=torch.int32, device="cuda")
+        sub = torch.full((T, self.outer_top_k, self.cfg.top_k), -1, dtype=torch.int32, device="cuda")
+        self.forward_device(xd, y, outer, sub)
+        torch.cuda.synchronize()
+        return {"y": y.float().cpu().numpy().astype(np.float64), "outer": outer.cpu().numpy().astype(np.int64),
+                "sub": sub.cpu().numpy().astype(np.int64)}
+
+    def dense_forward(self, x) -> np.ndarray:
+        torch = _torch()
+        xd = self._to_device(x)
+        y = torch.empty_like(xd)
+        self.dense_forward_device(xd, y)
+        torch.cuda.synchronize()
+        return y.float().cpu().numpy().astype(np.float64)
+
+    def close(self):
+        if self.h:
+            cmoe_hier_destroy(self.h)
+            self.h = None
+        for l in self.layers:
+            l.close()
+        self._weights = None
+        self._ws = None

@@ -1,0 +1,735 @@
+// C ABI of libcmoe (see include/cmoe.h): handles, argument checks, weight packing and upload, and the
+// forward calls, which only enqueue kernels on the caller's stream.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/cmoe.h"
+#include "cmoe_internal.h"
+#include "host_build.h"
+#include "host_pack.h"
+
+namespace cmoe {
+
+// ---------------------------------------------------------------------------------- errors
+static thread_local std::string g_err = "";
+static int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+static int fail_hip(hipError_t e, const char* what) {
+  return fail(CMOE_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---------------------------------------------------------------------------------- small helpers
+size_t elem_size(int dtype) { return dtype == CMOE_BF16 ? 2 : 4; }
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+void parallel_for(int64_t n, const std::function<void(int64_t)>& fn, int max_threads) {
+  int nt = max_threads > 0 ? max_threads : (int)std::thread::hardware_concurrency();
+  if (const char* env = std::getenv("CMOE_HOST_THREADS")) nt = std::atoi(env);
+  if (nt > 16) nt = 16;
+  if (nt < 1) nt = 1;
+  if ((int64_t)nt > n) nt = (int)std::max<int64_t>(n, 1);
+  if (nt == 1) {
+    for (int64_t i = 0; i < n; ++i) fn(i);
+    return;
+  }
+  std::vector<std::thread> th;
+  for (int w = 0; w < nt; ++w)
+    th.emplace_back([=, &fn]() {
+      const int64_t lo = n * w / nt, hi = n * (w + 1) / nt;
+      for (int64_t i = lo; i < hi; ++i) fn(i);
+    });
+  for (auto& t : th) t.join();
+}
+
+bool use_simt_experts(int dtype) {
+  static const int force = std::getenv("CMOE_FORCE_SIMT") ? std::atoi(std::getenv("CMOE_FORCE_SIMT")) : 0;
+  return dtype != CMOE_BF16 || force != 0;
+}
+
+int gemm_tile(int dtype, int which) { return use_simt_experts(dtype) ? simt_gemm_tile(which) : bf16_gemm_tile(which); }
+
+int64_t gemm_work_bound(const Engine& e, int64_t T, int which) {
+  const int bm = gemm_tile(e.dtype, which == 1 ? 1 : 2);
+  const int bn = gemm_tile(e.dtype, which == 1 ? 3 : 4);
+  auto nt_of = [&](int g) { return which == 1 ? cdiv(2 * e.width_pad_host[g], bn) : cdiv(e.d, bn); };
+  const int64_t mt_all = (T + bm - 1) / bm;
+  int64_t total = 0;
+  for (int g = 0; g < e.n_always; ++g) total += mt_all * nt_of(g);
+  int64_t per_group = 0;
+  int nt_max = 0;
+  for (int g = e.n_always; g < e.G; ++g) {
+    per_group += mt_all * nt_of(g);
+    nt_max = std::max(nt_max, nt_of(g));
+  }
+  const int64_t by_entries = (int64_t)nt_max * (T * e.S_dyn / bm + (e.G - e.n_always));
+  total += std::min(per_group, by_entries);
+  return std::max<int64_t>(total, 1);
+}
+
+WsLayout ws_layout(const Engine& e, int64_t T) {
+  WsLayout L{};
+  const size_t es = elem_size(e.dtype);
+  const int64_t Tn = std::max<int64_t>(T, 1);
+  const int S_all = e.S_all();
+  L.n_slots = Tn * S_all;
+  L.n_tok_tiles = (int)((Tn + TOK_TILE - 1) / TOK_TILE);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  L.sel_group = take(sizeof(int32_t) * Tn * std::max(e.S_dyn, 1));
+  L.sel_weight = take(sizeof(float) * Tn * std::max(e.S_dyn, 1));
+  L.tile_counts = take(sizeof(int32_t) * (size_t)L.n_tok_tiles * e.G);
+  L.seg_off = take(sizeof(int32_t) * (e.G + 1));
+  L.counts = take(sizeof(int32_t) * (e.G + 1));
+  L.work1 = take(sizeof(int32_t) * (e.G + 1));
+  L.work2 = take(sizeof(int32_t) * (e.G + 1));
+  L.h_off = take(sizeof(int64_t) * (e.G + 1));
+  L.slot2tok = take(sizeof(int32_t) * L.n_slots);
+  L.tok2slot = take(sizeof(int32_t) * L.n_slots);
+  L.slot_w = take(sizeof(float) * L.n_slots);
+  L.scores = take(sizeof(float) * Tn * std::max(e.r.n_scored + e.r.n_lin, 1));
+  L.h = take(es * (size_t)Tn * (size_t)e.h_per_token);
+  L.y_slots = take(S_all == 1 ? 0 : es * (size_t)L.n_slots * e.d);
+  L.total = off;
+  return L;
+}
+
+hipError_t launch_experts(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
+                          hipStream_t s) {
+  if (T == 0) return hipSuccess;
+  if (use_simt_experts(e.dtype)) return launch_experts_simt(e, x, T, ws, L, y, s);
+  return launch_experts_bf16(e, x, T, ws, L, y, s);
+}
+
+// ---------------------------------------------------------------------------------- packing
+static void store_elem(uint8_t* dst, int dtype, float v) {
+  if (dtype == CMOE_BF16) {
+    const uint16_t b = host_f32_to_bf16(v);
+    std::memcpy(dst, &b, 2);
+  } else {
+    std::memcpy(dst, &v, 4);
+  }
+}
+
+void RoundedDense::from_fp32(int dtype_, int d_, int d_ff_, const float* w_gate, const float* w_up,
+                             const float* w_down) {
+  dtype = dtype_;
+  d = d_;
+  d_ff = d_ff_;
+  const size_t es = elem_size(dtype);
+  gate_t.assign((size_t)d * d_ff * es, 0);
+  up_t.assign((size_t)d * d_ff * es, 0);
+  down.assign((size_t)d * d_ff * es, 0);
+  // blocked transpose [d][d_ff] -> [d_ff][d] with rounding; 64 neurons per task
+  const int64_t n_blocks = (d_ff + 63) / 64;
+  parallel_for(n_blocks, [&](int64_t b) {
+    const int i0 = (int)b * 64, i1 = std::min(d_ff, i0 + 64);
+    for (int k0 = 0; k0 < d; k0 += 64) {
+      const int k1 = std::min(d, k0 + 64);
+      for (int k = k0; k < k1; ++k) {
+        const float* gs = w_gate + (size_t)k * d_ff;
+        const float* us = w_up + (size_t)k * d_ff;
+        for (int i = i0; i < i1; ++i) {
+          store_elem(gate_t.data() + ((size_t)i * d + k) * es, dtype, gs[i]);
+          store_elem(up_t.data() + ((size_t)i * d + k) * es, dtype, us[i]);
+        }
+      }
+    }
+    for (int i = i0; i < i1; ++i) {
+      const float* src = w_down + (size_t)i * d;
+      uint8_t* dst = down.data() + (size_t)i * d * es;
+      for (int c = 0; c < d; ++c) store_elem(dst + (size_t)c * es, dtype, src[c]);
+    }
+  });
+}
+
+void pack_group(PackedSet& ps, const RoundedDense& rd, const int32_t* neurons, int width) {
+  const size_t es = elem_size(ps.dtype);
+  const int d = ps.d;
+  const int wp = round_up(width, WPAD);
+  GroupDev gd;
+  gd.width_pad = wp;
+  gd.w1_row0 = (int32_t)ps.w1_rows;
+  gd.w2_off = ps.w2_elems;
+  ps.groups.push_back(gd);
+  ps.width.push_back(width);
+  const size_t row_bytes = (size_t)d * es;
+  const size_t w1_base = ps.w1.size();
+  ps.w1.resize(w1_base + (size_t)2 * wp * row_bytes, 0);
+  const size_t w2_base = ps.w2.size();
+  ps.w2.resize(w2_base + (size_t)d * wp * es, 0);
+  ps.w1_rows += 2 * wp;
+  ps.w2_elems += (int64_t)d * wp;
+  // gate/up rows: packed row = blk*2*IL + {0: gate, IL: up} + c  <->  neuron blk*IL + c
+  parallel_for(wp / IL, [&](int64_t blk) {
+    for (int c = 0; c < IL; ++c) {
+      const int n = (int)blk * IL + c;
+      if (n >= width) continue;
+      uint8_t* g_dst = ps.w1.data() + w1_base + ((size_t)blk * 2 * IL + c) * row_bytes;
+      uint8_t* u_dst = ps.w1.data() + w1_base + ((size_t)blk * 2 * IL + IL + c) * row_bytes;
+      std::memcpy(g_dst, rd.gate_row(neurons[n]), row_bytes);
+      std::memcpy(u_dst, rd.up_row(neurons[n]), row_bytes);
+    }
+  });
+  // down: W2[c][n] = W_down[neuron n][c]; tiles of 64 output columns per task
+  parallel_for((d + 63) / 64, [&](int64_t cb) {
+    const int c0 = (int)cb * 64, c1 = std::min(d, c0 + 64);
+    for (int n = 0; n < width; ++n) {
+      const uint8_t* src = rd.down_row(neurons[n]);
+      for (int c = c0; c < c1; ++c)
+        std::memcpy(ps.w2.data() + w2_base + ((size_t)c * wp + n) * es, src + (size_t)c * es, es);
+    }
+  });
+}
+
+void pack_router_rows(std::vector<uint8_t>& out, int dtype, int d, int n_scored_total) {
+  const int rows = 2 * IL * cdiv(std::max(n_scored_total, 0), IL);
+  out.assign((size_t)rows * d * elem_size(dtype), 0);
+}
+
+void set_router_rows(std::vector<uint8_t>& out, const RoundedDense& rd, int scored_index, int32_t rep) {
+  const size_t row_bytes = (size_t)rd.d * elem_size(rd.dtype);
+  const int blk = scored_index / IL, c = scored_index % IL;
+  std::memcpy(out.data() + ((size_t)blk * 2 * IL + c) * row_bytes, rd.gate_row(rep), row_bytes);
+  std::memcpy(out.data() + ((size_t)blk * 2 * IL + IL + c) * row_bytes, rd.up_row(rep), row_bytes);
+}
+
+}  // namespace cmoe
+
+using namespace cmoe;
+
+// ---------------------------------------------------------------------------------- handles
+struct cmoe_layer {
+  cmoe_config cfg{};
+  int m = 0, n_r = 0;
+  std::vector<int32_t> neuron_order, rep_neuron;
+  std::vector<float> mu;
+  double cost = 0.0;
+  PackedSet moe, dense;
+  std::vector<uint8_t> router;                 // [n_sw_rows][d]
+  std::vector<uint8_t> rep_rows;               // [N_r][2][d] gate row, up row of each R_j (for a hierarchy)
+  std::vector<float> u, b;
+  bool has_u = false, has_b = false;
+  bool uploaded = false;
+  bool in_hier = false;
+  Engine e_moe, e_dense;
+  float* d_u = nullptr;
+  float* d_b = nullptr;
+};
+
+struct cmoe_hier {
+  std::vector<cmoe_layer*> experts;
+  cmoe_config cfg{};
+  int n_outer = 0, outer_top_k = 0;
+  std::vector<uint8_t> router;                 // SwiGLU rows of all sub-routers, then IL linear rows
+  std::vector<uint8_t> lin_rows;               // [IL][d] outer router, rows = outer experts
+  std::vector<float> lin_off;
+  bool uploaded = false;
+  Engine e_moe, e_dense;
+};
+
+static int check_config(const cmoe_config* c) {
+  if (!c) return fail(CMOE_EINVAL, "config is null");
+  if (c->dtype != CMOE_F32 && c->dtype != CMOE_BF16) return fail(CMOE_EINVAL, "dtype must be CMOE_F32 or CMOE_BF16");
+  if (c->d_model < 1 || c->d_ff < 1 || c->n_experts < 1) return fail(CMOE_EINVAL, "d_model, d_ff, n_experts must be positive");
+  if (c->d_ff % c->n_experts != 0)
+    return fail(CMOE_EINVAL, "d_ff (%d) is not a multiple of n_experts (%d): m = d_h / N must be integral", c->d_ff, c->n_experts);
+  if (c->n_shared < 0 || c->n_shared >= c->n_experts) return fail(CMOE_EINVAL, "need 0 <= n_shared < n_experts");
+  const int n_r = c->n_experts - c->n_shared;
+  if (c->top_k < 1 || c->top_k > n_r) return fail(CMOE_EINVAL, "need 1 <= top_k <= n_experts - n_shared (%d)", n_r);
+  if (c->top_k > MAX_TOPK) return fail(CMOE_EINVAL, "top_k above %d is not supported", MAX_TOPK);
+  if (n_r > MAX_SCORED) return fail(CMOE_EINVAL, "more than %d routed experts are not supported", MAX_SCORED);
+  if (c->dtype == CMOE_BF16 && c->d_model % 8 != 0) return fail(CMOE_EINVAL, "bf16 layers need d_model %% 8 == 0");
+  if (c->score_mode != 0 && c->score_mode != 1) return fail(CMOE_EINVAL, "score_mode must be 0 or 1");
+  return CMOE_OK;
+}
+
+static void fill_flat_engines(cmoe_layer* L) {
+  const cmoe_config& c = L->cfg;
+  Engine& e = L->e_moe;
+  e = Engine{};
+  e.dtype = c.dtype;
+  e.d = c.d_model;
+  e.G = (int)L->moe.groups.size();
+  e.n_always = c.n_shared > 0 ? 1 : 0;
+  e.S_dyn = c.top_k;
+  e.h_per_token = 0;
+  for (int g = 0; g < e.G; ++g) {
+    e.width_pad_host[g] = L->moe.groups[g].width_pad;
+    e.max_width_pad = std::max(e.max_width_pad, L->moe.groups[g].width_pad);
+  }
+  if (e.n_always) e.h_per_token += L->moe.groups[0].width_pad;
+  e.h_per_token += (int64_t)c.top_k * L->moe.groups[e.G - 1].width_pad;
+  RouterDev& r = e.r;
+  r.n_scored = L->n_r;
+  r.n_sw_rows = 2 * IL * cdiv(L->n_r, IL);
+  r.n_lin = 0;
+  r.n_lin_rows = 0;
+  r.top_k = c.top_k;
+  r.outer_top_k = 0;
+  r.n_r_sub = L->n_r;
+  r.n_always = e.n_always;
+  r.score_abs = c.score_mode;
+  r.use_gate = (L->has_u || L->has_b) ? 1 : 0;
+  r.groups_per_outer = 0;
+  r.sub_has_shared = 0;
+  Engine& dn = L->e_dense;
+  dn = Engine{};
+  dn.dtype = c.dtype;
+  dn.d = c.d_model;
+  dn.G = 1;
+  dn.n_always = 1;
+  dn.S_dyn = 0;
+  dn.width_pad_host[0] = L->dense.groups[0].width_pad;
+  dn.max_width_pad = dn.width_pad_host[0];
+  dn.h_per_token = dn.width_pad_host[0];
+  dn.r.n_always = 1;
+}
+
+static int build_common(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
+                        const float* calib_x, int64_t q, const int32_t* order_in, const int32_t* rep_in,
+                        cmoe_layer** out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!w_gate || !w_up || !w_down || !out) return fail(CMOE_EINVAL, "null weight or output pointer");
+  const int d = cfg->d_model, d_ff = cfg->d_ff, N = cfg->n_experts, m = d_ff / N;
+  const int n_r = N - cfg->n_shared;
+  std::unique_ptr<cmoe_layer> L(new (std::nothrow) cmoe_layer());
+  if (!L) return fail(CMOE_ENOMEM, "out of host memory");
+  try {
+    L->cfg = *cfg;
+    L->m = m;
+    L->n_r = n_r;
+    L->mu.assign(d_ff, 0.0f);
+    RoundedDense rd;
+    rd.from_fp32(cfg->dtype, d, d_ff, w_gate, w_up, w_down);
+    if (order_in) {
+      if (!rep_in) return fail(CMOE_EINVAL, "rep_neuron is null");
+      std::vector<char> seen(d_ff, 0);
+      for (int i = 0; i < d_ff; ++i) {
+        const int v = order_in[i];
+        if (v < 0 || v >= d_ff || seen[v]) return fail(CMOE_EINVAL, "neuron_order is not a permutation of 0..d_ff-1 (entry %d)", i);
+        seen[v] = 1;
+      }
+      for (int j = 0; j < n_r; ++j)
+        if (rep_in[j] < 0 || rep_in[j] >= d_ff) return fail(CMOE_EINVAL, "rep_neuron[%d] out of range", j);
+      L->neuron_order.assign(order_in, order_in + d_ff);
+      L->rep_neuron.assign(rep_in, rep_in + n_r);
+    } else {
+      if (!calib_x || q < 1) return fail(CMOE_EINVAL, "calibration set is null or empty");
+      if (cfg->k_act < 1 || cfg->k_act > d_ff) return fail(CMOE_EINVAL, "need 1 <= k_act <= d_ff");
+      if (cfg->kmeans_iters < 1) return fail(CMOE_EINVAL, "kmeans_iters must be >= 1");
+      if (cfg->dist_mode != 0 && cfg->dist_mode != 1) return fail(CMOE_EINVAL, "dist_mode must be 0 or 1");
+      std::string msg;
+      L->neuron_order.resize(d_ff);
+      L->rep_neuron.resize(n_r);
+      if (!host_construct(*cfg, rd, calib_x, q, L->neuron_order.data(), L->rep_neuron.data(), L->mu.data(),
+                          &L->cost, &msg))
+        return fail(CMOE_EINVAL, "construction failed: %s", msg.c_str());
+    }
+    // expert groups: one shared group of N_s*m neurons (if any), then the routed experts
+    L->moe.dtype = cfg->dtype;
+    L->moe.d = d;
+    if (cfg->n_shared > 0) pack_group(L->moe, rd, L->neuron_order.data(), cfg->n_shared * m);
+    for (int j = 0; j < n_r; ++j) pack_group(L->moe, rd, L->neuron_order.data() + (size_t)(cfg->n_shared + j) * m, m);
+    // dense baseline: every neuron in its original order, one group, padded once
+    L->dense.dtype = cfg->dtype;
+    L->dense.d = d;
+    std::vector<int32_t> ident(d_ff);
+    for (int i = 0; i < d_ff; ++i) ident[i] = i;
+    pack_group(L->dense, rd, ident.data(), d_ff);
+    // router rows (Eq. 8)
+    pack_router_rows(L->router, cfg->dtype, d, n_r);
+    const size_t row_bytes = (size_t)d * elem_size(cfg->dtype);
+    L->rep_rows.assign((size_t)n_r * 2 * row_bytes, 0);
+    for (int j = 0; j < n_r; ++j) {
+      set_router_rows(L->router, rd, j, L->rep_neuron[j]);
+      std::memcpy(L->rep_rows.data() + (size_t)(2 * j) * row_bytes, rd.gate_row(L->rep_neuron[j]), row_bytes);
+      std::memcpy(L->rep_rows.data() + (size_t)(2 * j + 1) * row_bytes, rd.up_row(L->rep_neuron[j]), row_bytes);
+    }
+    L->u.assign(n_r, 0.0f);
+    L->b.assign(n_r, 0.0f);
+    fill_flat_engines(L.get());
+  } catch (const std::bad_alloc&) {
+    return fail(CMOE_ENOMEM, "out of host memory while packing");
+  }
+  *out = L.release();
+  return CMOE_OK;
+}
+
+extern "C" {
+
+int cmoe_build(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
+               const float* calib_x, int64_t q, cmoe_layer** out) {
+  if (!calib_x) return fail(CMOE_EINVAL, "calib_x is null");
+  return build_common(cfg, w_gate, w_up, w_down, calib_x, q, nullptr, nullptr, out);
+}
+
+int cmoe_build_from_partition(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
+                              const int32_t* neuron_order, const int32_t* rep_neuron, cmoe_layer** out) {
+  if (!neuron_order) return fail(CMOE_EINVAL, "neuron_order is null");
+  return build_common(cfg, w_gate, w_up, w_down, nullptr, 0, neuron_order, rep_neuron, out);
+}
+
+int cmoe_export_partition(const cmoe_layer* L, int32_t* neuron_order, int32_t* rep_neuron, float* mu, double* cost) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (neuron_order) std::memcpy(neuron_order, L->neuron_order.data(), sizeof(int32_t) * L->neuron_order.size());
+  if (rep_neuron) std::memcpy(rep_neuron, L->rep_neuron.data(), sizeof(int32_t) * L->rep_neuron.size());
+  if (mu) std::memcpy(mu, L->mu.data(), sizeof(float) * L->mu.size());
+  if (cost) *cost = L->cost;
+  return CMOE_OK;
+}
+
+int cmoe_set_gate_params(cmoe_layer* L, const float* u, const float* b) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (L->in_hier) return fail(CMOE_ESTATE, "gate parameters of a layer inside a hierarchy must be set before cmoe_hier_create");
+  L->has_u = u != nullptr;
+  L->has_b = b != nullptr;
+  for (int j = 0; j < L->n_r; ++j) {
+    L->u[j] = u ? u[j] : 0.0f;
+    L->b[j] = b ? b[j] : 0.0f;
+  }
+  L->e_moe.r.use_gate = (L->has_u || L->has_b) ? 1 : 0;
+  if (L->uploaded) {
+    hipError_t e = hipMemcpy(L->d_u, L->u.data(), sizeof(float) * L->n_r, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(L->d_b, L->b.data(), sizeof(float) * L->n_r, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(e, "copying gate parameters");
+  }
+  return CMOE_OK;
+}
+
+// device buffer of a flat layer: [moe W1][moe W2][dense W1][dense W2][router][moe groups][dense groups][u][b]
+struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, total; };
+static FlatOffsets flat_offsets(const cmoe_layer* L) {
+  FlatOffsets o{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off = align256(off + bytes); return r; };
+  o.w1 = take(L->moe.w1.size());
+  o.w2 = take(L->moe.w2.size());
+  o.dw1 = take(L->dense.w1.size());
+  o.dw2 = take(L->dense.w2.size());
+  o.wr = take(L->router.size());
+  o.g = take(sizeof(GroupDev) * L->moe.groups.size());
+  o.dg = take(sizeof(GroupDev) * L->dense.groups.size());
+  o.u = take(sizeof(float) * L->n_r);
+  o.b = take(sizeof(float) * L->n_r);
+  o.total = off;
+  return o;
+}
+
+size_t cmoe_packed_bytes(const cmoe_layer* L) { return L ? flat_offsets(L).total : 0; }
+
+size_t cmoe_workspace_bytes(const cmoe_layer* L, int64_t max_tokens) {
+  if (!L || max_tokens < 0) return 0;
+  return std::max(ws_layout(L->e_moe, max_tokens).total, ws_layout(L->e_dense, max_tokens).total);
+}
+
+static hipError_t h2d(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  return hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, s);
+}
+
+int cmoe_upload(cmoe_layer* L, void* dev_weights, void* hip_stream) {
+  if (!L || !dev_weights) return fail(CMOE_EINVAL, "layer or device buffer is null");
+  if (L->in_hier) return fail(CMOE_ESTATE, "layer belongs to a hierarchy; upload the hierarchy instead");
+  if (((uintptr_t)dev_weights & 255) != 0) return fail(CMOE_EINVAL, "device weight buffer must be 256-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const FlatOffsets o = flat_offsets(L);
+  char* base = static_cast<char*>(dev_weights);
+  hipError_t e = h2d(base + o.w1, L->moe.w1.data(), L->moe.w1.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.w2, L->moe.w2.data(), L->moe.w2.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.dw1, L->dense.w1.data(), L->dense.w1.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.dw2, L->dense.w2.data(), L->dense.w2.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.wr, L->router.data(), L->router.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.g, L->moe.groups.data(), sizeof(GroupDev) * L->moe.groups.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.dg, L->dense.groups.data(), sizeof(GroupDev) * L->dense.groups.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.u, L->u.data(), sizeof(float) * L->n_r, s);
+  if (e == hipSuccess) e = h2d(base + o.b, L->b.data(), sizeof(float) * L->n_r, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail_hip(e, "uploading packed weights");
+  Engine& m = L->e_moe;
+  m.w1 = base + o.w1;
+  m.w2 = base + o.w2;
+  m.wr = base + o.wr;
+  m.groups = reinterpret_cast<const GroupDev*>(base + o.g);
+  L->d_u = reinterpret_cast<float*>(base + o.u);
+  L->d_b = reinterpret_cast<float*>(base + o.b);
+  m.gate_u = L->d_u;
+  m.gate_b = L->d_b;
+  Engine& dn = L->e_dense;
+  dn.w1 = base + o.dw1;
+  dn.w2 = base + o.dw2;
+  dn.groups = reinterpret_cast<const GroupDev*>(base + o.dg);
+  L->uploaded = true;
+  return CMOE_OK;
+}
+
+static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_t* topk, int32_t* outer,
+                      float* scores, int32_t* counts, void* ws, size_t ws_bytes, hipStream_t s) {
+  if (T < 0) return fail(CMOE_EINVAL, "negative token count");
+  if (T == 0) return CMOE_OK;
+  if (!x || !y || !ws) return fail(CMOE_EINVAL, "x, y or workspace is null");
+  if (T * (int64_t)e.S_all() > (int64_t)0x7fffffff / 2) return fail(CMOE_EINVAL, "batch too large for 32-bit slot indices");
+  const WsLayout L = ws_layout(e, T);
+  if (ws_bytes < L.total) return fail(CMOE_EINVAL, "workspace too small: %zu bytes given, %zu needed", ws_bytes, L.total);
+  if (((uintptr_t)ws & 255) != 0) return fail(CMOE_EINVAL, "workspace must be 256-byte aligned");
+  char* w = static_cast<char*>(ws);
+  const bool single = (e.G == 1 && e.n_always == 1);
+  hipError_t err = hipSuccess;
+  if (!single) {
+    err = launch_router(e, x, T, w, L, topk, outer, scores, s);
+    if (err != hipSuccess) return fail_hip(err, "router kernel");
+    err = launch_permute(e, T, w, L, counts, s);
+    if (err != hipSuccess) return fail_hip(err, "permute kernel");
+  }
+  err = launch_experts(e, x, T, w, L, y, s);
+  if (err != hipSuccess) return fail_hip(err, "expert kernels");
+  err = launch_combine(e, T, w, L, y, s);
+  if (err != hipSuccess) return fail_hip(err, "combine kernel");
+  return CMOE_OK;
+}
+
+int cmoe_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev, int32_t* topk_idx_dev,
+                 float* scores_dev, int32_t* counts_dev, void* workspace_dev, size_t workspace_bytes,
+                 void* hip_stream) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (!L->uploaded) return fail(CMOE_ESTATE, "cmoe_upload has not been called");
+  Engine e = L->e_moe;
+  if (!L->has_u) e.gate_u = nullptr;
+  if (!L->has_b) e.gate_b = nullptr;
+  return run_engine(e, x_dev, T, y_dev, topk_idx_dev, nullptr, scores_dev, counts_dev, workspace_dev,
+                    workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int cmoe_dense_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev, void* workspace_dev,
+                       size_t workspace_bytes, void* hip_stream) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (!L->uploaded) return fail(CMOE_ESTATE, "cmoe_upload has not been called");
+  return run_engine(L->e_dense, x_dev, T, y_dev, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes,
+                    static_cast<hipStream_t>(hip_stream));
+}
+
+void cmoe_destroy(cmoe_layer* L) { delete L; }
+
+// ---------------------------------------------------------------------------------- hierarchy
+int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_top_k, const float* w_router,
+                     const float* logit_offset, cmoe_hier** out) {
+  if (!experts || !w_router || !out) return fail(CMOE_EINVAL, "null argument");
+  if (n_outer < 1 || n_outer > IL) return fail(CMOE_EINVAL, "need 1 <= n_outer <= %d", IL);
+  if (outer_top_k < 1 || outer_top_k > n_outer || outer_top_k > MAX_TOPK) return fail(CMOE_EINVAL, "bad outer_top_k");
+  for (int e = 0; e < n_outer; ++e) {
+    if (!experts[e]) return fail(CMOE_EINVAL, "expert %d is null", e);
+    if (experts[e]->uploaded || experts[e]->in_hier) return fail(CMOE_ESTATE, "expert %d is already uploaded or owned", e);
+    if (std::memcmp(&experts[e]->cfg, &experts[0]->cfg, sizeof(cmoe_config)) != 0)
+      return fail(CMOE_EINVAL, "expert %d has a different configuration", e);
+  }
+  const cmoe_config& c = experts[0]->cfg;
+  const int n_r = c.n_experts - c.n_shared;
+  const int has_shared = c.n_shared > 0 ? 1 : 0;
+  if (n_outer * n_r > MAX_SCORED) return fail(CMOE_EINVAL, "n_outer * N_r = %d exceeds %d scored experts", n_outer * n_r, MAX_SCORED);
+  if (outer_top_k * (has_shared + c.top_k) > MAX_DYN) return fail(CMOE_EINVAL, "too many slots per token");
+  if (n_outer * (has_shared + n_r) > MAX_GROUPS) return fail(CMOE_EINVAL, "too many expert groups");
+  std::unique_ptr<cmoe_hier> H(new (std::nothrow) cmoe_hier());
+  if (!H) return fail(CMOE_ENOMEM, "out of host memory");
+  try {
+    H->experts.assign(experts, experts + n_outer);
+    H->cfg = c;
+    H->n_outer = n_outer;
+    H->outer_top_k = outer_top_k;
+    const int d = c.d_model;
+    const size_t es = elem_size(c.dtype), row_bytes = (size_t)d * es;
+    pack_router_rows(H->router, c.dtype, d, n_outer * n_r);
+    for (int e = 0; e < n_outer; ++e)
+      for (int j = 0; j < n_r; ++j) {
+        const int idx = e * n_r + j, blk = idx / IL, cc = idx % IL;
+        std::memcpy(H->router.data() + ((size_t)blk * 2 * IL + cc) * row_bytes,
+                    experts[e]->rep_rows.data() + (size_t)(2 * j) * row_bytes, row_bytes);
+        std::memcpy(H->router.data() + ((size_t)blk * 2 * IL + IL + cc) * row_bytes,
+                    experts[e]->rep_rows.data() + (size_t)(2 * j + 1) * row_bytes, row_bytes);
+      }
+    H->lin_rows.assign((size_t)IL * row_bytes, 0);
+    for (int e = 0; e < n_outer; ++e)
+      for (int k = 0; k < d; ++k) store_elem(H->lin_rows.data() + ((size_t)e * d + k) * es, c.dtype, w_router[(size_t)k * n_outer + e]);
+    H->lin_off.assign(n_outer, 0.0f);
+    if (logit_offset) H->lin_off.assign(logit_offset, logit_offset + n_outer);
+    // engines
+    Engine& m = H->e_moe;
+    m = Engine{};
+    m.dtype = c.dtype;
+    m.d = d;
+    const int gpo = has_shared + n_r;
+    m.G = n_outer * gpo;
+    m.n_always = 0;
+    m.S_dyn = outer_top_k * (has_shared + c.top_k);
+    for (int e = 0; e < n_outer; ++e)
+      for (int g = 0; g < gpo; ++g) {
+        const int wp = experts[e]->moe.groups[g].width_pad;
+        m.width_pad_host[e * gpo + g] = wp;
+        m.max_width_pad = std::max(m.max_width_pad, wp);
+      }
+    m.h_per_token = (int64_t)outer_top_k * ((has_shared ? experts[0]->moe.groups[0].width_pad : 0) +
+                                            (int64_t)c.top_k * experts[0]->moe.groups[gpo - 1].width_pad);
+    RouterDev& r = m.r;
+    r.n_scored = n_outer * n_r;
+    r.n_sw_rows = 2 * IL * cdiv(n_outer * n_r, IL);
+    r.n_lin = n_outer;
+    r.n_lin_rows = IL;
+    r.top_k = c.top_k;
+    r.outer_top_k = outer_top_k;
+    r.n_r_sub = n_r;
+    r.n_always = 0;
+    r.score_abs = c.score_mode;
+    r.use_gate = 0;
+    for (int e = 0; e < n_outer; ++e) r.use_gate |= (experts[e]->has_u || experts[e]->has_b) ? 1 : 0;
+    r.groups_per_outer = gpo;
+    r.sub_has_shared = has_shared;
+    Engine& dn = H->e_dense;
+    dn = Engine{};
+    dn.dtype = c.dtype;
+    dn.d = d;
+    dn.G = n_outer;
+    dn.n_always = 0;
+    dn.S_dyn = outer_top_k;
+    for (int e = 0; e < n_outer; ++e) dn.width_pad_host[e] = experts[e]->dense.groups[0].width_pad;
+    dn.max_width_pad = dn.width_pad_host[0];
+    dn.h_per_token = (int64_t)outer_top_k * dn.width_pad_host[0];
+    dn.r = RouterDev{};
+    dn.r.n_lin = n_outer;
+    dn.r.n_lin_rows = IL;
+    dn.r.outer_top_k = outer_top_k;
+    dn.r.groups_per_outer = 1;
+    dn.r.sub_has_shared = 1;
+    for (int e = 0; e < n_outer; ++e) experts[e]->in_hier = true;
+  } catch (const std::bad_alloc&) {
+    return fail(CMOE_ENOMEM, "out of host memory");
+  }
+  *out = H.release();
+  return CMOE_OK;
+}
+
+// device buffer of a hierarchy:
+// [moe W1 of all experts][moe W2 ...][dense W1 ...][dense W2 ...][router sw rows][lin rows][moe groups][dense groups][u][b][offsets]
+struct HierOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, off, total; };
+static HierOffsets hier_offsets(const cmoe_hier* H) {
+  HierOffsets o{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off = align256(off + bytes); return r; };
+  size_t w1 = 0, w2 = 0, dw1 = 0, dw2 = 0;
+  for (auto* L : H->experts) { w1 += L->moe.w1.size(); w2 += L->moe.w2.size(); dw1 += L->dense.w1.size(); dw2 += L->dense.w2.size(); }
+  o.w1 = take(w1);
+  o.w2 = take(w2);
+  o.dw1 = take(dw1);
+  o.dw2 = take(dw2);
+  o.wr = take(H->router.size() + H->lin_rows.size());
+  o.g = take(sizeof(GroupDev) * H->e_moe.G);
+  o.dg = take(sizeof(GroupDev) * H->e_dense.G);
+  o.u = take(sizeof(float) * std::max(H->e_moe.r.n_scored, 1));
+  o.b = take(sizeof(float) * std::max(H->e_moe.r.n_scored, 1));
+  o.off = take(sizeof(float) * H->n_outer);
+  o.total = off;
+  return o;
+}
+
+size_t cmoe_hier_packed_bytes(const cmoe_hier* H) { return H ? hier_offsets(H).total : 0; }
+
+size_t cmoe_hier_workspace_bytes(const cmoe_hier* H, int64_t max_tokens) {
+  if (!H || max_tokens < 0) return 0;
+  return std::max(ws_layout(H->e_moe, max_tokens).total, ws_layout(H->e_dense, max_tokens).total);
+}
+
+int cmoe_hier_upload(cmoe_hier* H, void* dev_weights, void* hip_stream) {
+  if (!H || !dev_weights) return fail(CMOE_EINVAL, "hierarchy or device buffer is null");
+  if (((uintptr_t)dev_weights & 255) != 0) return fail(CMOE_EINVAL, "device weight buffer must be 256-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const HierOffsets o = hier_offsets(H);
+  char* base = static_cast<char*>(dev_weights);
+  const size_t es = elem_size(H->cfg.dtype);
+  std::vector<GroupDev> g_moe, g_dense;
+  std::vector<float> u, b;
+  size_t w1 = 0, w2 = 0, dw1 = 0, dw2 = 0;
+  hipError_t e = hipSuccess;
+  for (auto* L : H->experts) {
+    const int64_t row_shift = (int64_t)(w1 / ((size_t)H->cfg.d_model * es));
+    const int64_t el_shift = (int64_t)(w2 / es);
+    for (const GroupDev& gd : L->moe.groups) g_moe.push_back(GroupDev{gd.width_pad, (int32_t)(gd.w1_row0 + row_shift), gd.w2_off + el_shift});
+    const int64_t drow_shift = (int64_t)(dw1 / ((size_t)H->cfg.d_model * es));
+    const int64_t del_shift = (int64_t)(dw2 / es);
+    for (const GroupDev& gd : L->dense.groups) g_dense.push_back(GroupDev{gd.width_pad, (int32_t)(gd.w1_row0 + drow_shift), gd.w2_off + del_shift});
+    if (e == hipSuccess) e = h2d(base + o.w1 + w1, L->moe.w1.data(), L->moe.w1.size(), s);
+    if (e == hipSuccess) e = h2d(base + o.w2 + w2, L->moe.w2.data(), L->moe.w2.size(), s);
+    if (e == hipSuccess) e = h2d(base + o.dw1 + dw1, L->dense.w1.data(), L->dense.w1.size(), s);
+    if (e == hipSuccess) e = h2d(base + o.dw2 + dw2, L->dense.w2.data(), L->dense.w2.size(), s);
+    w1 += L->moe.w1.size();
+    w2 += L->moe.w2.size();
+    dw1 += L->dense.w1.size();
+    dw2 += L->dense.w2.size();
+    u.insert(u.end(), L->u.begin(), L->u.end());
+    b.insert(b.end(), L->b.begin(), L->b.end());
+  }
+  if (e == hipSuccess) e = h2d(base + o.wr, H->router.data(), H->router.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.wr + H->router.size(), H->lin_rows.data(), H->lin_rows.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.g, g_moe.data(), sizeof(GroupDev) * g_moe.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.dg, g_dense.data(), sizeof(GroupDev) * g_dense.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.u, u.data(), sizeof(float) * u.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.b, b.data(), sizeof(float) * b.size(), s);
+  if (e == hipSuccess) e = h2d(base + o.off, H->lin_off.data(), sizeof(float) * H->lin_off.size(), s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail_hip(e, "uploading packed weights");
+  Engine& m = H->e_moe;
+  m.w1 = base + o.w1;
+  m.w2 = base + o.w2;
+  m.wr = base + o.wr;
+  m.groups = reinterpret_cast<const GroupDev*>(base + o.g);
+  m.gate_u = m.r.use_gate ? reinterpret_cast<const float*>(base + o.u) : nullptr;
+  m.gate_b = m.r.use_gate ? reinterpret_cast<const float*>(base + o.b) : nullptr;
+  m.lin_off = reinterpret_cast<const float*>(base + o.off);
+  Engine& dn = H->e_dense;
+  dn.w1 = base + o.dw1;
+  dn.w2 = base + o.dw2;
+  dn.wr = base + o.wr + H->router.size();      // the linear rows only
+  dn.groups = reinterpret_cast<const GroupDev*>(base + o.dg);
+  dn.lin_off = m.lin_off;
+  H->uploaded = true;
+  return CMOE_OK;
+}
+
+int cmoe_hier_forward(cmoe_hier* H, const void* x_dev, int64_t T, void* y_dev, int32_t* outer_idx_dev,
+                      int32_t* sub_idx_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!H) return fail(CMOE_EINVAL, "hierarchy is null");
+  if (!H->uploaded) return fail(CMOE_ESTATE, "cmoe_hier_upload has not been called");
+  return run_engine(H->e_moe, x_dev, T, y_dev, sub_idx_dev, outer_idx_dev, nullptr, nullptr, workspace_dev,
+                    workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int cmoe_hier_dense_forward(cmoe_hier* H, const void* x_dev, int64_t T, void* y_dev, void* workspace_dev,
+                            size_t workspace_bytes, void* hip_stream) {
+  if (!H) return fail(CMOE_EINVAL, "hierarchy is null");
+  if (!H->uploaded) return fail(CMOE_ESTATE, "cmoe_hier_upload has not been called");
+  return run_engine(H->e_dense, x_dev, T, y_dev, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes,
+                    static_cast<hipStream_t>(hip_stream));
+}
+
+void cmoe_hier_destroy(cmoe_hier* H) {
+  if (!H) return;
+  for (auto* L : H->experts) L->in_hier = false;
+  delete H;
+}
+
+const char* cmoe_last_error(void) { return g_err.c_str(); }
+const char* cmoe_version(void) { return "cmoe 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,118 @@
+// Internal declarations shared by the host side (packing, C ABI) and the HIP kernels of libcmoe.
+// Not part of the public interface.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace cmoe {
+
+// ---- packing constants ---------------------------------------------------------------------
+// Gate and up rows of one expert are interleaved in blocks of IL neurons (IL gate rows, then the
+// IL up rows of the same neurons) so that a 32x32 MFMA tile of gate pre-activations and the tile
+// of up pre-activations of the same (token, neuron) pairs land in the same lanes.
+constexpr int IL = 32;
+// Expert widths are padded with zero neurons to a multiple of WPAD (zero gate/up rows give h = 0,
+// zero down columns multiply it: the padded neurons contribute exactly nothing).
+constexpr int WPAD = 32;
+constexpr int MAX_TOPK = 8;        // N_k, and outer_top_k
+constexpr int MAX_DYN = 24;        // routed slots per token (hierarchy: outer_top_k * (1 + N_k))
+constexpr int MAX_SCORED = 64;     // routed experts scored by one router (one lane per expert)
+constexpr int MAX_GROUPS = 128;    // expert groups of one engine
+constexpr int TOK_TILE = 64;       // tokens per router / permute tile
+
+__host__ __device__ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+static inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+__host__ __device__ static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// One expert group as the device kernels see it.
+struct GroupDev {
+  int32_t width_pad;    // neurons incl. zero padding (multiple of WPAD)
+  int32_t w1_row0;      // first packed (interleaved gate/up) row of the group in W1
+  int64_t w2_off;       // element offset of the group's down matrix [d][width_pad] in W2
+};
+
+// What the router kernel scores and selects.  Rows of the router matrix Wr [n_sw_rows + n_lin_rows][d]:
+//   SwiGLU blocks of 2*IL rows (IL gate rows, IL up rows) scoring IL routed experts each (Eq. 8),
+//   then n_lin_rows rows of plain linear logits (outer router of the hierarchical case).
+struct RouterDev {
+  int32_t n_scored;        // routed experts scored (flat: N_r; hierarchy: n_outer * N_r)
+  int32_t n_sw_rows;       // 2 * IL * ceil(n_scored / IL)
+  int32_t n_lin;           // linear logits in use (n_outer); 0 for a flat layer
+  int32_t n_lin_rows;      // padded row count (0 or IL)
+  int32_t top_k;           // N_k (0: the dense form of a hierarchy, outer routing only)
+  int32_t outer_top_k;     // 0 for a flat layer
+  int32_t n_r_sub;         // routed experts per outer expert (flat: N_r)
+  int32_t n_always;        // always-on groups in front
+  int32_t score_abs;       // rank by |s|
+  int32_t use_gate;        // evaluate softmax / u / b (Eq. 9); 0 = binary gate of Eq. 4
+  int32_t groups_per_outer;   // hierarchy: sub_has_shared + N_r
+  int32_t sub_has_shared;     // hierarchy: each outer expert starts with a shared group
+};
+
+// Workspace carve-up for a batch of T tokens (byte offsets, 256-aligned).
+struct WsLayout {
+  size_t sel_group, sel_weight;      // [T][S_dyn] int32 / float   (router -> permute)
+  size_t tile_counts;                // [n_tok_tiles][G] int32
+  size_t seg_off, counts;            // [G+1] / [G] int32
+  size_t work1, work2;               // [G+1] int32: prefix of work items of the two grouped GEMMs
+  size_t h_off;                      // [G+1] int64: element offset of each group's rows in H
+  size_t slot2tok;                   // [n_slots] int32
+  size_t tok2slot, slot_w;           // [T][S_all] int32 / float
+  size_t scores;                     // [T][n_scored + n_lin] float
+  size_t h;                          // hidden activations, ragged: rows of group g are width_pad(g) wide
+  size_t y_slots;                    // [n_slots][d]; unused when S_all == 1 (written straight to y)
+  size_t total;
+  int64_t n_slots;
+  int n_tok_tiles;
+};
+
+// A grouped SwiGLU problem on the device: router (optional) -> permute -> experts -> combine.
+struct Engine {
+  int dtype = 1;
+  int d = 0;
+  int G = 0;                 // groups
+  int n_always = 0;          // leading groups every token visits (identity segments)
+  int S_dyn = 0;             // routed slots per token
+  int64_t h_per_token = 0;   // upper bound of hidden elements per token (sum of its groups' width_pad)
+  int max_width_pad = 0;
+  int width_pad_host[MAX_GROUPS] = {0};   // host copy of the groups' padded widths
+  RouterDev r{};
+  // device pointers (inside the caller's weight buffer)
+  const void* w1 = nullptr;        // [rows][d] interleaved gate/up rows of all groups
+  const void* w2 = nullptr;        // per group [d][width_pad]
+  const void* wr = nullptr;        // router rows
+  const GroupDev* groups = nullptr;
+  const float* gate_u = nullptr;   // [n_scored] or null
+  const float* gate_b = nullptr;   // [n_scored] or null
+  const float* lin_off = nullptr;  // [n_lin] or null
+  int S_all() const { return n_always + S_dyn; }
+};
+
+size_t elem_size(int dtype);
+WsLayout ws_layout(const Engine& e, int64_t T);
+
+// Kernel launchers (defined in the .hip files).  All enqueue on `s` and return the launch status.
+hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
+                         int32_t* topk_out, int32_t* outer_out, float* scores_out, hipStream_t s);
+hipError_t launch_permute(const Engine& e, int64_t T, char* ws, const WsLayout& L, int32_t* counts_out,
+                          hipStream_t s);
+hipError_t launch_experts(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
+                          hipStream_t s);
+hipError_t launch_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
+
+// Tile sizes of the two grouped GEMMs (the permute kernel builds their work lists from them):
+// which = 1: rows of a gate/up tile, 2: rows of a down tile, 3: packed gate/up rows (columns of the
+// product) of a gate/up tile, 4: columns of a down tile.
+int gemm_tile(int dtype, int which);
+bool use_simt_experts(int dtype);
+int bf16_gemm_tile(int which);
+int simt_gemm_tile(int which);
+hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
+                               hipStream_t s);
+hipError_t launch_experts_simt(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
+                               hipStream_t s);
+// Upper bound of work items of grouped GEMM `which` (1: gate/up, 2: down) for T tokens.
+int64_t gemm_work_bound(const Engine& e, int64_t T, int which);
+
+}  // namespace cmoe

@@ -1,0 +1,72 @@
+// Small device helpers: bf16 conversion, wave reductions, the wave-level top-k.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cmoe {
+
+typedef uint16_t bf16_t;   // storage type of a bf16 element (bit pattern)
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// SiLU / Swish with beta = 1 (Eq. 3): z * sigmoid(z), evaluated in fp32.
+__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Monotone map float -> uint32 (larger float <=> larger integer; -0 < +0).
+__device__ __forceinline__ uint32_t ordered_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Wave arg-max: every lane passes (key, active); returns the lane index holding the largest key
+// among active lanes, ties to the lowest lane; -1 when no lane is active.  All 64 lanes must call.
+__device__ __forceinline__ int wave_argmax(float key, bool active) {
+  const int lane = threadIdx.x & 63;
+  uint32_t hi = active ? ordered_key(key) : 0u;
+  uint32_t lo = active ? (uint32_t)(64 - lane) : 0u;     // larger = lower lane; 0 = inactive
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    uint32_t ohi = __shfl_xor(hi, o, 64);
+    uint32_t olo = __shfl_xor(lo, o, 64);
+    bool take = (ohi > hi) || (ohi == hi && olo > lo);
+    hi = take ? ohi : hi;
+    lo = take ? olo : lo;
+  }
+  return lo == 0u ? -1 : 64 - (int)lo;
+}
+
+}  // namespace cmoe

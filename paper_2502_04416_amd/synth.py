@@ -82,12 +82,14 @@ def scaled(cfg: LayerConfig, **kw) -> LayerConfig:
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
-    """fp32 array -> nearest bf16-representable fp32 array (ties to even)."""
+    """fp32 array -> nearest bf16-representable fp32 array (ties to even); finite inputs only."""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    bits = a.view(np.uint32).astype(np.uint64)
-    lsb = (bits >> 16) & 1
-    bits = (bits + 0x7FFF + lsb) & 0xFFFF0000
-    return bits.astype(np.uint32).view(np.float32).reshape(a.shape)
+    bits = a.view(np.uint32)
+    out = (bits >> np.uint32(16)) & np.uint32(1)
+    out += np.uint32(0x7FFF)
+    out += bits
+    out &= np.uint32(0xFFFF0000)
+    return out.view(np.float32).reshape(a.shape)
 
 
 def _finish(a: np.ndarray, dtype: str) -> np.ndarray:

@@ -1,0 +1,207 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Small cases are compared element by element on every token; the full-size configurations compare the
+routing of every token and the outputs of a random sample of tokens (the oracle evaluates those one
+group at a time), plus size-independent properties (counts, determinism)."""
+import numpy as np
+import pytest
+
+from oracle import cmoe_oracle as O
+from paper_2502_04416_amd import synth
+from parity_utils import check_dense, check_flat, tokenwise_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2502_04416_amd import binding as b
+    b.load()
+    return b
+
+
+def _layer(binding, cfg, weights, part, **kw):
+    return binding.Layer.from_partition(cfg, *weights, part["neuron_order"], part["rep_neuron"], **kw)
+
+
+def _say(name, rep):
+    print("\n[parity] %s: %s" % (name, rep), flush=True)
+
+
+# ---------------------------------------------------------------------------------- config 0 (fp32)
+
+@pytest.fixture(scope="module")
+def cfg0():
+    cfg = synth.CONFIGS[0]
+    weights = synth.make_weights(cfg)
+    src = synth.make_token_source(cfg)
+    part = O.build(weights[0], weights[1], src.calibration(), cfg.n_experts, cfg.n_shared, cfg.k_act)
+    return cfg, weights, src, part
+
+
+def test_cfg0_fp32_end_to_end(binding, cfg0):
+    cfg, weights, src, part = cfg0
+    x = src.eval_batch(0)
+    layer = _layer(binding, cfg, weights, part)
+    out = layer.forward(x)
+    rep = check_flat(cfg, weights, part, x, out)
+    _say("cfg0 T=64", rep)
+    rep_d = check_dense(cfg, weights, x, layer.dense_forward(x))
+    _say("cfg0 dense", rep_d)
+    # run-to-run determinism: bit-identical outputs
+    out2 = layer.forward(x)
+    assert np.array_equal(out["y"], out2["y"]) and np.array_equal(out["topk"], out2["topk"])
+    layer.close()
+
+
+@pytest.mark.parametrize("T", [1, 3, 65, 200])
+def test_cfg0_ragged_batches(binding, cfg0, T):
+    cfg, weights, src, part = cfg0
+    x = src.eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    _say("cfg0 T=%d" % T, check_flat(cfg, weights, part, x, layer.forward(x)))
+    layer.close()
+
+
+def test_cfg0_gate_params(binding, cfg0):
+    """Eq. 9 with non-zero u and b: softmax scores, biased selection, gate-weighted combine."""
+    cfg, weights, src, part = cfg0
+    x = src.eval_batch(0)
+    u, b = synth.make_gate_params(cfg)
+    layer = _layer(binding, cfg, weights, part)
+    layer.set_gate_params(u, b)
+    _say("cfg0 gate", check_flat(cfg, weights, part, x, layer.forward(x), u=u, b=b))
+    layer.set_gate_params(None, None)
+    _say("cfg0 gate reset", check_flat(cfg, weights, part, x, layer.forward(x)))
+    layer.close()
+
+
+def test_cfg0_all_experts_active_equals_dense(binding, cfg0):
+    """N_k = N_r: the MoE output equals the dense FFN (Eq. 5 with no deactivated expert)."""
+    cfg, weights, src, part = cfg0
+    full = synth.scaled(cfg, top_k=cfg.n_routed)
+    x = src.eval_batch(0)
+    layer = _layer(binding, full, weights, part)
+    out = layer.forward(x)
+    dense_ref = O.dense_ffn(x, *weights)
+    assert tokenwise_rel_err(out["y"], dense_ref).max() <= 1e-5
+    assert tokenwise_rel_err(layer.dense_forward(x), dense_ref).max() <= 1e-5
+    assert (out["counts"] == x.shape[0]).all()
+    layer.close()
+
+
+def test_cfg0_abs_score_mode(binding, cfg0):
+    cfg, weights, src, part = cfg0
+    x = src.eval_batch(0)
+    layer = _layer(binding, cfg, weights, part, score_mode=1)
+    _say("cfg0 |s|", check_flat(cfg, weights, part, x, layer.forward(x), abs_score=True))
+    layer.close()
+
+
+def test_identical_tokens_all_go_to_one_expert(binding, cfg0):
+    """Degenerate routing: every token identical, so one routed expert receives the whole batch and the
+    others none."""
+    cfg, weights, src, part = cfg0
+    x = np.repeat(src.eval_batch(0, n=1), 130, axis=0)
+    layer = _layer(binding, cfg, weights, part)
+    out = layer.forward(x)
+    rep = check_flat(cfg, weights, part, x, out)
+    assert rep["union"] == 1 and out["counts"].max() == 130
+    layer.close()
+
+
+def test_no_shared_expert(binding):
+    cfg = synth.scaled(synth.CONFIGS[0], n_shared=0, top_k=2)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=77)
+    layer = _layer(binding, cfg, weights, part)
+    _say("N_s=0", check_flat(cfg, weights, part, x, layer.forward(x)))
+    layer.close()
+
+
+def test_empty_batch_and_errors(binding, cfg0):
+    import torch
+    cfg, weights, src, part = cfg0
+    layer = _layer(binding, cfg, weights, part)
+    x = torch.zeros((0, cfg.d_model), device="cuda")
+    y = torch.zeros((0, cfg.d_model), device="cuda")
+    layer.forward_device(x, y)                     # T = 0 is a no-op
+    ws = layer._ensure_ws(8)
+    x8 = torch.zeros((8, cfg.d_model), device="cuda")
+    y8 = torch.zeros((8, cfg.d_model), device="cuda")
+    with pytest.raises(binding.CmoeError, match="workspace too small"):
+        binding.cmoe_forward(layer.h, x8.data_ptr(), 8, y8.data_ptr(), None, None, None, ws.data_ptr(), 16)
+    with pytest.raises(binding.CmoeError, match="null"):
+        binding.cmoe_forward(layer.h, None, 8, y8.data_ptr(), None, None, None, ws.data_ptr(), ws.numel())
+    layer.close()
+
+
+# ---------------------------------------------------------------------------------- reduced bf16 cases
+
+SMALL_BF16 = [
+    # (name, d, d_ff, N, N_s, N_k, T)   widths that miss the 32-neuron tile, ragged T, several row tiles
+    ("m172", 512, 2752, 16, 1, 3, 777),
+    ("m44", 1024, 1408, 32, 2, 6, 1500),
+    ("m448", 512, 3584, 8, 2, 2, 300),
+    ("decode1", 512, 2752, 16, 1, 3, 1),
+    ("decode16", 512, 2752, 16, 1, 3, 16),
+]
+
+
+@pytest.mark.parametrize("name,d,d_ff,N,N_s,N_k,T", SMALL_BF16)
+def test_small_bf16(binding, name, d, d_ff, N, N_s, N_k, T):
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=d, d_ff=d_ff, n_experts=N, n_shared=N_s, top_k=N_k, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    out = layer.forward(x)
+    _say("small %s" % name, check_flat(cfg, weights, part, x, out))
+    _say("small %s dense" % name, check_dense(cfg, weights, x, layer.dense_forward(x)))
+    out2 = layer.forward(x)
+    assert np.array_equal(out["y"], out2["y"])
+    layer.close()
+
+
+def test_small_bf16_gate_params(binding):
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=333)
+    u, b = synth.make_gate_params(cfg)
+    layer = _layer(binding, cfg, weights, part)
+    layer.set_gate_params(u, b)
+    _say("small gate", check_flat(cfg, weights, part, x, layer.forward(x), u=u, b=b))
+    layer.close()
+
+
+# ---------------------------------------------------------------------------------- full-size configs
+
+def _full(binding, ci, batches, n_sample=48):
+    cfg = synth.CONFIGS[ci]
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    src = synth.make_token_source(cfg)
+    layer = _layer(binding, cfg, weights, part)
+    rng = np.random.Generator(np.random.PCG64(99 + ci))
+    for bi in batches:
+        x = src.eval_batch(bi)
+        T = x.shape[0]
+        sample = np.sort(rng.choice(T, size=min(T, n_sample), replace=False))
+        out = layer.forward(x)
+        _say("cfg%d T=%d" % (ci, T), check_flat(cfg, weights, part, x, out, sample=sample))
+        _say("cfg%d T=%d dense" % (ci, T), check_dense(cfg, weights, x, layer.dense_forward(x), sample=sample[:16]))
+    layer.close()
+
+
+def test_cfg1_full(binding):
+    _full(binding, 1, [0, 1, 2])
+
+
+def test_cfg2_full(binding):
+    _full(binding, 2, [0, 1], n_sample=32)
+
+
+def test_cfg3_full(binding):
+    _full(binding, 3, [0, 1, 2], n_sample=32)

@@ -1,0 +1,98 @@
+"""Host-side checks of libcmoe that need no GPU: the library loads, exports every symbol the public
+header declares, and its argument checks turn bad input into error codes (never a crash)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_04416_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "cmoe.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(cmoe_[a-z_]+)\s*\(", header))
+    assert len(declared) >= 19
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert "gfx950" in binding.cmoe_version()
+
+
+def _tiny():
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=16, d_ff=32, n_experts=4, n_shared=1, top_k=1)
+    return cfg, synth.make_weights(cfg), synth.trivial_partition(cfg)
+
+
+def test_build_from_partition_roundtrip(lib):
+    cfg, w, p = _tiny()
+    h = binding.cmoe_build_from_partition(binding.make_config(cfg), *w, p["neuron_order"], p["rep_neuron"])
+    e = binding.cmoe_export_partition(h, cfg.d_ff, cfg.n_routed)
+    assert np.array_equal(e["neuron_order"], p["neuron_order"]) and np.array_equal(e["rep_neuron"], p["rep_neuron"])
+    assert binding.cmoe_packed_bytes(h) > 3 * cfg.d_model * cfg.d_ff * 4
+    assert binding.cmoe_workspace_bytes(h, 128) > binding.cmoe_workspace_bytes(h, 1) > 0
+    binding.cmoe_destroy(h)
+
+
+@pytest.mark.parametrize("field,value,msg", [
+    ("n_experts", 5, "multiple"),            # d_ff % N != 0
+    ("n_shared", 4, "n_shared"),             # N_s >= N
+    ("top_k", 4, "top_k"),                   # N_k > N_r
+    ("top_k", 0, "top_k"),
+    ("dtype", "bad", "dtype"),
+])
+def test_bad_config_is_rejected(lib, field, value, msg):
+    cfg, w, p = _tiny()
+    c = binding.make_config(cfg)
+    if field == "dtype":
+        c.dtype = 7
+    else:
+        setattr(c, field, value)
+    with pytest.raises(binding.CmoeError, match=msg):
+        binding.cmoe_build_from_partition(c, *w, p["neuron_order"], p["rep_neuron"])
+
+
+def test_bad_partition_is_rejected(lib):
+    cfg, w, p = _tiny()
+    order = p["neuron_order"].copy()
+    order[0] = order[1]
+    with pytest.raises(binding.CmoeError, match="permutation"):
+        binding.cmoe_build_from_partition(binding.make_config(cfg), *w, order, p["rep_neuron"])
+    reps = p["rep_neuron"].copy()
+    reps[0] = cfg.d_ff
+    with pytest.raises(binding.CmoeError, match="rep_neuron"):
+        binding.cmoe_build_from_partition(binding.make_config(cfg), *w, p["neuron_order"], reps)
+
+
+def test_forward_before_upload_is_an_error(lib):
+    cfg, w, p = _tiny()
+    h = binding.cmoe_build_from_partition(binding.make_config(cfg), *w, p["neuron_order"], p["rep_neuron"])
+    with pytest.raises(binding.CmoeError, match="upload"):
+        binding.cmoe_forward(h, 1, 1, 1, None, None, None, 1, 1)
+    binding.cmoe_destroy(h)
+
+
+def test_null_handles(lib):
+    assert binding.cmoe_packed_bytes(None) == 0
+    assert binding.cmoe_workspace_bytes(None, 4) == 0
+    with pytest.raises(binding.CmoeError):
+        binding.cmoe_set_gate_params(None, None, None)
+    binding.cmoe_destroy(None)
+
+
+def test_generator_rounding_matches_torch():
+    """The input generator's bf16 rounding against torch's conversion (a library routine)."""
+    import torch
+    x = (np.random.default_rng(0).standard_normal(100000) * 3).astype(np.float32)
+    assert np.array_equal(synth.round_to_bf16(x), torch.from_numpy(x).bfloat16().float().numpy())
