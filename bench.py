@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Bench of the MoE-FFN forward (router -> top-k -> permute -> shared + routed SwiGLU experts -> combine)
+on one MI355X, through the C ABI of libcmoe.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--batch 2048]
+
+A step is one pass of the whole hot path over one batch of synthetic tokens already resident in HBM.
+The headline workload is the LLaMA-2-7B-shaped layer of config 1 (16 experts of 688 neurons, 1 shared +
+top-3 of 15 routed) on its 2048-token prefill batch.  One JSON line is printed with tokens/s, the
+speedup over the dense-FFN kernels of the same library, per-stage times, the roofline of the dominant
+kernel (gate/up grouped contraction, bf16 MFMA), decode-batch results against the HBM roofline, and
+the CPU oracle timed on the host cores (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TF = 2500.0     # dense bf16 MFMA
+FP32_VALU_PEAK_TF = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--batch", type=int, default=None, help="token count (default: the config's largest eval batch)")
+    ap.add_argument("--construct", choices=["library", "arbitrary"], default="library",
+                    help="partition from cmoe_build on the calibration set, or a seeded arbitrary one")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-batch measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--layer-copies", type=int, default=8, help="device copies of the layer cycled at decode")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported. DESIGN.md says how the path would shard." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2502_04416_amd import binding, synth
+    binding.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device visible", file=sys.stderr)
+        sys.exit(2)
+    cfg = synth.CONFIGS[args.config]
+    if cfg.n_outer:
+        print("bench.py: use --config 0..3 (the hierarchical case is covered by the tests)", file=sys.stderr)
+        sys.exit(2)
+    T = args.batch if args.batch else max(cfg.eval_batches)
+    dev = torch.device("cuda:0")
+    t_setup = time.time()
+    weights = synth.make_weights(cfg)
+    src = synth.make_token_source(cfg)
+    construct_s = None
+    if args.construct == "library":
+        t0 = time.time()
+        try:
+            layer = binding.Layer.build(cfg, *weights, src.calibration())
+            construct_s = time.time() - t0
+        except binding.CmoeError as e:
+            print("bench.py: cmoe_build unavailable (%s); using an arbitrary partition" % e, file=sys.stderr)
+            args.construct = "arbitrary"
+    if args.construct == "arbitrary":
+        part = synth.trivial_partition(cfg)
+        layer = binding.Layer.from_partition(cfg, *weights, part["neuron_order"], part["rep_neuron"])
+    part = layer.export_partition()
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    es = 2 if cfg.dtype == "bf16" else 4
+    bi = cfg.eval_batches.index(T) if T in cfg.eval_batches else 0
+    x_host = src.eval_batch(bi, n=T)
+    x = torch.from_numpy(x_host).to(dev, tdt)
+    y = torch.empty_like(x)
+    topk = torch.empty((T, cfg.top_k), dtype=torch.int32, device=dev)
+    counts = torch.empty((cfg.n_routed,), dtype=torch.int32, device=dev)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    # ---- headline: K steps of the MoE forward, bracketed by synchronize ----
+    ms_moe = timed(lambda: layer.forward_device(x, y, topk, None, counts), args.steps, args.warmup)
+    ms_dense = timed(lambda: layer.dense_forward_device(x, y), args.steps, args.warmup)
+    layer.forward_device(x, y, topk, None, counts)
+    torch.cuda.synchronize()
+    cnt = counts.cpu().numpy()
+
+    # ---- per-stage times from HIP events recorded inside the library on the launch stream ----
+    def stages(dense, n):
+        acc = np.zeros(5)
+        for _ in range(3):
+            layer.forward_timed(x, y, dense)
+        for _ in range(n):
+            acc += layer.forward_timed(x, y, dense)
+        return acc / n
+    n_prof = max(5, min(args.steps, 30))
+    st_moe = stages(False, n_prof)
+    st_dense = stages(True, n_prof)
+
+    d, m = cfg.d_model, cfg.m
+    act = cfg.n_shared + cfg.top_k
+    flops_gate_up = 4.0 * d * m * act * T                     # two contractions of 2*d*m flops per active neuron-row
+    flops_total = T * (6.0 * d * m * act + 4.0 * d * cfg.n_routed)
+    flops_dense = T * 6.0 * d * cfg.d_ff
+    union = int((cnt > 0).sum())
+    w_bytes_touched = es * (3.0 * d * m * (cfg.n_shared + union) + 2.0 * d * cfg.n_routed)
+    prefill = T >= 256
+    if prefill:
+        gu_ms = float(st_moe[2])
+        roofline = {"kernel": "grouped_gemm_bf16<gate_up>", "bound": "mfma",
+                    "achieved": flops_gate_up / (gu_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s",
+                    "traffic": None}
+    else:
+        gu_ms = float(st_moe[2])
+        b = es * 2.0 * d * m * (cfg.n_shared + union)
+        roofline = {"kernel": "gate_up", "bound": "hbm", "achieved": b / (gu_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "traffic": None}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["avg_launch_ms"] = gu_ms
+    if cfg.dtype != "bf16":
+        roofline.update({"bound": "alu", "peak": FP32_VALU_PEAK_TF, "frac": roofline["achieved"] / FP32_VALU_PEAK_TF})
+
+    out = {
+        "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
+        "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_moe, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "cfg%d %s: d=%d d_ff=%d, %d experts of %d neurons, %d shared + top-%d of %d routed, T=%d tokens"
+                   % (cfg.cfg, cfg.name, d, cfg.d_ff, cfg.n_experts, m, cfg.n_shared, cfg.top_k, cfg.n_routed, T),
+                   "partition": args.construct, "k_act": cfg.k_act, "sigma_o": synth.SIGMA_O},
+        "dense_ms_per_step": ms_dense, "dense_tokens_per_s": T / (ms_dense * 1e-3),
+        "speedup_vs_dense": ms_dense / ms_moe,
+        "whole_path_tflops": flops_total / (ms_moe * 1e-3) / 1e12,
+        "dense_tflops": flops_dense / (ms_dense * 1e-3) / 1e12,
+        "stage_ms": dict(zip(binding.STAGES, [float(v) for v in st_moe])),
+        "dense_stage_ms": dict(zip(binding.STAGES, [float(v) for v in st_dense])),
+        "expert_counts": cnt.tolist(), "experts_touched": union,
+        "weight_bytes_touched": w_bytes_touched,
+        "roofline": roofline,
+        "construct_s": construct_s,
+    }
+
+    # ---- decode batches: cycle over several device copies of the layer so weights come from HBM ----
+    if not args.no_decode and cfg.dtype == "bf16":
+        copies = [layer]
+        order, reps = part["neuron_order"], part["rep_neuron"]
+        for _ in range(max(0, args.layer_copies - 1)):
+            copies.append(binding.Layer.from_partition(cfg, *weights, order, reps))
+        dec = []
+        for Td in [b for b in cfg.eval_batches if b <= 64] or [1]:
+            xs = [torch.from_numpy(src.draw(9000 + 100 * Td + i, Td)).to(dev, tdt)
+                  for i in range(len(copies))]
+            yd = torch.empty_like(xs[0])
+            cd = torch.empty((cfg.n_routed,), dtype=torch.int32, device=dev)
+            state = {"i": 0}
+
+            def step_moe():
+                i = state["i"] % len(copies)
+                state["i"] += 1
+                copies[i].forward_device(xs[i], yd, None, None, cd)
+
+            def step_dense():
+                i = state["i"] % len(copies)
+                state["i"] += 1
+                copies[i].dense_forward_device(xs[i], yd)
+            steps_d = max(args.steps, 64)
+            ms_m = timed(step_moe, steps_d, 16)
+            ms_dn = timed(step_dense, steps_d, 16)
+            # stage times and touched bytes, averaged over the copies
+            st = np.zeros(5)
+            std_ = np.zeros(5)
+            touched = 0.0
+            for i, c in enumerate(copies):
+                c.forward_timed(xs[i], yd, False)
+            for rep_i in range(2):
+                for i, c in enumerate(copies):
+                    st += c.forward_timed(xs[i], yd, False)
+                    std_ += c.forward_timed(xs[i], yd, True)
+                    if rep_i == 0:
+                        c.forward_device(xs[i], yd, None, None, cd)
+                        torch.cuda.synchronize()
+                        touched += float((cd.cpu().numpy() > 0).sum())
+            st /= 2 * len(copies)
+            std_ /= 2 * len(copies)
+            u_avg = touched / len(copies)
+            bytes_moe = es * (3.0 * d * m * (cfg.n_shared + u_avg) + 2.0 * d * cfg.n_routed)
+            bytes_gu = es * 2.0 * d * m * (cfg.n_shared + u_avg)
+            bytes_dense = es * 3.0 * d * cfg.d_ff
+            dec.append({
+                "T": Td, "ms_per_step": ms_m, "tokens_per_s": Td / (ms_m * 1e-3), "dense_ms_per_step": ms_dn,
+                "speedup_vs_dense": ms_dn / ms_m, "experts_touched_avg": u_avg,
+                "weight_bytes_touched": bytes_moe,
+                "hbm_frac_whole_path": bytes_moe / (ms_m * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "dense_hbm_frac": bytes_dense / (ms_dn * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "stage_ms": dict(zip(binding.STAGES, [float(v) for v in st])),
+                "dense_stage_ms": dict(zip(binding.STAGES, [float(v) for v in std_])),
+                "roofline": {"kernel": "gate_up", "bound": "hbm", "achieved": bytes_gu / (st[2] * 1e-3) / 1e9,
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_gu / (st[2] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "traffic": None},
+            })
+        out["decode"] = dec
+        out["decode_layer_copies"] = len(copies)
+
+    # ---- CPU oracle on the host cores (reported baseline) ----
+    if not args.no_cpu:
+        from oracle import cmoe_oracle as O
+        n_cpu = min(T, 2048)
+        xs_cpu = x_host[:n_cpu]
+        t0 = time.perf_counter()
+        O.moe_forward(xs_cpu, *weights, part["neuron_order"], part["rep_neuron"], cfg.n_experts, cfg.n_shared, cfg.top_k)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        out["cpu_baseline"] = {"value": n_cpu / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": "%d tokens of the same batch, fp64 numpy oracle, %.1f s" % (n_cpu, dt)}
+    out["setup_s"] = time.time() - t_setup
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

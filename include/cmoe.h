@@ -125,6 +125,14 @@ int cmoe_forward(cmoe_layer* layer, const void* x_dev, int64_t T, void* y_dev,
 int cmoe_dense_forward(cmoe_layer* layer, const void* x_dev, int64_t T, void* y_dev,
                        void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* Measurement aid: cmoe_forward (dense = 0) or cmoe_dense_forward (dense = 1) with HIP events recorded
+ * on the stream between the stages; waits for the last event and writes the elapsed milliseconds of
+ * the five stages to stage_ms[5] (host): router scoring + top-k (Eq. 8/9), permutation, gate/up
+ * contraction with SwiGLU (Eq. 3 line 1), down contraction (Eq. 3 line 2), gate-weighted combine
+ * (Eq. 4).  Stages a path does not run report ~0.  Synchronises; not for production use. */
+int cmoe_forward_timed(cmoe_layer* layer, int dense, const void* x_dev, int64_t T, void* y_dev,
+                       void* workspace_dev, size_t workspace_bytes, void* hip_stream, float* stage_ms);
+
 void cmoe_destroy(cmoe_layer* layer);
 
 /* ---- hierarchical case (Sec. 4.4, Eq. 10) ------------------------------------------------ */
@@ -152,6 +160,9 @@ int cmoe_hier_forward(cmoe_hier* h, const void* x_dev, int64_t T, void* y_dev,
  * hierarchical case. */
 int cmoe_hier_dense_forward(cmoe_hier* h, const void* x_dev, int64_t T, void* y_dev,
                             void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+/* Measurement aid, as cmoe_forward_timed (Eq. 10 path when dense = 0). */
+int cmoe_hier_forward_timed(cmoe_hier* h, int dense, const void* x_dev, int64_t T, void* y_dev,
+                            void* workspace_dev, size_t workspace_bytes, void* hip_stream, float* stage_ms);
 void cmoe_hier_destroy(cmoe_hier* h);
 
 /* ---- misc -------------------------------------------------------------------------------- */

@@ -37,7 +37,7 @@ EXPORTS = [
     "cmoe_packed_bytes", "cmoe_workspace_bytes", "cmoe_upload", "cmoe_forward", "cmoe_dense_forward",
     "cmoe_destroy", "cmoe_hier_create", "cmoe_hier_packed_bytes", "cmoe_hier_workspace_bytes",
     "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
-    "cmoe_last_error", "cmoe_version",
+    "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
 ]
 
 
@@ -63,6 +63,8 @@ def load():
     lib.cmoe_upload.argtypes = [vp, vp, vp]
     lib.cmoe_forward.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.cmoe_dense_forward.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+    lib.cmoe_forward_timed.argtypes = [vp, C.c_int, vp, i64, vp, vp, sz, vp, f32p]
+    lib.cmoe_hier_forward_timed.argtypes = [vp, C.c_int, vp, i64, vp, vp, sz, vp, f32p]
     lib.cmoe_destroy.argtypes = [vp]
     lib.cmoe_destroy.restype = None
     lib.cmoe_hier_create.argtypes = [C.POINTER(vp), C.c_int32, C.c_int32, f32p, f32p, C.POINTER(vp)]
@@ -161,6 +163,24 @@ def cmoe_forward(layer: int, x_ptr: int, T: int, y_ptr: int, topk_ptr, scores_pt
 
 def cmoe_dense_forward(layer: int, x_ptr: int, T: int, y_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(load().cmoe_dense_forward(layer, x_ptr, T, y_ptr, ws_ptr, ws_bytes, stream), "cmoe_dense_forward")
+
+
+STAGES = ("router", "permute", "gate_up", "down", "combine")
+
+
+def cmoe_forward_timed(layer: int, dense: int, x_ptr: int, T: int, y_ptr: int, ws_ptr: int, ws_bytes: int,
+                       stream: int = 0) -> np.ndarray:
+    ms = np.zeros(5, dtype=np.float32)
+    _check(load().cmoe_forward_timed(layer, dense, x_ptr, T, y_ptr, ws_ptr, ws_bytes, stream, _fp(ms)), "cmoe_forward_timed")
+    return ms
+
+
+def cmoe_hier_forward_timed(h: int, dense: int, x_ptr: int, T: int, y_ptr: int, ws_ptr: int, ws_bytes: int,
+                            stream: int = 0) -> np.ndarray:
+    ms = np.zeros(5, dtype=np.float32)
+    _check(load().cmoe_hier_forward_timed(h, dense, x_ptr, T, y_ptr, ws_ptr, ws_bytes, stream, _fp(ms)),
+           "cmoe_hier_forward_timed")
+    return ms
 
 
 def cmoe_destroy(layer: int) -> None:
@@ -296,6 +316,14 @@ class Layer(_DeviceMixin):
         ws = self._ensure_ws(T)
         cmoe_dense_forward(self.h, x_dev.data_ptr(), T, y_dev.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(torch))
 
+    def forward_timed(self, x_dev, y_dev, dense: bool = False) -> np.ndarray:
+        """Per-stage milliseconds of one forward (see binding.STAGES); synchronises."""
+        torch = _torch()
+        T = x_dev.shape[0]
+        ws = self._ensure_ws(T)
+        return cmoe_forward_timed(self.h, int(dense), x_dev.data_ptr(), T, y_dev.data_ptr(), ws.data_ptr(), ws.numel(),
+                                  _stream_ptr(torch))
+
     def forward(self, x) -> Dict[str, np.ndarray]:
         torch = _torch()
         xd = self._to_device(x)
@@ -362,6 +390,13 @@ class Hierarchy(_DeviceMixin):
         T = x_dev.shape[0]
         ws = self._ensure_ws(T)
         cmoe_hier_dense_forward(self.h, x_dev.data_ptr(), T, y_dev.data_ptr(), ws.data_ptr(), ws.numel(), _stream_ptr(torch))
+
+    def forward_timed(self, x_dev, y_dev, dense: bool = False) -> np.ndarray:
+        torch = _torch()
+        T = x_dev.shape[0]
+        ws = self._ensure_ws(T)
+        return cmoe_hier_forward_timed(self.h, int(dense), x_dev.data_ptr(), T, y_dev.data_ptr(), ws.data_ptr(),
+                                       ws.numel(), _stream_ptr(torch))
 
     def forward(self, x) -> Dict[str, np.ndarray]:
         torch = _torch()

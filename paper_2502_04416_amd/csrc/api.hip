@@ -109,10 +109,10 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
 }
 
 hipError_t launch_experts(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
-                          hipStream_t s) {
+                          hipStream_t s, int stage) {
   if (T == 0) return hipSuccess;
-  if (use_simt_experts(e.dtype)) return launch_experts_simt(e, x, T, ws, L, y, s);
-  return launch_experts_bf16(e, x, T, ws, L, y, s);
+  if (use_simt_experts(e.dtype)) return launch_experts_simt(e, x, T, ws, L, y, s, stage);
+  return launch_experts_bf16(e, x, T, ws, L, y, s, stage);
 }
 
 // ---------------------------------------------------------------------------------- packing
@@ -479,7 +479,8 @@ int cmoe_upload(cmoe_layer* L, void* dev_weights, void* hip_stream) {
 }
 
 static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_t* topk, int32_t* outer,
-                      float* scores, int32_t* counts, void* ws, size_t ws_bytes, hipStream_t s) {
+                      float* scores, int32_t* counts, void* ws, size_t ws_bytes, hipStream_t s,
+                      hipEvent_t* ev = nullptr) {
   if (T < 0) return fail(CMOE_EINVAL, "negative token count");
   if (T == 0) return CMOE_OK;
   if (!x || !y || !ws) return fail(CMOE_EINVAL, "x, y or workspace is null");
@@ -490,17 +491,52 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   char* w = static_cast<char*>(ws);
   const bool single = (e.G == 1 && e.n_always == 1);
   hipError_t err = hipSuccess;
+  auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
+  mark(0);
   if (!single) {
     err = launch_router(e, x, T, w, L, topk, outer, scores, s);
     if (err != hipSuccess) return fail_hip(err, "router kernel");
+  }
+  mark(1);
+  if (!single) {
     err = launch_permute(e, T, w, L, counts, s);
     if (err != hipSuccess) return fail_hip(err, "permute kernel");
   }
-  err = launch_experts(e, x, T, w, L, y, s);
-  if (err != hipSuccess) return fail_hip(err, "expert kernels");
+  mark(2);
+  err = launch_experts(e, x, T, w, L, y, s, 1);
+  if (err != hipSuccess) return fail_hip(err, "gate/up expert kernel");
+  mark(3);
+  err = launch_experts(e, x, T, w, L, y, s, 2);
+  if (err != hipSuccess) return fail_hip(err, "down expert kernel");
+  mark(4);
   err = launch_combine(e, T, w, L, y, s);
   if (err != hipSuccess) return fail_hip(err, "combine kernel");
+  mark(5);
   return CMOE_OK;
+}
+
+// Timed variant shared by the two *_forward_timed entry points: five stages bracketed by six events.
+static int run_engine_timed(const Engine& e, const void* x, int64_t T, void* y, void* ws, size_t ws_bytes,
+                            hipStream_t s, float* stage_ms) {
+  if (!stage_ms) return fail(CMOE_EINVAL, "stage_ms is null");
+  hipEvent_t ev[6];
+  for (int i = 0; i < 6; ++i) {
+    hipError_t err = hipEventCreate(&ev[i]);
+    if (err != hipSuccess) return fail_hip(err, "hipEventCreate");
+  }
+  int rc = run_engine(e, x, T, y, nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, s, ev);
+  if (rc == CMOE_OK && T > 0) {
+    hipError_t err = hipEventSynchronize(ev[5]);
+    if (err != hipSuccess) rc = fail_hip(err, "hipEventSynchronize");
+    for (int i = 0; i < 5 && rc == CMOE_OK; ++i) {
+      err = hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]);
+      if (err != hipSuccess) rc = fail_hip(err, "hipEventElapsedTime");
+    }
+  } else {
+    for (int i = 0; i < 5; ++i) stage_ms[i] = 0.0f;
+  }
+  for (int i = 0; i < 6; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
 }
 
 int cmoe_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev, int32_t* topk_idx_dev,
@@ -521,6 +557,16 @@ int cmoe_dense_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev,
   if (!L->uploaded) return fail(CMOE_ESTATE, "cmoe_upload has not been called");
   return run_engine(L->e_dense, x_dev, T, y_dev, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes,
                     static_cast<hipStream_t>(hip_stream));
+}
+
+int cmoe_forward_timed(cmoe_layer* L, int dense, const void* x_dev, int64_t T, void* y_dev, void* workspace_dev,
+                       size_t workspace_bytes, void* hip_stream, float* stage_ms) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (!L->uploaded) return fail(CMOE_ESTATE, "cmoe_upload has not been called");
+  Engine e = dense ? L->e_dense : L->e_moe;
+  if (!L->has_u) e.gate_u = nullptr;
+  if (!L->has_b) e.gate_b = nullptr;
+  return run_engine_timed(e, x_dev, T, y_dev, workspace_dev, workspace_bytes, static_cast<hipStream_t>(hip_stream), stage_ms);
 }
 
 void cmoe_destroy(cmoe_layer* L) { delete L; }
@@ -721,6 +767,14 @@ int cmoe_hier_dense_forward(cmoe_hier* H, const void* x_dev, int64_t T, void* y_
   if (!H->uploaded) return fail(CMOE_ESTATE, "cmoe_hier_upload has not been called");
   return run_engine(H->e_dense, x_dev, T, y_dev, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes,
                     static_cast<hipStream_t>(hip_stream));
+}
+
+int cmoe_hier_forward_timed(cmoe_hier* H, int dense, const void* x_dev, int64_t T, void* y_dev, void* workspace_dev,
+                            size_t workspace_bytes, void* hip_stream, float* stage_ms) {
+  if (!H) return fail(CMOE_EINVAL, "hierarchy is null");
+  if (!H->uploaded) return fail(CMOE_ESTATE, "cmoe_hier_upload has not been called");
+  return run_engine_timed(dense ? H->e_dense : H->e_moe, x_dev, T, y_dev, workspace_dev, workspace_bytes,
+                          static_cast<hipStream_t>(hip_stream), stage_ms);
 }
 
 void cmoe_hier_destroy(cmoe_hier* H) {

@@ -97,8 +97,9 @@ hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, co
                          int32_t* topk_out, int32_t* outer_out, float* scores_out, hipStream_t s);
 hipError_t launch_permute(const Engine& e, int64_t T, char* ws, const WsLayout& L, int32_t* counts_out,
                           hipStream_t s);
+// stage: 0 = gate/up GEMM then down GEMM, 1 = gate/up only, 2 = down only
 hipError_t launch_experts(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
-                          hipStream_t s);
+                          hipStream_t s, int stage = 0);
 hipError_t launch_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
 
 // Tile sizes of the two grouped GEMMs (the permute kernel builds their work lists from them):
@@ -109,9 +110,9 @@ bool use_simt_experts(int dtype);
 int bf16_gemm_tile(int which);
 int simt_gemm_tile(int which);
 hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
-                               hipStream_t s);
+                               hipStream_t s, int stage);
 hipError_t launch_experts_simt(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
-                               hipStream_t s);
+                               hipStream_t s, int stage);
 // Upper bound of work items of grouped GEMM `which` (1: gate/up, 2: down) for T tokens.
 int64_t gemm_work_bound(const Engine& e, int64_t T, int which);
 

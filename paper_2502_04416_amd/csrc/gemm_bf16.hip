@@ -223,15 +223,12 @@ static int env_int(const char* name, int dflt) {
   const char* v = std::getenv(name);
   return v ? std::atoi(v) : dflt;
 }
+// The environment is read at every call (a getenv is nothing next to a kernel launch) so that a tuning
+// script can switch tile shapes inside one process.
 static int cfg_index(int which) {
-  static int c1 = -1, c2 = -1;
-  if (c1 < 0) {
-    c1 = env_int("CMOE_GEMM1_CFG", 0);
-    c2 = env_int("CMOE_GEMM2_CFG", 0);
-    if (c1 < 0 || c1 >= kNumCfgs) c1 = 0;
-    if (c2 < 0 || c2 >= kNumCfgs) c2 = 0;
-  }
-  return which == 1 ? c1 : c2;
+  int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", 0);
+  if (c < 0 || c >= kNumCfgs) c = 0;
+  return c;
 }
 
 // which = 1: BM of gate/up, 2: BM of down, 3: BN of gate/up (packed rows), 4: BN of down
@@ -271,8 +268,8 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
-                               hipStream_t s) {
-  static const int remap = env_int("CMOE_XCD_REMAP", 1);
+                               hipStream_t s, int stage) {
+  const int remap = env_int("CMOE_XCD_REMAP", 1);
   GemmArgs a;
   a.groups = e.groups;
   a.seg_off = reinterpret_cast<const int32_t*>(ws + L.seg_off);
@@ -289,8 +286,10 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.work = reinterpret_cast<const int32_t*>(ws + L.work1);
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
   a.n_blocks = (int)round_up64(gemm_work_bound(e, T, 1), 8);
-  hipError_t err = launch_cfg<1>(cfg_index(1), a, s);
-  if (err != hipSuccess) return err;
+  if (stage != 2) {
+    hipError_t err = launch_cfg<1>(cfg_index(1), a, s);
+    if (err != hipSuccess || stage == 1) return err;
+  }
   // down
   a.A = reinterpret_cast<const bf16_t*>(ws + L.h);
   a.B = static_cast<const bf16_t*>(e.w2);

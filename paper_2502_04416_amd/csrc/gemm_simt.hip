@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_simt(SimtArgs<T> p) {
 
 template <typename T>
 static hipError_t run_simt(const Engine& e, const void* x, int64_t Tn, char* ws, const WsLayout& L, void* y,
-                           hipStream_t s) {
+                           hipStream_t s, int stage) {
   SimtArgs<T> a;
   a.groups = e.groups;
   a.seg_off = reinterpret_cast<const int32_t*>(ws + L.seg_off);
@@ -145,9 +145,11 @@ static hipError_t run_simt(const Engine& e, const void* x, int64_t Tn, char* ws,
   a.C = reinterpret_cast<T*>(ws + L.h);
   a.work = reinterpret_cast<const int32_t*>(ws + L.work1);
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
-  hipLaunchKernelGGL((grouped_gemm_simt<T, 1>), dim3((unsigned)gemm_work_bound(e, Tn, 1)), dim3(256), 0, s, a);
-  hipError_t err = hipGetLastError();
-  if (err != hipSuccess) return err;
+  if (stage != 2) {
+    hipLaunchKernelGGL((grouped_gemm_simt<T, 1>), dim3((unsigned)gemm_work_bound(e, Tn, 1)), dim3(256), 0, s, a);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || stage == 1) return err;
+  }
   a.A = reinterpret_cast<const T*>(ws + L.h);
   a.B = static_cast<const T*>(e.w2);
   a.C = (e.S_all() == 1) ? static_cast<T*>(y) : reinterpret_cast<T*>(ws + L.y_slots);
@@ -158,9 +160,9 @@ static hipError_t run_simt(const Engine& e, const void* x, int64_t Tn, char* ws,
 }
 
 hipError_t launch_experts_simt(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
-                               hipStream_t s) {
-  if (e.dtype == 1) return run_simt<bf16_t>(e, x, T, ws, L, y, s);
-  return run_simt<float>(e, x, T, ws, L, y, s);
+                               hipStream_t s, int stage) {
+  if (e.dtype == 1) return run_simt<bf16_t>(e, x, T, ws, L, y, s, stage);
+  return run_simt<float>(e, x, T, ws, L, y, s, stage);
 }
 
 int simt_gemm_tile(int) { return SB; }

@@ -133,6 +133,10 @@ class TokenSource:
         x = self.centres[k] + self.offset[None, :] + eps
         return _finish(x, self.cfg.dtype)
 
+    def draw(self, seed: int, n: int) -> np.ndarray:
+        """n tokens from this source with an explicit seed (extra batches for timing loops)."""
+        return self._draw(seed, n)
+
     def calibration(self, n: Optional[int] = None) -> np.ndarray:
         return self._draw(3000 + self.cfg.cfg, self.cfg.n_calib if n is None else n)
 
