@@ -77,6 +77,13 @@ typedef struct {
 int cmoe_build(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
                const float* calib_x, int64_t q, cmoe_layer** out);
 
+/* The balanced assignment step of App. A.3 on its own: given dist [n, n_r] (host, row-major,
+ * n = n_r * m) find label[i] in [0, n_r) minimising sum_i dist[i, label[i]] with exactly m rows per
+ * cluster.  Exact (successive shortest paths on the transportation problem; same optimum as the
+ * replicated-column assignment the paper describes).  label_out [n] int32, cost_out may be NULL. */
+int cmoe_balanced_assignment(const double* dist, int32_t n, int32_t n_r, int32_t m, int32_t* label_out,
+                             double* cost_out);
+
 /* Same slicing and packing, but from a given partition instead of profiling:
  * neuron_order [d_h] lists dense neuron ids, the N_s*m shared ones first, then routed expert
  * 0, 1, ... with m ids each; rep_neuron [N_r] holds the dense neuron id R_j of each routed

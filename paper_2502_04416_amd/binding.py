@@ -38,6 +38,7 @@ EXPORTS = [
     "cmoe_destroy", "cmoe_hier_create", "cmoe_hier_packed_bytes", "cmoe_hier_workspace_bytes",
     "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
+    "cmoe_balanced_assignment",
 ]
 
 
@@ -54,6 +55,8 @@ def load():
     cfgp = C.POINTER(cmoe_config)
     lib.cmoe_build.argtypes = [cfgp, f32p, f32p, f32p, f32p, i64, C.POINTER(vp)]
     lib.cmoe_build_from_partition.argtypes = [cfgp, f32p, f32p, f32p, i32p, i32p, C.POINTER(vp)]
+    lib.cmoe_balanced_assignment.argtypes = [C.POINTER(C.c_double), C.c_int32, C.c_int32, C.c_int32, i32p,
+                                             C.POINTER(C.c_double)]
     lib.cmoe_export_partition.argtypes = [vp, i32p, i32p, f32p, C.POINTER(C.c_double)]
     lib.cmoe_set_gate_params.argtypes = [vp, f32p, f32p]
     lib.cmoe_packed_bytes.argtypes = [vp]
@@ -126,6 +129,17 @@ def cmoe_build_from_partition(cfg: cmoe_config, w_gate, w_up, w_down, neuron_ord
     _check(load().cmoe_build_from_partition(C.byref(cfg), _fp(wg), _fp(wu), _fp(wd), _ip(no), _ip(rn), C.byref(h)),
            "cmoe_build_from_partition")
     return h.value
+
+
+def cmoe_balanced_assignment(dist: np.ndarray, m: int):
+    """(label [n], cost) of the exact balanced assignment of App. A.3 for dist [n, n_r], n = n_r * m."""
+    dd = np.ascontiguousarray(dist, dtype=np.float64)
+    n, n_r = dd.shape
+    label = np.empty(n, dtype=np.int32)
+    cost = C.c_double()
+    _check(load().cmoe_balanced_assignment(dd.ctypes.data_as(C.POINTER(C.c_double)), n, n_r, m, _ip(label),
+                                           C.byref(cost)), "cmoe_balanced_assignment")
+    return label, cost.value
 
 
 def cmoe_export_partition(layer: int, d_ff: int, n_routed: int) -> Dict[str, np.ndarray]:

@@ -379,6 +379,20 @@ int cmoe_build(const cmoe_config* cfg, const float* w_gate, const float* w_up, c
   return build_common(cfg, w_gate, w_up, w_down, calib_x, q, nullptr, nullptr, out);
 }
 
+int cmoe_balanced_assignment(const double* dist, int32_t n, int32_t n_r, int32_t m, int32_t* label_out,
+                             double* cost_out) {
+  if (!dist || !label_out) return fail(CMOE_EINVAL, "null argument");
+  if (n < 1 || n_r < 1 || m < 1 || (int64_t)n_r * m != n) return fail(CMOE_EINVAL, "need n == n_r * m with positive sizes");
+  std::string msg;
+  try {
+    if (!solve_balanced_assignment(dist, n, n_r, m, label_out, cost_out, &msg))
+      return fail(CMOE_EINVAL, "%s", msg.c_str());
+  } catch (const std::bad_alloc&) {
+    return fail(CMOE_ENOMEM, "out of host memory");
+  }
+  return CMOE_OK;
+}
+
 int cmoe_build_from_partition(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
                               const int32_t* neuron_order, const int32_t* rep_neuron, cmoe_layer** out) {
   if (!neuron_order) return fail(CMOE_EINVAL, "neuron_order is null");

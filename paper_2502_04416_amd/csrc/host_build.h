@@ -14,4 +14,8 @@ namespace cmoe {
 bool host_construct(const cmoe_config& cfg, const RoundedDense& rd, const float* calib_x, int64_t q,
                     int32_t* neuron_order, int32_t* rep_neuron, float* mu, double* cost, std::string* msg);
 
+// Exact balanced assignment (App. A.3) on a dense distance matrix; see host_build.cpp.
+bool solve_balanced_assignment(const double* dist, int n, int n_r, int m, int32_t* label_out, double* cost_out,
+                               std::string* msg);
+
 }  // namespace cmoe

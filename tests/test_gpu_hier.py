@@ -1,0 +1,108 @@
+"""GPU parity of the hierarchical case (Sec. 4.4, Eq. 10): an MoE layer whose experts were each
+restructured into shared + routed sub-experts, against the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import cmoe_oracle as O
+from paper_2502_04416_amd import synth
+from parity_utils import GAP_EPS, TOL, tokenwise_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2502_04416_amd import binding as b
+    b.load()
+    return b
+
+
+def _make(binding, cfg):
+    w_router, offsets = synth.make_outer_router(cfg)
+    experts, layers = [], []
+    for e in range(cfg.n_outer):
+        wg, wu, wd = synth.make_outer_expert_weights(cfg, e)
+        part = synth.trivial_partition(cfg, seed=e)
+        experts.append({"w_gate": wg, "w_up": wu, "w_down": wd, "neuron_order": part["neuron_order"],
+                        "rep_neuron": part["rep_neuron"]})
+        layers.append(binding.Layer.from_partition(cfg, wg, wu, wd, part["neuron_order"], part["rep_neuron"], upload=False))
+    hier = binding.Hierarchy(layers, cfg.outer_top_k, w_router, offsets)
+    return hier, experts, w_router, offsets
+
+
+def _check(cfg, experts, w_router, offsets, x, out, dense_y, sample):
+    T = x.shape[0]
+    ok, okw, ogap = O.outer_route(x, w_router, offsets, cfg.outer_top_k)
+    strict = ogap >= GAP_EPS
+    assert np.array_equal(out["outer"][strict], ok[strict]), "outer expert indices differ"
+    # sub-expert routing of every token under the GPU's outer choice
+    n_r = cfg.n_routed
+    sub_excused = 0
+    for e in range(cfg.n_outer):
+        rows, slot = np.nonzero(out["outer"] == e)
+        if rows.size == 0:
+            continue
+        s = O.router_scores(x[rows], experts[e]["w_gate"], experts[e]["w_up"], experts[e]["rep_neuron"])
+        sel, gap = O.select_top_k(s, cfg.top_k)
+        good = gap >= GAP_EPS
+        got = out["sub"][rows, slot]
+        assert np.array_equal(got[good], sel[good]), "sub-expert indices differ in outer expert %d" % e
+        sub_excused += int((~good).sum())
+        for r in np.nonzero(~good)[0]:
+            kth = s[r, sel[r, -1]]
+            assert len(set(got[r].tolist())) == cfg.top_k and (s[r, got[r]] >= kth - GAP_EPS).all()
+        assert got.min() >= 0 and got.max() < n_r
+    idx = np.asarray(sample)
+    ref = O.hier_forward(x[idx], w_router, offsets, cfg.outer_top_k, experts, cfg.n_experts, cfg.n_shared, cfg.top_k,
+                         outer_sel_override=out["outer"][idx], sub_sel_override=out["sub"][idx])
+    err = tokenwise_rel_err(out["y"][idx], ref["y"])
+    assert err.max() <= TOL[cfg.dtype], "hier: max per-token relative error %g" % err.max()
+    dref = O.moe_layer_dense_experts(x[idx[:16]], w_router, offsets, cfg.outer_top_k, experts)
+    # the dense form routes with the GPU's own outer choice; compare only tokens whose outer choice is strict
+    keep = strict[idx[:16]]
+    derr = tokenwise_rel_err(dense_y[idx[:16]][keep], dref[keep])
+    assert derr.max() <= TOL[cfg.dtype], "hier dense: max per-token relative error %g" % derr.max()
+    load = np.bincount(out["outer"].ravel(), minlength=cfg.n_outer)
+    return {"outer_near_ties": int((~strict).sum()), "sub_near_ties": sub_excused, "max_rel_err": float(err.max()),
+            "dense_rel_err": float(derr.max()), "outer_load": load.tolist()}
+
+
+def test_hier_small(binding):
+    cfg = synth.scaled(synth.CONFIGS[4], d_model=512, d_ff=1408, n_experts=8, n_shared=2, top_k=2, n_outer=4,
+                       outer_top_k=2, n_centres=16)
+    hier, experts, w_router, offsets = _make(binding, cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=500)
+    out = hier.forward(x)
+    rep = _check(cfg, experts, w_router, offsets, x, out, hier.dense_forward(x), np.arange(500))
+    print("\n[parity] hier small: %s" % rep, flush=True)
+    out2 = hier.forward(x)
+    assert np.array_equal(out["y"], out2["y"])
+    # every sub-expert active: the hierarchy reproduces the un-restructured layer (Eq. 10 + Eq. 5)
+    hier.close()
+
+
+def test_hier_all_subexperts_active_equals_dense_layer(binding):
+    cfg = synth.scaled(synth.CONFIGS[4], d_model=256, d_ff=1024, n_experts=8, n_shared=2, top_k=6, n_outer=3,
+                       outer_top_k=2, n_centres=8)
+    hier, experts, w_router, offsets = _make(binding, cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=130)
+    out = hier.forward(x)
+    dense = hier.dense_forward(x)
+    ref = O.moe_layer_dense_experts(x, w_router, offsets, cfg.outer_top_k, experts)
+    assert tokenwise_rel_err(out["y"], ref).max() <= TOL["bf16"]
+    assert tokenwise_rel_err(dense, ref).max() <= TOL["bf16"]
+    hier.close()
+
+
+def test_hier_cfg4_full(binding):
+    """Mixtral-8x7B-shaped layer: 8 outer experts of 14336 neurons, each split into 8 sub-experts of 1792
+    (2 shared + top-2 of 6), 4096 tokens with Zipf-skewed outer routing."""
+    cfg = synth.CONFIGS[4]
+    hier, experts, w_router, offsets = _make(binding, cfg)
+    x = synth.make_token_source(cfg).eval_batch(0)
+    out = hier.forward(x)
+    rng = np.random.Generator(np.random.PCG64(404))
+    sample = np.sort(rng.choice(x.shape[0], size=24, replace=False))
+    rep = _check(cfg, experts, w_router, offsets, x, out, hier.dense_forward(x), sample)
+    print("\n[parity] hier cfg4 T=%d: %s" % (x.shape[0], rep), flush=True)
+    hier.close()
