@@ -36,6 +36,10 @@ def parse():
                     help="partition from cmoe_build on the calibration set, or a seeded arbitrary one")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-batch measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the dense-FFN baseline (so that a kernel trace holds MoE launches only)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (reference reading for HBM byte counters)")
     ap.add_argument("--layer-copies", type=int, default=8, help="device copies of the layer cycled at decode")
     return ap.parse_args()
 
@@ -94,9 +98,17 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    if args.copy_probe:
+        # a copy of known size: 2^30 bytes read + 2^30 bytes written; scales FETCH_SIZE / WRITE_SIZE readings
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        a.copy_(b)
+        torch.cuda.synchronize()
+        del a, b
+
     # ---- headline: K steps of the MoE forward, bracketed by synchronize ----
     ms_moe = timed(lambda: layer.forward_device(x, y, topk, None, counts), args.steps, args.warmup)
-    ms_dense = timed(lambda: layer.dense_forward_device(x, y), args.steps, args.warmup)
+    ms_dense = float("nan") if args.no_dense else timed(lambda: layer.dense_forward_device(x, y), args.steps, args.warmup)
     layer.forward_device(x, y, topk, None, counts)
     torch.cuda.synchronize()
     cnt = counts.cpu().numpy()
@@ -111,7 +123,7 @@ def main():
         return acc / n
     n_prof = max(5, min(args.steps, 30))
     st_moe = stages(False, n_prof)
-    st_dense = stages(True, n_prof)
+    st_dense = np.full(5, np.nan) if args.no_dense else stages(True, n_prof)
 
     d, m = cfg.d_model, cfg.m
     act = cfg.n_shared + cfg.top_k

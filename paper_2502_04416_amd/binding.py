@@ -50,6 +50,9 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise CmoeError("libcmoe.so is not built (%s missing): run `python __graft_entry__.py`; "
                         "there is no fallback path" % LIB_PATH)
+    # torch first: its bundled HIP runtime must be the one already in the process when libcmoe.so
+    # resolves libamdhip64, so that both share one runtime (device pointers and streams come from torch)
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32p, f32p, i64, sz = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int64, C.c_size_t
     cfgp = C.POINTER(cmoe_config)

@@ -37,6 +37,11 @@ size_t elem_size(int dtype) { return dtype == CMOE_BF16 ? 2 : 4; }
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+int w1_row_stride(int d) {
+  static const int pad = std::getenv("CMOE_LDPAD") ? std::atoi(std::getenv("CMOE_LDPAD")) : 0;
+  return d + ((pad > 0 && pad % 8 == 0) ? pad : 0);
+}
+
 void parallel_for(int64_t n, const std::function<void(int64_t)>& fn, int max_threads) {
   int nt = max_threads > 0 ? max_threads : (int)std::thread::hardware_concurrency();
   if (const char* env = std::getenv("CMOE_HOST_THREADS")) nt = std::atoi(env);
@@ -101,7 +106,7 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
   L.slot2tok = take(sizeof(int32_t) * L.n_slots);
   L.tok2slot = take(sizeof(int32_t) * L.n_slots);
   L.slot_w = take(sizeof(float) * L.n_slots);
-  L.scores = take(sizeof(float) * Tn * std::max(e.r.n_scored + e.r.n_lin, 1));
+  L.scores = take(sizeof(float) * 8 * Tn * std::max(e.r.n_sw_rows + e.r.n_lin_rows, 1));   // router K-slice partials
   L.h = take(es * (size_t)Tn * (size_t)e.h_per_token);
   L.y_slots = take(S_all == 1 ? 0 : es * (size_t)L.n_slots * e.d);
   L.total = off;
@@ -112,6 +117,7 @@ hipError_t launch_experts(const Engine& e, const void* x, int64_t T, char* ws, c
                           hipStream_t s, int stage) {
   if (T == 0) return hipSuccess;
   if (use_simt_experts(e.dtype)) return launch_experts_simt(e, x, T, ws, L, y, s, stage);
+  if (decode_path_ok(e, T)) return launch_experts_decode(e, x, T, ws, L, y, s, stage);
   return launch_experts_bf16(e, x, T, ws, L, y, s, stage);
 }
 
@@ -167,9 +173,10 @@ void pack_group(PackedSet& ps, const RoundedDense& rd, const int32_t* neurons, i
   gd.w2_off = ps.w2_elems;
   ps.groups.push_back(gd);
   ps.width.push_back(width);
-  const size_t row_bytes = (size_t)d * es;
+  const size_t row_bytes = (size_t)d * es;            // payload of a row
+  const size_t ld_bytes = (size_t)ps.ld * es;         // distance between rows of w1
   const size_t w1_base = ps.w1.size();
-  ps.w1.resize(w1_base + (size_t)2 * wp * row_bytes, 0);
+  ps.w1.resize(w1_base + (size_t)2 * wp * ld_bytes, 0);
   const size_t w2_base = ps.w2.size();
   ps.w2.resize(w2_base + (size_t)d * wp * es, 0);
   ps.w1_rows += 2 * wp;
@@ -179,8 +186,8 @@ void pack_group(PackedSet& ps, const RoundedDense& rd, const int32_t* neurons, i
     for (int c = 0; c < IL; ++c) {
       const int n = (int)blk * IL + c;
       if (n >= width) continue;
-      uint8_t* g_dst = ps.w1.data() + w1_base + ((size_t)blk * 2 * IL + c) * row_bytes;
-      uint8_t* u_dst = ps.w1.data() + w1_base + ((size_t)blk * 2 * IL + IL + c) * row_bytes;
+      uint8_t* g_dst = ps.w1.data() + w1_base + ((size_t)blk * 2 * IL + c) * ld_bytes;
+      uint8_t* u_dst = ps.w1.data() + w1_base + ((size_t)blk * 2 * IL + IL + c) * ld_bytes;
       std::memcpy(g_dst, rd.gate_row(neurons[n]), row_bytes);
       std::memcpy(u_dst, rd.up_row(neurons[n]), row_bytes);
     }
@@ -264,6 +271,7 @@ static void fill_flat_engines(cmoe_layer* L) {
   e = Engine{};
   e.dtype = c.dtype;
   e.d = c.d_model;
+  e.ldw1 = L->moe.ld;
   e.G = (int)L->moe.groups.size();
   e.n_always = c.n_shared > 0 ? 1 : 0;
   e.S_dyn = c.top_k;
@@ -291,6 +299,7 @@ static void fill_flat_engines(cmoe_layer* L) {
   dn = Engine{};
   dn.dtype = c.dtype;
   dn.d = c.d_model;
+  dn.ldw1 = L->dense.ld;
   dn.G = 1;
   dn.n_always = 1;
   dn.S_dyn = 0;
@@ -344,11 +353,13 @@ static int build_common(const cmoe_config* cfg, const float* w_gate, const float
     // expert groups: one shared group of N_s*m neurons (if any), then the routed experts
     L->moe.dtype = cfg->dtype;
     L->moe.d = d;
+    L->moe.ld = w1_row_stride(d);
     if (cfg->n_shared > 0) pack_group(L->moe, rd, L->neuron_order.data(), cfg->n_shared * m);
     for (int j = 0; j < n_r; ++j) pack_group(L->moe, rd, L->neuron_order.data() + (size_t)(cfg->n_shared + j) * m, m);
     // dense baseline: every neuron in its original order, one group, padded once
     L->dense.dtype = cfg->dtype;
     L->dense.d = d;
+    L->dense.ld = w1_row_stride(d);
     std::vector<int32_t> ident(d_ff);
     for (int i = 0; i < d_ff; ++i) ident[i] = i;
     pack_group(L->dense, rd, ident.data(), d_ff);
@@ -631,6 +642,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     m = Engine{};
     m.dtype = c.dtype;
     m.d = d;
+    m.ldw1 = experts[0]->moe.ld;
     const int gpo = has_shared + n_r;
     m.G = n_outer * gpo;
     m.n_always = 0;
@@ -661,6 +673,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     dn = Engine{};
     dn.dtype = c.dtype;
     dn.d = d;
+    dn.ldw1 = experts[0]->dense.ld;
     dn.G = n_outer;
     dn.n_always = 0;
     dn.S_dyn = outer_top_k;
@@ -723,10 +736,10 @@ int cmoe_hier_upload(cmoe_hier* H, void* dev_weights, void* hip_stream) {
   size_t w1 = 0, w2 = 0, dw1 = 0, dw2 = 0;
   hipError_t e = hipSuccess;
   for (auto* L : H->experts) {
-    const int64_t row_shift = (int64_t)(w1 / ((size_t)H->cfg.d_model * es));
+    const int64_t row_shift = (int64_t)(w1 / ((size_t)L->moe.ld * es));
     const int64_t el_shift = (int64_t)(w2 / es);
     for (const GroupDev& gd : L->moe.groups) g_moe.push_back(GroupDev{gd.width_pad, (int32_t)(gd.w1_row0 + row_shift), gd.w2_off + el_shift});
-    const int64_t drow_shift = (int64_t)(dw1 / ((size_t)H->cfg.d_model * es));
+    const int64_t drow_shift = (int64_t)(dw1 / ((size_t)L->dense.ld * es));
     const int64_t del_shift = (int64_t)(dw2 / es);
     for (const GroupDev& gd : L->dense.groups) g_dense.push_back(GroupDev{gd.width_pad, (int32_t)(gd.w1_row0 + drow_shift), gd.w2_off + del_shift});
     if (e == hipSuccess) e = h2d(base + o.w1 + w1, L->moe.w1.data(), L->moe.w1.size(), s);

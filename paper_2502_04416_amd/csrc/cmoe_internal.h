@@ -59,7 +59,7 @@ struct WsLayout {
   size_t h_off;                      // [G+1] int64: element offset of each group's rows in H
   size_t slot2tok;                   // [n_slots] int32
   size_t tok2slot, slot_w;           // [T][S_all] int32 / float
-  size_t scores;                     // [T][n_scored + n_lin] float
+  size_t scores;                     // [8][T][router rows] float: K-slice partial pre-activations of the router
   size_t h;                          // hidden activations, ragged: rows of group g are width_pad(g) wide
   size_t y_slots;                    // [n_slots][d]; unused when S_all == 1 (written straight to y)
   size_t total;
@@ -76,6 +76,7 @@ struct Engine {
   int S_dyn = 0;             // routed slots per token
   int64_t h_per_token = 0;   // upper bound of hidden elements per token (sum of its groups' width_pad)
   int max_width_pad = 0;
+  int ldw1 = 0;              // row stride (elements) of W1: d plus a pad that breaks the power-of-two stride
   int width_pad_host[MAX_GROUPS] = {0};   // host copy of the groups' padded widths
   RouterDev r{};
   // device pointers (inside the caller's weight buffer)
@@ -90,6 +91,9 @@ struct Engine {
 };
 
 size_t elem_size(int dtype);
+// Row stride of the packed gate/up matrix for model width d.  Rows that are a power of two apart all map
+// to the same L2 channel; the pad spreads the rows of a tile over the channels.
+int w1_row_stride(int d);
 WsLayout ws_layout(const Engine& e, int64_t T);
 
 // Kernel launchers (defined in the .hip files).  All enqueue on `s` and return the launch status.
@@ -113,6 +117,10 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
                                hipStream_t s, int stage);
 hipError_t launch_experts_simt(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                hipStream_t s, int stage);
+// Decode batches (bf16, T <= 32): weight-streaming expert kernels, see decode.hip.
+bool decode_path_ok(const Engine& e, int64_t T);
+hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
+                                 hipStream_t s, int stage);
 // Upper bound of work items of grouped GEMM `which` (1: gate/up, 2: down) for T tokens.
 int64_t gemm_work_bound(const Engine& e, int64_t T, int which);
 

@@ -1,0 +1,257 @@
+// Expert kernels for decode batches (T <= 32 tokens, bf16): weight streaming bound by HBM bandwidth.
+//
+// Every expert group with at least one token is cut into units of 16 neurons (gate/up) or 16 output
+// columns (down).  The weights of a unit are the A operand of v_mfma_f32_16x16x32_bf16 and are read
+// straight from global memory exactly once, 64 contiguous bytes per row and instruction; the tokens
+// of the group (at most 32, gathered through slot2tok) are the B operand and stay in registers for
+// the whole unit.  The reduction dimension is split over the waves of a workgroup so that a unit
+// keeps many independent loads in flight; the partial sums are added in a fixed order through LDS.
+// This is the per-neuron form of the FFN, F(x) = sum_i h_i w_i (Eq. 1), evaluated only for the
+// neurons of the experts some token selected (Eq. 4).
+#include <algorithm>
+#include "cmoe_internal.h"
+#include "device_utils.h"
+
+namespace cmoe {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+struct DecArgs {
+  const bf16_t* x;          // [T][d]
+  const bf16_t* w1;
+  const bf16_t* w2;
+  bf16_t* h;                // ragged hidden activations
+  bf16_t* y;                // per-slot outputs [n_slots][d] (or y itself when every token has one slot)
+  const GroupDev* groups;
+  const int32_t* seg_off;
+  const int32_t* work;      // [G+1] prefix of units
+  const int64_t* h_off;
+  const int32_t* slot2tok;
+  int G, d;
+  int ldw;                  // row stride of w1
+  int64_t T;
+  int single;
+};
+
+__device__ __forceinline__ bf16x8_t ld_frag(const bf16_t* p) { return *reinterpret_cast<const bf16x8_t*>(p); }
+__device__ __forceinline__ bf16x8_t zero_frag() {
+  bf16x8_t z;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.0f;
+  return z;
+}
+
+// Which unit is this workgroup?  Returns false when past the end of the list.
+__device__ __forceinline__ bool find_unit(const DecArgs& p, int units_single, int& g, int& local, int& seg0, int& cnt,
+                                          int& wp, int64_t& hoff) {
+  const int u = blockIdx.x;
+  if (p.single) {
+    if (u >= units_single) return false;
+    g = 0;
+    local = u;
+    seg0 = 0;
+    cnt = (int)p.T;
+    wp = p.groups[0].width_pad;
+    hoff = 0;
+    return true;
+  }
+  if (u >= p.work[p.G]) return false;
+  int lo = 0, hi = p.G;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (p.work[mid] <= u) lo = mid; else hi = mid;
+  }
+  g = lo;
+  local = u - p.work[g];
+  seg0 = p.seg_off[g];
+  cnt = p.seg_off[g + 1] - seg0;
+  wp = p.groups[g].width_pad;
+  hoff = p.h_off[g];
+  return true;
+}
+
+// ---- gate/up: H[slot][n] = Swish(x . wgate_n) * (x . wup_n) for 16 neurons of one group ---------------
+// 8 waves, wave w multiplies the K slice [w*d/8, (w+1)*d/8).  NTT = token tiles of 16.  KSTEPS = d/8/32.
+template <int NTT, int KSTEPS>
+__global__ __launch_bounds__(512) void decode_gate_up_kernel(DecArgs p) {
+  __shared__ float red[8][2][NTT][16][17];
+  int g, local, seg0, cnt, wp;
+  int64_t hoff;
+  if (!find_unit(p, p.single ? p.groups[0].width_pad / 16 : 0, g, local, seg0, cnt, wp, hoff)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int neuron0 = local * 16;
+  const int kbase = wave * (KSTEPS * 32) + kq * 8;
+  // weight rows of this lane: packed row = (n / IL) * 2 * IL + n % IL (+ IL for the up row)
+  const int n = neuron0 + r16;
+  const int64_t grow = (int64_t)p.groups[g].w1_row0 + (n / IL) * 2 * IL + (n % IL);
+  const bf16_t* wg = p.w1 + grow * p.ldw + kbase;
+  const bf16_t* wu = wg + (int64_t)IL * p.ldw;
+  // tokens (B operand), kept for the whole unit
+  bf16x8_t bx[NTT][KSTEPS];
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt) {
+    const int col = tt * 16 + r16;
+    const bool ok = col < cnt;
+    int64_t tok = 0;
+    if (ok) tok = p.slot2tok ? p.slot2tok[seg0 + col] : (seg0 + col);
+    const bf16_t* xr = p.x + tok * p.d + kbase;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) bx[tt][ks] = ok ? ld_frag(xr + ks * 32) : zero_frag();
+  }
+  floatx4_t accg[NTT], accu[NTT];
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { accg[tt][i] = 0.0f; accu[tt][i] = 0.0f; }
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) {
+    const bf16x8_t ag = ld_frag(wg + ks * 32);
+    const bf16x8_t au = ld_frag(wu + ks * 32);
+#pragma unroll
+    for (int tt = 0; tt < NTT; ++tt) {
+      accg[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, bx[tt][ks], accg[tt], 0, 0, 0);
+      accu[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, bx[tt][ks], accu[tt], 0, 0, 0);
+    }
+  }
+  // accumulator element i: neuron row (lane/16)*4 + i, token column lane%16
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      red[wave][0][tt][kq * 4 + i][r16] = accg[tt][i];
+      red[wave][1][tt][kq * 4 + i][r16] = accu[tt][i];
+    }
+  __syncthreads();
+  for (int e = tid; e < NTT * 256; e += 512) {
+    const int tt = e >> 8, tok = (e >> 4) & 15, nn = e & 15;     // neuron fastest: contiguous stores
+    const int col = tt * 16 + tok;
+    if (col >= cnt) continue;
+    float sg = 0.0f, su = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) { sg += red[w][0][tt][nn][tok]; su += red[w][1][tt][nn][tok]; }
+    p.h[hoff + (int64_t)col * wp + neuron0 + nn] = f32_to_bf16(silu_f32(sg) * su);
+  }
+}
+
+// ---- down: Y[slot][c] = sum_n H[slot][n] * Wdown[n][c] for 16 output columns of one group --------------
+// 4 waves; wave w takes the 32-wide K steps w, w+4, ...
+template <int NTT>
+__global__ __launch_bounds__(256) void decode_down_kernel(DecArgs p) {
+  __shared__ float red[4][NTT][16][17];
+  int g, local, seg0, cnt, wp;
+  int64_t hoff;
+  if (!find_unit(p, p.single ? p.d / 16 : 0, g, local, seg0, cnt, wp, hoff)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int c0 = local * 16;
+  const bf16_t* wrow = p.w2 + p.groups[g].w2_off + (int64_t)(c0 + r16) * wp + kq * 8;
+  const bf16_t* hrow[NTT];
+  bool hok[NTT];
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt) {
+    const int col = tt * 16 + r16;
+    hok[tt] = col < cnt;
+    hrow[tt] = p.h + hoff + (int64_t)(hok[tt] ? col : 0) * wp + kq * 8;
+  }
+  floatx4_t acc[NTT];
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[tt][i] = 0.0f;
+  const int n_steps = wp / 32;
+  int ks = wave;
+  // four K steps of this wave at a time: their loads are independent and all in flight together
+  for (; ks + 12 < n_steps; ks += 16) {
+    bf16x8_t a[4], b[NTT][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a[u] = ld_frag(wrow + (ks + 4 * u) * 32);
+#pragma unroll
+      for (int tt = 0; tt < NTT; ++tt) b[tt][u] = hok[tt] ? ld_frag(hrow[tt] + (ks + 4 * u) * 32) : zero_frag();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int tt = 0; tt < NTT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[tt][u], acc[tt], 0, 0, 0);
+  }
+  for (; ks < n_steps; ks += 4) {
+    const bf16x8_t a = ld_frag(wrow + ks * 32);
+#pragma unroll
+    for (int tt = 0; tt < NTT; ++tt) {
+      const bf16x8_t b = hok[tt] ? ld_frag(hrow[tt] + ks * 32) : zero_frag();
+      acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[tt], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[wave][tt][kq * 4 + i][r16] = acc[tt][i];
+  __syncthreads();
+  for (int e = tid; e < NTT * 256; e += 256) {
+    const int tt = e >> 8, tok = (e >> 4) & 15, cc = e & 15;       // column fastest: contiguous stores
+    const int col = tt * 16 + tok;
+    if (col >= cnt) continue;
+    const float s = (red[0][tt][cc][tok] + red[1][tt][cc][tok]) + (red[2][tt][cc][tok] + red[3][tt][cc][tok]);
+    p.y[(int64_t)(seg0 + col) * p.d + c0 + cc] = f32_to_bf16(s);
+  }
+}
+
+bool decode_path_ok(const Engine& e, int64_t T) {
+  if (e.dtype != 1 || T < 1 || T > 32) return false;
+  if (e.d % 256 != 0) return false;
+  const int ksteps = e.d / 256;
+  return ksteps == 16 || ksteps == 8 || ksteps == 4 || ksteps == 2;
+}
+
+int64_t decode_unit_bound(const Engine& e, int64_t T, int which) {
+  const int64_t dyn_groups = std::min<int64_t>(T * e.S_dyn, e.G - e.n_always);
+  const int64_t per_group = which == 1 ? e.max_width_pad / 16 : e.d / 16;
+  return std::max<int64_t>((e.n_always + dyn_groups) * per_group, 1);
+}
+
+template <int NTT>
+static hipError_t launch_gate_up(const DecArgs& a, int ksteps, int64_t n_blocks, hipStream_t s) {
+  dim3 grid((unsigned)n_blocks), block(512);
+  switch (ksteps) {
+    case 16: hipLaunchKernelGGL((decode_gate_up_kernel<NTT, 16>), grid, block, 0, s, a); break;
+    case 8: hipLaunchKernelGGL((decode_gate_up_kernel<NTT, 8>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((decode_gate_up_kernel<NTT, 4>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((decode_gate_up_kernel<NTT, 2>), grid, block, 0, s, a); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
+                                 hipStream_t s, int stage) {
+  DecArgs a;
+  a.x = static_cast<const bf16_t*>(x);
+  a.w1 = static_cast<const bf16_t*>(e.w1);
+  a.w2 = static_cast<const bf16_t*>(e.w2);
+  a.h = reinterpret_cast<bf16_t*>(ws + L.h);
+  a.y = (e.S_all() == 1) ? static_cast<bf16_t*>(y) : reinterpret_cast<bf16_t*>(ws + L.y_slots);
+  a.groups = e.groups;
+  a.seg_off = reinterpret_cast<const int32_t*>(ws + L.seg_off);
+  a.h_off = reinterpret_cast<const int64_t*>(ws + L.h_off);
+  a.G = e.G;
+  a.d = e.d;
+  a.ldw = e.ldw1;
+  a.T = T;
+  a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
+  a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
+  const bool two = T > 16;
+  if (stage != 2) {
+    a.work = reinterpret_cast<const int32_t*>(ws + L.work1);
+    const int64_t nb = a.single ? e.max_width_pad / 16 : decode_unit_bound(e, T, 1);
+    hipError_t err = two ? launch_gate_up<2>(a, e.d / 256, nb, s) : launch_gate_up<1>(a, e.d / 256, nb, s);
+    if (err != hipSuccess || stage == 1) return err;
+  }
+  a.work = reinterpret_cast<const int32_t*>(ws + L.work2);
+  const int64_t nb = a.single ? e.d / 16 : decode_unit_bound(e, T, 2);
+  if (two) hipLaunchKernelGGL((decode_down_kernel<2>), dim3((unsigned)nb), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((decode_down_kernel<1>), dim3((unsigned)nb), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace cmoe

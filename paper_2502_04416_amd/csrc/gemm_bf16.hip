@@ -6,6 +6,7 @@
 // items is a device-side prefix array written by the permute kernel, so ragged, empty and skewed
 // groups need no host round trip.  Workgroups whose index is past the list exit at once.
 #include <cstdlib>
+#include <type_traits>
 #include "cmoe_internal.h"
 #include "device_utils.h"
 
@@ -25,10 +26,13 @@ struct GemmArgs {
   const int32_t* slot2tok;   // MODE 1 gather; null = identity
   int G;
   int d;
+  int ldb;                   // row stride of B in MODE 1 (packed gate/up rows)
   int64_t T;
   int single;                // 1: one always-on group holding all T tokens; no device schedule is read
   int n_blocks;              // grid size (multiple of 8)
   int xcd_remap;             // 1: consecutive work items run on the same XCD
+  int dbg;                   // tuning aid: bit 0 skips the global->LDS loads, bit 1 skips LDS reads and MFMAs
+  unsigned long long* tstamps;   // tuning aid: per workgroup [8] clock samples (null = off)
 };
 
 constexpr int BK = 64;
@@ -93,7 +97,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16(GemmArgs p) {
   const int K = (MODE == 1) ? p.d : wp;
   const int n_cols = (MODE == 1) ? 2 * wp : p.d;         // columns of C^T = rows of B
   const int n_nt = (n_cols + BN - 1) / BN;
-  const int mt = local / n_nt, nt = local % n_nt;
+  const int n_mt = (cnt + BM - 1) / BM;
+  // raster inside a group: super-rows of GM row tiles; inside a super-row the row tile runs fastest, so
+  // the (up to GM) tiles that read the same weight tile are neighbours in time and, with the XCD remap,
+  // in one L2
+  constexpr int GM = 8;
+  const int sr = local / (GM * n_nt);
+  const int rem = local - sr * (GM * n_nt);
+  const int rows_in_sr = (n_mt - sr * GM) < GM ? (n_mt - sr * GM) : GM;
+  const int mt = sr * GM + rem % rows_in_sr;
+  const int nt = rem / rows_in_sr;
 
   // ---- per-thread global sources ----
   const bf16_t* a_src[A_CH];
@@ -118,7 +131,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16(GemmArgs p) {
     const int row = (tid >> 3) + i * (NT >> 3);
     int n = nt * BN + row;
     if (n >= n_cols) n = n_cols - 1;
-    if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.d + cchunk * 8;
+    if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + cchunk * 8;
     else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + cchunk * 8;
     b_dst[i] = lds_off(row, cchunk);
   }
@@ -208,14 +221,324 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16(GemmArgs p) {
   }
 }
 
+// ---- variant with direct global->LDS loads and a ring of STAGES tiles ------------------------------
+// Each global_load_lds_dwordx4 moves 64 lanes x 16 bytes into 1 KB of consecutive LDS (8 tile rows);
+// which global chunk a lane fetches is free, so the XOR swizzle is applied on the global side.  No
+// VGPRs are spent on staging, and STAGES-1 tiles are in flight while one is multiplied.
+__device__ __attribute__((aligned(16))) uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void dma16(const void* gsrc, bf16_t* lds_dst) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc),
+                                   (__attribute__((address_space(3))) void*)(lds_dst), 16, 0, 0);
+}
+
+// LDS tile [rows][BKT] of bf16, 16-byte chunks XOR-swizzled so that the 16 rows one quarter of a
+// ds_read_b128 touches fall into 16 different 16-byte bank groups (256 bytes = all 64 banks).
+template <int BKT>
+__device__ __forceinline__ int lds_off_t(int row, int c) {
+  if (BKT == 64) return row * 64 + ((c ^ ((row >> 1) & 7)) << 3);
+  return row * 32 + ((c ^ ((row >> 2) & 3)) << 3);
+}
+
+template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE>
+__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs p) {
+  constexpr int NW = WGM * WGN;
+  constexpr int TM = BM / WGM, TN = BN / WGN, MI = TM / 32, NI = TN / 32;
+  constexpr int CPR = BKT / 8;                                  // 16-byte chunks per tile row
+  constexpr int RPI = 64 / CPR;                                 // tile rows one 1 KB DMA instruction fills
+  constexpr int A_CH = BM / RPI / NW, B_CH = BN / RPI / NW;     // DMA instructions per wave and tile
+  constexpr int LPT = A_CH + B_CH;
+  constexpr int STAGE_ELEMS = (BM + BN) * BKT;
+  constexpr int SWZ_SHIFT = (BKT == 64) ? 1 : 2;
+  // STAGES >= 2: ring of whole K tiles (A part + B part).  STAGES == 0: ring of five half tiles in the order
+  // A(0) B(0) A(1) B(1) ...: while tile kt is multiplied, B(kt+1) and A(kt+2) are fetched into the two
+  // halves tile kt-1 just released, and A(kt+1) is already resident, so only half a tile has to land
+  // within one K step although 2.5 tiles of LDS are in use.
+  constexpr bool HR = (STAGES == 0);
+  constexpr int HALF = (BM > BN ? BM : BN) * BKT;
+  constexpr int RING_ELEMS = HR ? 5 * HALF : STAGES * STAGE_ELEMS;
+  static_assert(BKT == 32 || BKT == 64, "K tile");
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "loader");
+  static_assert(MODE != 1 || TN % 64 == 0, "gate/up pairs must stay inside a wave tile");
+  static_assert(HR || (STAGES >= 2 && (STAGES - 2) * LPT < 64), "ring depth");
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: LDS destinations stay scalar
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  unsigned long long ts0 = 0, ts1 = 0, ts2 = 0, tw0 = 0;
+  if (p.tstamps) { ts0 = __builtin_amdgcn_s_memtime(); tw0 = wall_clock64(); }
+  int g = 0, cnt, seg0 = 0, wp;
+  int64_t hoff = 0;
+  int n_work;
+  if (p.single) {
+    cnt = (int)p.T;
+    wp = p.groups[0].width_pad;
+    const int nc = (MODE == 1) ? 2 * wp : p.d;
+    n_work = ((cnt + BM - 1) / BM) * ((nc + BN - 1) / BN);
+  } else {
+    n_work = p.work[p.G];
+  }
+  int wid = blockIdx.x;
+  if (p.xcd_remap) {
+    const int chunk = (n_work + 7) >> 3;
+    if ((wid >> 3) >= chunk) return;
+    wid = (wid & 7) * chunk + (wid >> 3);
+  }
+  if (wid >= n_work) return;
+  int local = wid;
+  if (!p.single) {
+    int lo = 0, hi = p.G;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.work[mid] <= wid) lo = mid; else hi = mid;
+    }
+    g = lo;
+    local = wid - p.work[g];
+    seg0 = p.seg_off[g];
+    cnt = p.seg_off[g + 1] - seg0;
+    wp = p.groups[g].width_pad;
+    hoff = p.h_off[g];
+  }
+  const int K = (MODE == 1) ? p.d : wp;
+  const int n_cols = (MODE == 1) ? 2 * wp : p.d;
+  const int n_nt = (n_cols + BN - 1) / BN;
+  const int n_mt = (cnt + BM - 1) / BM;
+  constexpr int GM = 8;
+  const int sr = local / (GM * n_nt);
+  const int rem = local - sr * (GM * n_nt);
+  const int rows_in_sr = (n_mt - sr * GM) < GM ? (n_mt - sr * GM) : GM;
+  const int mt = sr * GM + rem % rows_in_sr;
+  const int nt = rem / rows_in_sr;
+
+  // per-lane sources: transfer i of this wave covers tile rows rg*8 .. rg*8+7, rg = wave + i*NW; the lane
+  // writes physical chunk lane%8 of row rg*8 + lane/8 and therefore fetches logical chunk (lane%8) ^ swz(row)
+  const bf16_t* a_src[A_CH];
+  const bf16_t* b_src[B_CH];
+  int a_coff[A_CH], b_coff[B_CH];                      // element offset of the lane's chunk inside a 64-wide K tile
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int row = (wave + i * NW) * RPI + lane / CPR;
+    a_coff[i] = (((lane % CPR) ^ ((row >> SWZ_SHIFT) & (CPR - 1))) << 3);
+    int r = mt * BM + row;
+    if (r >= cnt) r = cnt - 1;
+    if (MODE == 1) {
+      const int64_t tok = p.slot2tok ? p.slot2tok[seg0 + r] : (seg0 + r);
+      a_src[i] = p.A + tok * p.d + a_coff[i];
+    } else {
+      a_src[i] = p.A + hoff + (int64_t)r * wp + a_coff[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    const int row = (wave + i * NW) * RPI + lane / CPR;
+    b_coff[i] = (((lane % CPR) ^ ((row >> SWZ_SHIFT) & (CPR - 1))) << 3);
+    int n = nt * BN + row;
+    if (n >= n_cols) n = n_cols - 1;
+    if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + b_coff[i];
+    else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + b_coff[i];
+  }
+  const int KT = (K + BKT - 1) / BKT;
+  const bool k_ragged = (K % BKT) != 0;
+  auto a_slot = [&](int kt) -> bf16_t* { return HR ? smem + ((2 * kt) % 5) * HALF : smem + (kt % (HR ? 1 : STAGES)) * STAGE_ELEMS; };
+  auto b_slot = [&](int kt) -> bf16_t* {
+    return HR ? smem + ((2 * kt + 1) % 5) * HALF : smem + (kt % (HR ? 1 : STAGES)) * STAGE_ELEMS + BM * BKT;
+  };
+  auto issue_a = [&](int kt) {
+    bf16_t* as = a_slot(kt);
+    const bool tail = k_ragged && kt == KT - 1;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+      const void* src = a_src[i] + kt * BKT;
+      if (tail && kt * BKT + a_coff[i] >= K) src = g_zero_chunk;
+      dma16(src, as + (wave + i * NW) * RPI * BKT);
+    }
+  };
+  auto issue_b = [&](int kt) {
+    bf16_t* bs = b_slot(kt);
+    const bool tail = k_ragged && kt == KT - 1;
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+      const void* src = b_src[i] + kt * BKT;
+      if (tail && kt * BKT + b_coff[i] >= K) src = g_zero_chunk;
+      dma16(src, bs + (wave + i * NW) * RPI * BKT);
+    }
+  };
+
+  floatx16_t acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
+
+  // prologue
+  if (HR) {
+    issue_a(0);
+    issue_b(0);
+    if (KT > 1) issue_a(1);
+  } else {
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st)
+      if (st < KT) { issue_a(st); issue_b(st); }
+  }
+
+  // One K tile: wait for it, multiply it and, in between the MFMAs of its first sub-step, issue the
+  // loads that run ahead.  AHEAD is a compile-time count of what is still to be fetched, so the issue is
+  // straight-line code the scheduler can interleave with the MFMAs:
+  //   whole-tile ring: 1 = fetch tile kt+STAGES-1, 0 = nothing left
+  //   half-tile ring : 2 = fetch B(kt+1) and A(kt+2), 1 = fetch B(kt+1) only, 0 = last tile
+  auto k_tile = [&](int kt, auto ahead_tag) {
+    constexpr int AHEAD = decltype(ahead_tag)::value;
+    if (HR) {
+      if (AHEAD >= 1) wait_vmcnt<A_CH>();            // A(kt+1) may still be in flight; A(kt), B(kt) are older
+      else wait_vmcnt<0>();
+    } else {
+      if (AHEAD >= 1) wait_vmcnt<HR ? 0 : (STAGES - 2) * LPT>();
+      else wait_vmcnt<0>();
+    }
+    __syncthreads();                                 // all lanes' parts landed; the slots of tile kt-1 are free
+    const bf16_t* as = a_slot(kt);
+    const bf16_t* bs = b_slot(kt);
+    // fragments of sub-step ks+1 are read from LDS while the MFMAs of sub-step ks run (two register sets)
+    bf16x8_t af[2][MI], bfr[2][NI];
+    auto load_frags = [&](int ks, bf16x8_t (&fa)[MI], bf16x8_t (&fb)[NI]) {
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+        fa[mi] = *reinterpret_cast<const bf16x8_t*>(as + lds_off_t<BKT>(wm * TM + mi * 32 + l32, ks * 2 + lh));
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        fb[ni] = *reinterpret_cast<const bf16x8_t*>(bs + lds_off_t<BKT>(wn * TN + ni * 32 + l32, ks * 2 + lh));
+    };
+    if (!(p.dbg & 4)) load_frags(0, af[0], bfr[0]);
+#pragma unroll
+    for (int ks = 0; ks < BKT / 16; ++ks) {
+      const int cur = ks & 1;
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 1 < BKT / 16 && !(p.dbg & 4)) load_frags(ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (AHEAD >= 1 && !(p.dbg & 1)) {
+        if (HR) {                                    // spread over the K step: B half early, A half later
+          if (ks == 0) issue_b(kt + 1);
+          if (ks == (BKT / 16) / 2 && AHEAD >= 2) issue_a(kt + 2);
+        } else if (ks == 0) {
+          issue_a(kt + STAGES - 1);
+          issue_b(kt + STAGES - 1);
+        }
+      }
+      if (p.dbg & 2) continue;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mi], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
+      if (AHEAD >= 1 && (ks == 0 || (HR && AHEAD >= 2 && ks == (BKT / 16) / 2))) {
+        constexpr int N_LD = HR ? (A_CH > B_CH ? A_CH : B_CH) : LPT;
+        constexpr int PER = (N_LD + MI * NI - 1) / (MI * NI);
+#pragma unroll
+        for (int i = 0; i < MI * NI; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x020, PER, 0);    // then PER global->LDS loads
+        }
+      }
+    }
+  };
+  if (p.tstamps) ts1 = __builtin_amdgcn_s_memtime();
+  int kt = 0;
+  if (HR) {
+    for (; kt + 2 < KT; ++kt) k_tile(kt, std::integral_constant<int, 2>{});
+    for (; kt + 1 < KT; ++kt) k_tile(kt, std::integral_constant<int, 1>{});
+    for (; kt < KT; ++kt) k_tile(kt, std::integral_constant<int, 0>{});
+  } else {
+    const int kt_steady = KT - ((HR ? 2 : STAGES) - 1);    // tiles after this one have nothing left to prefetch
+    for (; kt < kt_steady; ++kt) k_tile(kt, std::integral_constant<int, 1>{});
+    for (; kt < KT; ++kt) k_tile(kt, std::integral_constant<int, 0>{});
+  }
+
+  // ---- epilogue: through LDS, so that global stores are 16-byte vectors along the rows ----
+  // Each wave stages 32 rows of its tile at a time in a private LDS strip (row stride padded by 16 bytes
+  // against bank conflicts), then every lane copies 16-byte pieces of rows out to global memory.
+  constexpr int TNO = (MODE == 1) ? TN / 2 : TN;          // output columns of a wave tile
+  constexpr int LDO = TNO + 8;                            // strip row stride in elements
+  constexpr int CPRO = TNO / 8;                           // 16-byte pieces per strip row
+  static_assert(NW * 32 * LDO <= RING_ELEMS, "epilogue strip must fit in the tile ring");
+  __syncthreads();                                        // every wave is done reading the last tile
+  if (p.tstamps) ts2 = __builtin_amdgcn_s_memtime();
+  bf16_t* strip = smem + wave * 32 * LDO;
+  const int out_col0 = (MODE == 1) ? (nt * BN + wn * TN) / 2 : nt * BN + wn * TN;
+  const int out_cols = (MODE == 1) ? wp : p.d;
+  bf16_t* out_base = (MODE == 1) ? p.C + hoff : p.C + (int64_t)seg0 * p.d;
+  const int64_t out_ld = (MODE == 1) ? wp : p.d;
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int rr = (i / 4) * 8 + lh * 4 + (i % 4);
+      if (MODE == 1) {
+#pragma unroll
+        for (int pi = 0; pi < NI / 2; ++pi) {
+          const float gt = acc[mi][2 * pi][i], up = acc[mi][2 * pi + 1][i];
+          // Swish(g) * u with the hardware exponential: the result is rounded to bf16 right after
+          const float sg = gt * __frcp_rn(1.0f + __expf(-gt));
+          strip[rr * LDO + pi * 32 + l32] = f32_to_bf16(sg * up);
+        }
+      } else {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) strip[rr * LDO + ni * 32 + l32] = f32_to_bf16(acc[mi][ni][i]);
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // the strip is private to this wave: no barrier
+#pragma unroll
+    for (int q = lane; q < 32 * CPRO; q += 64) {
+      const int rr = q / CPRO, cc = q % CPRO;
+      const int r = mt * BM + wm * TM + mi * 32 + rr;
+      const int col = out_col0 + cc * 8;
+      const uint4 v = *reinterpret_cast<const uint4*>(strip + rr * LDO + cc * 8);
+      if (r < cnt && col < out_cols) *reinterpret_cast<uint4*>(out_base + (int64_t)r * out_ld + col) = v;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // reads done before the strip is overwritten
+  }
+  if (p.tstamps && tid == 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    unsigned long long* o = p.tstamps + (size_t)blockIdx.x * 8;
+    o[0] = ts0; o[1] = ts1; o[2] = ts2; o[3] = __builtin_amdgcn_s_memtime(); o[4] = tw0; o[5] = wall_clock64();
+    o[6] = (unsigned long long)wid; o[7] = (unsigned long long)KT;
+  }
+}
+
 // ---- tile configurations ---------------------------------------------------------------------
-struct TileCfg { int bm, bn, wgm, wgn; };
+struct TileCfg { int bm, bn, wgm, wgn, stages, bk; };   // stages 0: register-staged loads, >= 2: LDS-DMA ring
 static const TileCfg kCfgs[] = {
-    {256, 128, 2, 2},   // 0
-    {128, 128, 2, 2},   // 1
-    {256, 256, 2, 4},   // 2
-    {256, 128, 4, 2},   // 3
-    {128, 256, 2, 2},   // 4
+    {256, 128, 2, 2, 0, 64},   // 0
+    {128, 128, 2, 2, 0, 64},   // 1
+    {256, 256, 2, 4, 0, 64},   // 2
+    {256, 128, 4, 2, 0, 64},   // 3
+    {128, 256, 2, 2, 0, 64},   // 4
+    {256, 256, 2, 4, 2, 64},   // 5
+    {256, 128, 2, 2, 3, 64},   // 6
+    {128, 128, 2, 2, 4, 64},   // 7
+    {256, 128, 4, 2, 3, 64},   // 8
+    {128, 128, 2, 2, 2, 64},   // 9
+    {128, 256, 2, 4, 3, 64},   // 10
+    {256, 256, 2, 4, 4, 32},   // 11
+    {256, 256, 2, 4, 3, 32},   // 12
+    {256, 128, 4, 2, 4, 32},   // 13
+    {128, 128, 2, 2, 4, 32},   // 14
+    {256, 256, 4, 2, 4, 32},   // 15
+    {256, 256, 2, 2, 2, 64},   // 16: four waves of 128x128
+    {128, 256, 2, 2, 3, 64},   // 17: four waves of 64x128, three stages
+    {256, 256, 2, 4, -1, 64},  // 18: ring of five half tiles
+    {128, 128, 2, 2, -1, 64},  // 19: ring of five half tiles, two workgroups per CU
+    {256, 256, 2, 2, -1, 64},  // 20: half-tile ring, four waves of 128x128
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -226,8 +549,11 @@ static int env_int(const char* name, int dflt) {
 // The environment is read at every call (a getenv is nothing next to a kernel launch) so that a tuning
 // script can switch tile shapes inside one process.
 static int cfg_index(int which) {
-  int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", 0);
-  if (c < 0 || c >= kNumCfgs) c = 0;
+  // defaults: 256x256 tiles on the half-tile ring for the long-K gate/up contraction, 128x128 tiles
+  // (two workgroups per CU) for the short-K, many-tile down contraction
+  const int dflt = which == 1 ? 18 : 9;
+  int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", dflt);
+  if (c < 0 || c >= kNumCfgs) c = dflt;
   return c;
 }
 
@@ -241,19 +567,30 @@ int bf16_gemm_tile(int which) {
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
-static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
-  constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(bf16_t);
-  static bool attr_done = false;
-  auto kern = grouped_gemm_bf16<BM, BN, WGM, WGN, MODE>;
+template <typename K>
+static hipError_t launch_kernel(K kern, size_t smem, int threads, bool& attr_done, const GemmArgs& a, hipStream_t s) {
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.n_blocks), dim3(WGM * WGN * 64), smem, s, a);
+  hipLaunchKernelGGL(kern, dim3(a.n_blocks), dim3(threads), smem, s, a);
   return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN, int MODE>
+static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
+  static bool attr_done = false;
+  return launch_kernel(grouped_gemm_bf16<BM, BN, WGM, WGN, MODE>, 2 * (size_t)(BM + BN) * BK * sizeof(bf16_t),
+                       WGM * WGN * 64, attr_done, a, s);
+}
+
+template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE>
+static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
+  static bool attr_done = false;
+  constexpr size_t smem = (STAGES == 0 ? 5 * (size_t)(BM > BN ? BM : BN) : STAGES * (size_t)(BM + BN)) * BKT * sizeof(bf16_t);
+  return launch_kernel(grouped_gemm_bf16_dma<BM, BN, BKT, STAGES, WGM, WGN, MODE>, smem, WGM * WGN * 64, attr_done, a, s);
 }
 
 template <int MODE>
@@ -263,7 +600,23 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
     case 1: return launch_one<128, 128, 2, 2, MODE>(a, s);
     case 2: return launch_one<256, 256, 2, 4, MODE>(a, s);
     case 3: return launch_one<256, 128, 4, 2, MODE>(a, s);
-    default: return launch_one<128, 256, 2, 2, MODE>(a, s);
+    case 4: return launch_one<128, 256, 2, 2, MODE>(a, s);
+    case 5: return launch_dma<256, 256, 64, 2, 2, 4, MODE>(a, s);
+    case 6: return launch_dma<256, 128, 64, 3, 2, 2, MODE>(a, s);
+    case 7: return launch_dma<128, 128, 64, 4, 2, 2, MODE>(a, s);
+    case 8: return launch_dma<256, 128, 64, 3, 4, 2, MODE>(a, s);
+    case 9: return launch_dma<128, 128, 64, 2, 2, 2, MODE>(a, s);
+    case 10: return launch_dma<128, 256, 64, 3, 2, 4, MODE>(a, s);
+    case 11: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
+    case 12: return launch_dma<256, 256, 32, 3, 2, 4, MODE>(a, s);
+    case 13: return launch_dma<256, 128, 32, 4, 4, 2, MODE>(a, s);
+    case 14: return launch_dma<128, 128, 32, 4, 2, 2, MODE>(a, s);
+    case 15: return launch_dma<256, 256, 32, 4, 4, 2, MODE>(a, s);
+    case 16: return launch_dma<256, 256, 64, 2, 2, 2, MODE>(a, s);
+    case 17: return launch_dma<128, 256, 64, 3, 2, 2, MODE>(a, s);
+    case 18: return launch_dma<256, 256, 64, 0, 2, 4, MODE>(a, s);
+    case 19: return launch_dma<128, 128, 64, 0, 2, 2, MODE>(a, s);
+    default: return launch_dma<256, 256, 64, 0, 2, 2, MODE>(a, s);
   }
 }
 
@@ -276,9 +629,13 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.h_off = reinterpret_cast<const int64_t*>(ws + L.h_off);
   a.G = e.G;
   a.d = e.d;
+  a.ldb = e.ldw1;
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.xcd_remap = remap;
+  a.dbg = env_int("CMOE_GEMM_DBG", 0);
+  a.tstamps = nullptr;
+  if (const char* tp = std::getenv("CMOE_GEMM_TSTAMPS")) a.tstamps = reinterpret_cast<unsigned long long*>(std::strtoull(tp, nullptr, 0));
   // gate/up
   a.A = static_cast<const bf16_t*>(x);
   a.B = static_cast<const bf16_t*>(e.w1);

@@ -20,6 +20,7 @@ struct SimtArgs {
   const int32_t* slot2tok;
   int G;
   int d;
+  int ldb;
   int64_t T_tokens;
   int single;
 };
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_simt(SimtArgs<T> p) {
   }
   int bn = nt * SB + lrow;
   if (bn >= n_cols) bn = n_cols - 1;
-  const T* b_src = (MODE == 1) ? p.B + ((int64_t)p.groups[g].w1_row0 + bn) * p.d
+  const T* b_src = (MODE == 1) ? p.B + ((int64_t)p.groups[g].w1_row0 + bn) * p.ldb
                                : p.B + p.groups[g].w2_off + (int64_t)bn * wp;
   // columns owned by this thread inside the 64-wide tile
   int cols[4];
@@ -138,6 +139,7 @@ static hipError_t run_simt(const Engine& e, const void* x, int64_t Tn, char* ws,
   a.h_off = reinterpret_cast<const int64_t*>(ws + L.h_off);
   a.G = e.G;
   a.d = e.d;
+  a.ldb = e.ldw1;
   a.T_tokens = Tn;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.A = static_cast<const T*>(x);

@@ -32,9 +32,10 @@ void parallel_for(int64_t n, const std::function<void(int64_t)>& fn, int max_thr
 struct PackedSet {
   int dtype = 1;
   int d = 0;
+  int ld = 0;                       // row stride of w1 in elements (w1_row_stride(d))
   std::vector<GroupDev> groups;     // offsets relative to this set's own W1 / W2
   std::vector<int> width;           // real neuron count per group
-  std::vector<uint8_t> w1;          // [rows][d] interleaved gate/up rows
+  std::vector<uint8_t> w1;          // [rows][ld] interleaved gate/up rows
   std::vector<uint8_t> w2;          // per group [d][width_pad]
   int64_t w1_rows = 0;
   int64_t w2_elems = 0;

@@ -31,11 +31,13 @@ struct PlaceArgs {
   int64_t T;
   int G, n_always, S_dyn, n_tiles;
   int bm1, bn1, bm2, bn2, d;   // tile sizes of the grouped GEMMs (bn1 in packed gate/up rows)
+  int decode;                  // 1: the work lists count decode units (16 neurons / 16 output columns per unit)
 };
 
 __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
   __shared__ int32_t base[MAX_GROUPS];      // next free slot of each group for this tile
   __shared__ int32_t total[MAX_GROUPS];
+  __shared__ int32_t wpad[MAX_GROUPS];      // padded widths (read once, in parallel)
   const int lane = threadIdx.x;
   const int tile = blockIdx.x;
   const int S_all = p.n_always + p.S_dyn;
@@ -47,7 +49,19 @@ __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
         tot = (int)p.T;
         prev = 0;
       } else {
-        for (int i = 0; i < p.n_tiles; ++i) {
+        // independent loads, eight in flight at a time (the compiler does not batch them by itself)
+        int i = 0;
+        for (; i + 8 <= p.n_tiles; i += 8) {
+          int c[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) c[k] = p.tile_counts[(int64_t)(i + k) * p.G + g];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            tot += c[k];
+            prev += (i + k < tile) ? c[k] : 0;
+          }
+        }
+        for (; i < p.n_tiles; ++i) {
           const int c = p.tile_counts[(int64_t)i * p.G + g];
           tot += c;
           prev += (i < tile) ? c : 0;
@@ -56,6 +70,7 @@ __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
     }
     total[g] = tot;
     base[g] = prev;
+    wpad[g] = (g < p.G) ? p.groups[g].width_pad : 0;
   }
   __syncthreads();
   // exclusive scan over groups (G <= 128: a serial pass by lane 0 is a few hundred cycles)
@@ -64,7 +79,7 @@ __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
     int64_t h = 0;
     for (int g = 0; g < p.G; ++g) {
       const int cnt = total[g];
-      const int wp = p.groups[g].width_pad;
+      const int wp = wpad[g];
       base[g] += run;
       if (tile == 0) {
         p.seg_off[g] = run;
@@ -75,8 +90,13 @@ __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
         if (p.counts_out && g >= p.n_always) p.counts_out[g - p.n_always] = cnt;
       }
       run += cnt;
-      w1 += cdiv(cnt, p.bm1) * cdiv(2 * wp, p.bn1);
-      w2 += cdiv(cnt, p.bm2) * cdiv(p.d, p.bn2);
+      if (p.decode) {
+        w1 += cnt > 0 ? wp / 16 : 0;
+        w2 += cnt > 0 ? p.d / 16 : 0;
+      } else {
+        w1 += cdiv(cnt, p.bm1) * cdiv(2 * wp, p.bn1);
+        w2 += cdiv(cnt, p.bm2) * cdiv(p.d, p.bn2);
+      }
       h += (int64_t)cnt * wp;
     }
     if (tile == 0) {
@@ -97,14 +117,25 @@ __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
       p.tok2slot[t * S_all + a] = slot;
       p.slot_w[t * S_all + a] = 1.0f;
     }
+  // this token's routed entries, loaded up front so that no load sits inside the group loop below
   int my_g[MAX_DYN];
+  float my_w[MAX_DYN];
 #pragma unroll
-  for (int i = 0; i < MAX_DYN; ++i) my_g[i] = (valid && i < p.S_dyn) ? p.sel_group[t * p.S_dyn + i] : -1;
+  for (int i = 0; i < MAX_DYN; ++i) {
+    const bool ok = valid && i < p.S_dyn;
+    my_g[i] = ok ? p.sel_group[t * p.S_dyn + i] : -1;
+    my_w[i] = ok ? p.sel_weight[t * p.S_dyn + i] : 0.0f;
+  }
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   for (int g = p.n_always; g < p.G; ++g) {
     int hit = -1;
+    float hit_w = 0.0f;
 #pragma unroll
-    for (int i = 0; i < MAX_DYN; ++i) hit = (my_g[i] == g) ? i : hit;
+    for (int i = 0; i < MAX_DYN; ++i) {
+      const bool m = my_g[i] == g;
+      hit = m ? i : hit;
+      hit_w = m ? my_w[i] : hit_w;
+    }
     const uint64_t mask = __ballot(hit >= 0);
     if (mask == 0ull) continue;
     const int b = base[g];
@@ -112,7 +143,7 @@ __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
       const int slot = b + __popcll(mask & lt_mask);
       p.slot2tok[slot] = (int)t;
       p.tok2slot[t * S_all + p.n_always + hit] = slot;
-      p.slot_w[t * S_all + p.n_always + hit] = p.sel_weight[t * p.S_dyn + hit];
+      p.slot_w[t * S_all + p.n_always + hit] = hit_w;
     }
   }
 }
@@ -144,6 +175,7 @@ hipError_t launch_permute(const Engine& e, int64_t T, char* ws, const WsLayout& 
   p.bm2 = gemm_tile(e.dtype, 2);
   p.bn2 = gemm_tile(e.dtype, 4);
   p.d = e.d;
+  p.decode = (!use_simt_experts(e.dtype) && decode_path_ok(e, T)) ? 1 : 0;
   hipLaunchKernelGGL(place_kernel, dim3(L.n_tok_tiles), dim3(64), 0, s, p);
   return hipGetLastError();
 }

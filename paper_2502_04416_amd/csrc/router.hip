@@ -1,8 +1,9 @@
 // Router scoring (Eq. 8), wavefront-level top-N_k selection and the gate of Eq. 9, for flat layers
 // and for the two-level hierarchy of Sec. 4.4.  Two scoring kernels feed the same selection code:
 //   router_simt_kernel  one token per workgroup, fp32 FMA dot products (fp32 layers, decode batches)
-//   router_mfma_kernel  a 64-token tile per workgroup, bf16 MFMA with the K range split over the
-//                       four waves (prefill batches); also emits the tile's per-group histogram
+//   router_gemm_kernel  bf16 MFMA partial products over (32-token tile, K slice) workgroups, followed by
+//                       route_tile_kernel, which sums the slices in order, selects, and emits each
+//                       64-token tile's per-group histogram (prefill batches)
 #include "cmoe_internal.h"
 #include "device_utils.h"
 
@@ -108,6 +109,109 @@ __device__ __forceinline__ void route_token(const RouterDev& r, const RouteIO& i
   }
 }
 
+// ---- lane-per-token routing (prefill tiles) -------------------------------------------------------
+// The cross-lane arg-max above costs a chain of dependent lane exchanges per token, which is what a
+// single decode token wants but is slow when one wave has to route many tokens in turn.  Here every
+// lane of the wave routes its own token with plain loops over the (at most 64) scores of that token's
+// row in LDS, so 64 tokens are selected at once.  Same semantics: descending key, ties to the lowest id.
+struct LaneSel {
+  int n;                   // entries written so far
+};
+
+__device__ __forceinline__ void lane_select_routed(const RouterDev& r, const RouteIO& io, const float* sc, int lo,
+                                                   int n, float scale, int group_base, int64_t t, LaneSel& st,
+                                                   int32_t* topk_ptr, int32_t* hist) {
+  float mx = -INFINITY, sum = 1.0f;
+  if (r.use_gate) {
+    for (int j = 0; j < n; ++j) mx = fmaxf(mx, r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j]);
+    sum = 0.0f;
+    for (int j = 0; j < n; ++j) sum += expf((r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j]) - mx);
+  }
+  uint64_t taken = 0ull;
+  for (int k = 0; k < r.top_k; ++k) {
+    float best = -INFINITY, best_sp = 0.0f;
+    int bj = -1;
+    for (int j = 0; j < n; ++j) {
+      const float sk = r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j];
+      float key = sk, sp = 0.0f;
+      if (r.use_gate) {
+        sp = expf(sk - mx) / sum;
+        key = sp + (io.gate_b ? io.gate_b[lo + j] : 0.0f);
+      }
+      const bool free_j = ((taken >> j) & 1ull) == 0ull;
+      if (free_j && (bj < 0 || key > best)) {
+        best = key;
+        best_sp = sp;
+        bj = j;
+      }
+    }
+    taken |= 1ull << bj;
+    float gate = 1.0f;
+    if (r.use_gate && io.gate_u) gate = 1.0f + best_sp * io.gate_u[lo + bj];
+    const int g = group_base + bj;
+    io.sel_group[t * io.S_dyn + st.n] = g;
+    io.sel_weight[t * io.S_dyn + st.n] = scale * gate;
+    if (topk_ptr) topk_ptr[k] = bj;
+    atomicAdd(&hist[g], 1);
+    ++st.n;
+  }
+}
+
+// `row` is the token's row of pre-activations in LDS; it is overwritten with the scores in place.
+__device__ __forceinline__ void route_token_lane(const RouterDev& r, const RouteIO& io, float* row, int64_t t,
+                                                 int32_t* hist) {
+  for (int j = 0; j < r.n_scored; ++j) {
+    const int blk = j / IL, c = j % IL;
+    const float g = row[blk * 2 * IL + c], u = row[blk * 2 * IL + IL + c];
+    const float s = silu_f32(g) * u;                                         // Eq. 8
+    if (io.scores_out) io.scores_out[t * r.n_scored + j] = s;
+    row[blk * 2 * IL + c] = s;
+  }
+  // compact the scores to row[0 .. n_scored): block b's scores sit at b*2*IL .. b*2*IL+IL-1
+  for (int j = IL; j < r.n_scored; ++j) row[j] = row[(j / IL) * 2 * IL + (j % IL)];
+  LaneSel st{0};
+  if (r.outer_top_k == 0) {
+    lane_select_routed(r, io, row, 0, r.n_scored, 1.0f, r.n_always, t, st,
+                       io.topk_out ? io.topk_out + t * r.top_k : nullptr, hist);
+    return;
+  }
+  const float* lin = row + r.n_sw_rows;
+  int oe[MAX_TOPK];
+  float ol[MAX_TOPK];
+  uint32_t taken = 0u;
+  for (int i = 0; i < r.outer_top_k; ++i) {
+    float best = -INFINITY;
+    int be = -1;
+    for (int e = 0; e < r.n_lin; ++e) {
+      const float l = lin[e] + (io.lin_off ? io.lin_off[e] : 0.0f);
+      if (((taken >> e) & 1u) == 0u && (be < 0 || l > best)) {
+        best = l;
+        be = e;
+      }
+    }
+    taken |= 1u << be;
+    oe[i] = be;
+    ol[i] = best;
+  }
+  float den = 0.0f;
+  for (int i = 0; i < r.outer_top_k; ++i) den += expf(ol[i] - ol[0]);
+  for (int i = 0; i < r.outer_top_k; ++i) {
+    const int e = oe[i];
+    const float w_e = expf(ol[i] - ol[0]) / den;
+    const int gbase = e * r.groups_per_outer;
+    if (io.outer_out) io.outer_out[t * r.outer_top_k + i] = e;
+    if (r.sub_has_shared) {
+      io.sel_group[t * io.S_dyn + st.n] = gbase;
+      io.sel_weight[t * io.S_dyn + st.n] = w_e;
+      atomicAdd(&hist[gbase], 1);
+      ++st.n;
+    }
+    if (r.top_k > 0)
+      lane_select_routed(r, io, row, e * r.n_r_sub, r.n_r_sub, w_e, gbase + r.sub_has_shared, t, st,
+                         io.topk_out ? io.topk_out + (t * r.outer_top_k + i) * r.top_k : nullptr, hist);
+  }
+}
+
 // Is router row `rr` one that some scored expert (or linear logit) uses?
 __device__ __forceinline__ bool router_row_used(const RouterDev& r, int rr) {
   if (rr < r.n_sw_rows) return (rr / (2 * IL)) * IL + (rr % IL) < r.n_scored;
@@ -139,74 +243,131 @@ __global__ __launch_bounds__(256) void router_simt_kernel(RouterDev r, RouteIO i
   if (wave == 0) route_token(r, io, pre, t, nullptr);
 }
 
-// ---- 64-token tile per workgroup, bf16 MFMA -------------------------------------------------
-// C[64 tokens][n_rows] = X_tile [64][d] * Wr[n_rows][d]^T.  Each of the four waves takes every fourth
-// 64-wide K chunk and multiplies straight out of global memory (no operand is shared between waves),
-// then the four partial sums are added in a fixed order through LDS.  NT = n_rows / 32 <= 5.
+// ---- prefill scoring: bf16 MFMA, split over tokens and over K ----------------------------------
+// P[ks][t][row] = X[t][K slice ks] * Wr[row][K slice ks]^T for a 32-token tile.  The grid is
+// (token tiles, K slices) so that even a 2048-token batch fills the chip; inside a workgroup each of
+// the four waves takes every fourth 64-wide chunk of the slice and multiplies straight out of global
+// memory, then the four partial sums are added in a fixed order through LDS.  NT = n_rows / 32 <= 5.
+constexpr int RT_TOK = 32;
+
 template <int NT>
-__global__ __launch_bounds__(256) void router_mfma_kernel(RouterDev r, RouteIO io, const bf16_t* __restrict__ x,
-                                                          const bf16_t* __restrict__ wr, int d, int64_t T,
-                                                          int32_t* __restrict__ tile_counts, int G) {
-  __shared__ float pre[TOK_TILE][NT * 32 + 1];
-  __shared__ int32_t hist[MAX_GROUPS];
+__global__ __launch_bounds__(256) void router_gemm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wr,
+                                                          int d, int64_t T, int k_slice, float* __restrict__ partial) {
+  __shared__ float red[RT_TOK][NT * 32 + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t t0 = (int64_t)blockIdx.x * TOK_TILE;
+  const int64_t t0 = (int64_t)blockIdx.x * RT_TOK;
+  const int ks = blockIdx.y;
   const int l32 = lane & 31, lh = lane >> 5;
-  floatx16_t acc[2][NT];
+  floatx16_t acc[NT];
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-    for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
-  const bf16_t* arow[2];
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
-    int64_t t = t0 + mi * 32 + l32;
-    if (t >= T) t = T - 1;                                   // duplicate the last token; never stored
-    arow[mi] = x + t * d + lh * 8;
-  }
+    for (int i = 0; i < 16; ++i) acc[ni][i] = 0.0f;
+  int64_t t = t0 + l32;
+  if (t >= T) t = T - 1;                                     // duplicate the last token; never stored
+  const bf16_t* arow = x + t * d + lh * 8;
   const bf16_t* brow = wr + (int64_t)l32 * d + lh * 8;
-  const int n_chunks = d / 64;                               // host guarantees d % 64 == 0
-  for (int kc = wave; kc < n_chunks; kc += 4) {
+  const int k_begin = ks * k_slice;
+  const int k_end = (k_begin + k_slice < d) ? k_begin + k_slice : d;     // host guarantees multiples of 64
+  // software pipeline over this wave's 64-wide chunks: the loads of the next chunk are issued before
+  // the MFMAs of the current one, so a wave always has a chunk of loads in flight
+  bf16x8_t a0[4], a1[4], b0[NT][4], b1[NT][4];
+  auto load_chunk = [&](int kc, bf16x8_t (&a)[4], bf16x8_t (&b)[NT][4]) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int k = kc * 64 + ks * 16;
-      bf16x8_t a[2], b[NT];
+    for (int s4 = 0; s4 < 4; ++s4) {
+      a[s4] = *reinterpret_cast<const bf16x8_t*>(arow + kc + s4 * 16);
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi) a[mi] = *reinterpret_cast<const bf16x8_t*>(arow[mi] + k);
-#pragma unroll
-      for (int ni = 0; ni < NT; ++ni) b[ni] = *reinterpret_cast<const bf16x8_t*>(brow + (int64_t)ni * 32 * d + k);
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NT; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+      for (int ni = 0; ni < NT; ++ni) b[ni][s4] = *reinterpret_cast<const bf16x8_t*>(brow + (int64_t)ni * 32 * d + kc + s4 * 16);
     }
+  };
+  auto mma_chunk = [&](bf16x8_t (&a)[4], bf16x8_t (&b)[NT][4]) {
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+      for (int ni = 0; ni < NT; ++ni) acc[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s4], b[ni][s4], acc[ni], 0, 0, 0);
+  };
+  int kc = k_begin + wave * 64;
+  if (kc < k_end) load_chunk(kc, a0, b0);
+  while (kc < k_end) {
+    if (kc + 256 < k_end) load_chunk(kc + 256, a1, b1);
+    mma_chunk(a0, b0);
+    kc += 256;
+    if (kc >= k_end) break;
+    if (kc + 256 < k_end) load_chunk(kc + 256, a0, b0);
+    mma_chunk(a1, b1);
+    kc += 256;
   }
-  // fixed-order reduction of the four K partials: wave 0 stores, waves 1..3 add in turn
   for (int wsel = 0; wsel < 4; ++wsel) {
     if (wave == wsel) {
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+      for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-        for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int row = mi * 32 + (i / 4) * 8 + lh * 4 + (i % 4);
-            const int col = ni * 32 + l32;
-            if (wsel == 0) pre[row][col] = acc[mi][ni][i];
-            else pre[row][col] += acc[mi][ni][i];
-          }
+        for (int i = 0; i < 16; ++i) {
+          const int row = (i / 4) * 8 + lh * 4 + (i % 4);
+          const int col = ni * 32 + l32;
+          if (wsel == 0) red[row][col] = acc[ni][i];
+          else red[row][col] += acc[ni][i];
+        }
     }
     __syncthreads();
   }
+  const int n_rows = NT * 32;
+  for (int i = tid; i < RT_TOK * n_rows; i += 256) {
+    const int row = i / n_rows, col = i - row * n_rows;
+    if (t0 + row < T) partial[((int64_t)ks * T + t0 + row) * n_rows + col] = red[row][col];
+  }
+}
+
+// Sum the K-slice partials in slice order, then score, select and histogram a 64-token tile: the
+// 256 threads load and add the partials, then wave 0 routes the tile with one token per lane.
+__global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io, const float* __restrict__ partial,
+                                                         int n_slices, int64_t T, int32_t* __restrict__ tile_counts,
+                                                         int G) {
+  extern __shared__ float pre[];                 // [TOK_TILE][n_rows + 1]
+  __shared__ int32_t hist[MAX_GROUPS];
+  const int tid = threadIdx.x;
+  const int n_rows = r.n_sw_rows + r.n_lin_rows;
+  const int ld = n_rows + 1;
+  const int64_t t0 = (int64_t)blockIdx.x * TOK_TILE;
+  // n_rows is a multiple of 32: float4 loads, all slices of up to four vectors in flight together
+  const int vec_per_row = n_rows >> 2;
+  const int n_vec = TOK_TILE * vec_per_row;
+  for (int i0 = tid; i0 < n_vec; i0 += 4 * 256) {
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int ks0 = 0; ks0 < n_slices; ks0 += 4) {
+      float4 ld4[4][4];                      // [slice][vector]: sixteen loads in flight, added in slice order
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + u * 256;
+          const int row = i / vec_per_row, cv = i - row * vec_per_row;
+          ld4[q][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (ks0 + q < n_slices && i < n_vec && t0 + row < T)
+            ld4[q][u] = *reinterpret_cast<const float4*>(partial + ((int64_t)(ks0 + q) * T + t0 + row) * n_rows + cv * 4);
+        }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          v[u].x += ld4[q][u].x; v[u].y += ld4[q][u].y; v[u].z += ld4[q][u].z; v[u].w += ld4[q][u].w;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * 256;
+      if (i < n_vec) {
+        const int row = i / vec_per_row, cv = i - row * vec_per_row;
+        float* dst = pre + row * ld + cv * 4;
+        dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
+      }
+    }
+  }
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
-  for (int i = wave; i < TOK_TILE; i += 4) {
-    const int64_t t = t0 + i;
-    if (t < T) route_token(r, io, &pre[i][0], t, hist);
-  }
+  if (tid < TOK_TILE && t0 + tid < T) route_token_lane(r, io, pre + tid * ld, t0 + tid, hist);
   __syncthreads();
   for (int g = tid; g < G; g += 256) tile_counts[(int64_t)blockIdx.x * G + g] = hist[g];
 }
@@ -240,18 +401,30 @@ hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, co
   io.S_dyn = e.S_dyn;
   int32_t* tile_counts = reinterpret_cast<int32_t*>(ws + L.tile_counts);
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
-  const bool mfma = e.dtype == 1 && T >= 64 && e.d % 64 == 0 && n_rows % 32 == 0 && n_rows / 32 <= 5;
+  const bool mfma = e.dtype == 1 && e.d % 256 == 0 && n_rows % 32 == 0 && n_rows / 32 <= 5;
   if (mfma) {
-    dim3 grid(L.n_tok_tiles), block(256);
+    // K slices: enough workgroups to fill 256 CUs, at least 256 of K per slice, at most the partial buffer's 8
+    const int n_tt = (int)((T + RT_TOK - 1) / RT_TOK);
+    int n_slices = (512 + n_tt - 1) / n_tt;
+    if (n_slices > 8) n_slices = 8;
+    while (n_slices > 1 && (e.d % (n_slices * 256) != 0)) --n_slices;
+    const int k_slice = e.d / n_slices;
+    float* partial = reinterpret_cast<float*>(ws + L.scores);
+    dim3 grid(n_tt, n_slices), block(256);
     const bf16_t* xx = static_cast<const bf16_t*>(x);
     const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
     switch (n_rows / 32) {
-      case 1: hipLaunchKernelGGL(router_mfma_kernel<1>, grid, block, 0, s, e.r, io, xx, ww, e.d, T, tile_counts, e.G); break;
-      case 2: hipLaunchKernelGGL(router_mfma_kernel<2>, grid, block, 0, s, e.r, io, xx, ww, e.d, T, tile_counts, e.G); break;
-      case 3: hipLaunchKernelGGL(router_mfma_kernel<3>, grid, block, 0, s, e.r, io, xx, ww, e.d, T, tile_counts, e.G); break;
-      case 4: hipLaunchKernelGGL(router_mfma_kernel<4>, grid, block, 0, s, e.r, io, xx, ww, e.d, T, tile_counts, e.G); break;
-      default: hipLaunchKernelGGL(router_mfma_kernel<5>, grid, block, 0, s, e.r, io, xx, ww, e.d, T, tile_counts, e.G); break;
+      case 1: hipLaunchKernelGGL(router_gemm_kernel<1>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+      case 2: hipLaunchKernelGGL(router_gemm_kernel<2>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+      case 3: hipLaunchKernelGGL(router_gemm_kernel<3>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+      case 4: hipLaunchKernelGGL(router_gemm_kernel<4>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+      default: hipLaunchKernelGGL(router_gemm_kernel<5>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
     }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const size_t smem = sizeof(float) * (size_t)TOK_TILE * (n_rows + 1);
+    hipLaunchKernelGGL(route_tile_kernel, dim3(L.n_tok_tiles), dim3(256), smem, s, e.r, io, partial, n_slices, T,
+                       tile_counts, e.G);
     return hipGetLastError();
   }
   const size_t smem = sizeof(float) * (size_t)(e.d + n_rows);
