@@ -6,6 +6,7 @@
 //                       64-token tile's per-group histogram (prefill batches)
 #include "cmoe_internal.h"
 #include "device_utils.h"
+#include "place_device.h"
 
 namespace cmoe {
 
@@ -372,6 +373,93 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
   for (int g = tid; g < G; g += 256) tile_counts[(int64_t)blockIdx.x * G + g] = hist[g];
 }
 
+// ---- decode front end: scoring, selection and permutation in one launch ---------------------------
+// For batches of at most 32 tokens the three steps are latency, not throughput, so they share one kernel.
+// Every workgroup scores 16 router rows for all tokens (v_mfma_f32_16x16x32_bf16, router rows as the A
+// operand, K split over the 8 waves, partials added in order through LDS) and publishes the 16 x T
+// pre-activations.  The workgroup that arrives last at a device-wide counter (no waiting: everybody else
+// simply exits) then routes every token, one per lane, and places the single 64-token tile.  The counter
+// lives in library-owned device memory, is zero between calls and is reset by the last workgroup.
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+template <int NTT, int KSTEPS>
+__global__ __launch_bounds__(512) void decode_front_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
+                                                           const bf16_t* __restrict__ x,
+                                                           const bf16_t* __restrict__ wr, int d, int T,
+                                                           float* __restrict__ pre_g, int32_t* __restrict__ counter) {
+  __shared__ float red[8][NTT][16][17];
+  __shared__ int32_t hist[MAX_GROUPS];
+  __shared__ int last_flag;
+  extern __shared__ float pre[];                 // [T][n_rows + 1], only used by the last workgroup
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int n_rows = r.n_sw_rows + r.n_lin_rows;
+  const int row0 = blockIdx.x * 16;
+  const int kbase = wave * (KSTEPS * 32) + kq * 8;
+  const bf16_t* wrow = wr + (int64_t)(row0 + r16) * d + kbase;
+  floatx4_t acc[NTT];
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[tt][i] = 0.0f;
+  bf16x8_t a[KSTEPS];
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) a[ks] = *reinterpret_cast<const bf16x8_t*>(wrow + ks * 32);
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt) {
+    const int col = tt * 16 + r16;
+    const bool ok = col < T;
+    const bf16_t* xr = x + (int64_t)(ok ? col : 0) * d + kbase;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      bf16x8_t b;
+      if (ok) b = *reinterpret_cast<const bf16x8_t*>(xr + ks * 32);
+      else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b[i] = (__bf16)0.0f;
+      }
+      acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], b, acc[tt], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int tt = 0; tt < NTT; ++tt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[wave][tt][kq * 4 + i][r16] = acc[tt][i];
+  __syncthreads();
+  for (int e = tid; e < NTT * 256; e += 512) {
+    const int tt = e >> 8, tok = (e >> 4) & 15, rr = e & 15;
+    const int col = tt * 16 + tok;
+    if (col >= T) continue;
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) v += red[w][tt][rr][tok];
+    pre_g[(int64_t)col * n_rows + row0 + rr] = v;
+  }
+  // publish, then count arrivals
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const int old = atomicAdd(counter, 1);
+    last_flag = (old == (int)gridDim.x - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!last_flag) return;
+  __threadfence();
+  const int ld = n_rows + 1;
+  for (int i = tid; i < T * n_rows; i += 512) {
+    const int row = i / n_rows, col = i - row * n_rows;
+    pre[row * ld + col] = __hip_atomic_load(pre_g + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  for (int i = tid; i < MAX_GROUPS; i += 512) hist[i] = 0;
+  if (tid == 0) *counter = 0;                    // ready for the next call
+  __syncthreads();
+  if (wave == 0) {
+    if (lane < T) route_token_lane(r, io, pre + lane * ld, lane, hist);
+    wave_lds_sync();
+    place_tile(pl, 0, hist, lane);
+  }
+}
+
 // Per-tile histogram of the routed entries (used when the scoring kernel did not produce one).
 __global__ __launch_bounds__(64) void tile_count_kernel(const int32_t* __restrict__ sel_group, int64_t T, int S_dyn,
                                                         int G, int32_t* __restrict__ tile_counts) {
@@ -384,6 +472,56 @@ __global__ __launch_bounds__(64) void tile_count_kernel(const int32_t* __restric
     for (int i = 0; i < S_dyn; ++i) atomicAdd(&hist[sel_group[t * S_dyn + i]], 1);
   __syncthreads();
   for (int g = lane; g < G; g += 64) tile_counts[(int64_t)blockIdx.x * G + g] = hist[g];
+}
+
+PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& L, int32_t* counts_out);
+
+bool decode_front_ok(const Engine& e, int64_t T) {
+  const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
+  return e.S_dyn > 0 && e.counters != nullptr && decode_path_ok(e, T) && n_rows % 16 == 0;
+}
+
+// Router scoring + selection + permutation of a decode batch in one kernel (see decode_front_kernel).
+hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
+                               int32_t* topk_out, int32_t* outer_out, float* scores_out, int32_t* counts_out,
+                               hipStream_t s) {
+  RouteIO io;
+  io.sel_group = reinterpret_cast<int32_t*>(ws + L.sel_group);
+  io.sel_weight = reinterpret_cast<float*>(ws + L.sel_weight);
+  io.topk_out = topk_out;
+  io.outer_out = outer_out;
+  io.scores_out = scores_out;
+  io.gate_u = e.gate_u;
+  io.gate_b = e.gate_b;
+  io.lin_off = e.lin_off;
+  io.S_dyn = e.S_dyn;
+  const PlaceArgs pl = make_place_args(e, T, ws, L, counts_out);
+  const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
+  float* pre_g = reinterpret_cast<float*>(ws + L.scores);
+  const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1);
+  dim3 grid(n_rows / 16), block(512);
+  const bf16_t* xx = static_cast<const bf16_t*>(x);
+  const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
+  const int ksteps = e.d / 256;
+  const int Ti = (int)T;
+#define CMOE_FRONT(NTT, KS) hipLaunchKernelGGL((decode_front_kernel<NTT, KS>), grid, block, smem, s, e.r, io, pl, xx, ww, e.d, Ti, pre_g, e.counters)
+  if (T <= 16) {
+    switch (ksteps) {
+      case 16: CMOE_FRONT(1, 16); break;
+      case 8: CMOE_FRONT(1, 8); break;
+      case 4: CMOE_FRONT(1, 4); break;
+      default: CMOE_FRONT(1, 2); break;
+    }
+  } else {
+    switch (ksteps) {
+      case 16: CMOE_FRONT(2, 16); break;
+      case 8: CMOE_FRONT(2, 8); break;
+      case 4: CMOE_FRONT(2, 4); break;
+      default: CMOE_FRONT(2, 2); break;
+    }
+  }
+#undef CMOE_FRONT
+  return hipGetLastError();
 }
 
 hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,

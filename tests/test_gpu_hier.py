@@ -81,6 +81,21 @@ def test_hier_small(binding):
     hier.close()
 
 
+@pytest.mark.parametrize("T", [1, 7, 20, 32, 33])
+def test_hier_decode_batches(binding, T):
+    """Small batches take the fused decode kernels (one launch scores, selects and permutes; the down
+    kernel also combines); 33 tokens is the first size back on the tiled path."""
+    cfg = synth.scaled(synth.CONFIGS[4], d_model=512, d_ff=1408, n_experts=8, n_shared=2, top_k=2, n_outer=4,
+                       outer_top_k=2, n_centres=16)
+    hier, experts, w_router, offsets = _make(binding, cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    for rep_i in range(2):                      # twice: the arrival counters must come back to zero
+        out = hier.forward(x)
+        rep = _check(cfg, experts, w_router, offsets, x, out, hier.dense_forward(x), np.arange(T))
+    print("\n[parity] hier decode T=%d: %s" % (T, rep), flush=True)
+    hier.close()
+
+
 def test_hier_all_subexperts_active_equals_dense_layer(binding):
     cfg = synth.scaled(synth.CONFIGS[4], d_model=256, d_ff=1024, n_experts=8, n_shared=2, top_k=6, n_outer=3,
                        outer_top_k=2, n_centres=8)

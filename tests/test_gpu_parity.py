@@ -164,6 +164,26 @@ def test_small_bf16(binding, name, d, d_ff, N, N_s, N_k, T):
     layer.close()
 
 
+@pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 31, 32, 33, 64])
+def test_small_bf16_decode_sizes(binding, T):
+    """Every batch size around the decode/tiled switch (32) and the 16-token MFMA tile, run twice so that
+    the self-resetting arrival counters of the fused decode kernels are exercised."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    u, b = synth.make_gate_params(cfg)
+    layer = _layer(binding, cfg, weights, part)
+    out1 = layer.forward(x)
+    check_flat(cfg, weights, part, x, out1)
+    out2 = layer.forward(x)
+    assert np.array_equal(out1["y"], out2["y"]) and np.array_equal(out1["topk"], out2["topk"])
+    layer.set_gate_params(u, b)
+    _say("small decode T=%d gate" % T, check_flat(cfg, weights, part, x, layer.forward(x), u=u, b=b))
+    check_dense(cfg, weights, x, layer.dense_forward(x))
+    layer.close()
+
+
 def test_small_bf16_gate_params(binding):
     cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
     weights = synth.make_weights(cfg)
