@@ -438,7 +438,7 @@ int cmoe_set_gate_params(cmoe_layer* L, const float* u, const float* b) {
 }
 
 // device buffer of a flat layer: [moe W1][moe W2][dense W1][dense W2][router][moe groups][dense groups][u][b]
-struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, ctr, total; };
+struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, total; };
 static FlatOffsets flat_offsets(const cmoe_layer* L) {
   FlatOffsets o{};
   size_t off = 0;
@@ -452,7 +452,6 @@ static FlatOffsets flat_offsets(const cmoe_layer* L) {
   o.dg = take(sizeof(GroupDev) * L->dense.groups.size());
   o.u = take(sizeof(float) * L->n_r);
   o.b = take(sizeof(float) * L->n_r);
-  o.ctr = take(sizeof(int32_t) * N_COUNTERS);
   o.total = off;
   return o;
 }
@@ -485,11 +484,9 @@ int cmoe_upload(cmoe_layer* L, void* dev_weights, void* hip_stream) {
   if (e == hipSuccess) e = h2d(base + o.dg, L->dense.groups.data(), sizeof(GroupDev) * L->dense.groups.size(), s);
   if (e == hipSuccess) e = h2d(base + o.u, L->u.data(), sizeof(float) * L->n_r, s);
   if (e == hipSuccess) e = h2d(base + o.b, L->b.data(), sizeof(float) * L->n_r, s);
-  if (e == hipSuccess) e = hipMemsetAsync(base + o.ctr, 0, sizeof(int32_t) * N_COUNTERS, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e != hipSuccess) return fail_hip(e, "uploading packed weights");
   Engine& m = L->e_moe;
-  m.counters = reinterpret_cast<int32_t*>(base + o.ctr);
   m.w1 = base + o.w1;
   m.w2 = base + o.w2;
   m.wr = base + o.wr;
@@ -520,9 +517,8 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   const bool single = (e.G == 1 && e.n_always == 1);
   hipError_t err = hipSuccess;
   auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
-  // decode batches: scoring + selection + permutation are one kernel, and the combine rides on the down kernel
+  // decode batches: scoring is one kernel, selection + permutation a second one
   const bool front = !single && !use_simt_experts(e.dtype) && decode_front_ok(e, T);
-  const bool fused_combine = !use_simt_experts(e.dtype) && decode_combine_fused(e, T);
   mark(0);
   if (!single) {
     err = front ? launch_decode_front(e, x, T, w, L, topk, outer, scores, counts, s)
@@ -541,10 +537,8 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   err = launch_experts(e, x, T, w, L, y, s, 2);
   if (err != hipSuccess) return fail_hip(err, "down expert kernel");
   mark(4);
-  if (!fused_combine) {
-    err = launch_combine(e, T, w, L, y, s);
-    if (err != hipSuccess) return fail_hip(err, "combine kernel");
-  }
+  err = launch_combine(e, T, w, L, y, s);
+  if (err != hipSuccess) return fail_hip(err, "combine kernel");
   mark(5);
   return CMOE_OK;
 }
@@ -705,7 +699,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
 
 // device buffer of a hierarchy:
 // [moe W1 of all experts][moe W2 ...][dense W1 ...][dense W2 ...][router sw rows][lin rows][moe groups][dense groups][u][b][offsets]
-struct HierOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, off, ctr, total; };
+struct HierOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, off, total; };
 static HierOffsets hier_offsets(const cmoe_hier* H) {
   HierOffsets o{};
   size_t off = 0;
@@ -722,7 +716,6 @@ static HierOffsets hier_offsets(const cmoe_hier* H) {
   o.u = take(sizeof(float) * std::max(H->e_moe.r.n_scored, 1));
   o.b = take(sizeof(float) * std::max(H->e_moe.r.n_scored, 1));
   o.off = take(sizeof(float) * H->n_outer);
-  o.ctr = take(sizeof(int32_t) * N_COUNTERS);
   o.total = off;
   return o;
 }
@@ -770,7 +763,6 @@ int cmoe_hier_upload(cmoe_hier* H, void* dev_weights, void* hip_stream) {
   if (e == hipSuccess) e = h2d(base + o.u, u.data(), sizeof(float) * u.size(), s);
   if (e == hipSuccess) e = h2d(base + o.b, b.data(), sizeof(float) * b.size(), s);
   if (e == hipSuccess) e = h2d(base + o.off, H->lin_off.data(), sizeof(float) * H->lin_off.size(), s);
-  if (e == hipSuccess) e = hipMemsetAsync(base + o.ctr, 0, sizeof(int32_t) * N_COUNTERS, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e != hipSuccess) return fail_hip(e, "uploading packed weights");
   Engine& m = H->e_moe;
@@ -781,14 +773,12 @@ int cmoe_hier_upload(cmoe_hier* H, void* dev_weights, void* hip_stream) {
   m.gate_u = m.r.use_gate ? reinterpret_cast<const float*>(base + o.u) : nullptr;
   m.gate_b = m.r.use_gate ? reinterpret_cast<const float*>(base + o.b) : nullptr;
   m.lin_off = reinterpret_cast<const float*>(base + o.off);
-  m.counters = reinterpret_cast<int32_t*>(base + o.ctr);
   Engine& dn = H->e_dense;
   dn.w1 = base + o.dw1;
   dn.w2 = base + o.dw2;
   dn.wr = base + o.wr + H->router.size();      // the linear rows only
   dn.groups = reinterpret_cast<const GroupDev*>(base + o.dg);
   dn.lin_off = m.lin_off;
-  dn.counters = m.counters;      // the two forms never run concurrently on one hierarchy
   H->uploaded = true;
   return CMOE_OK;
 }

@@ -20,7 +20,6 @@ constexpr int MAX_DYN = 24;        // routed slots per token (hierarchy: outer_t
 constexpr int MAX_SCORED = 64;     // routed experts scored by one router (one lane per expert)
 constexpr int MAX_GROUPS = 128;    // expert groups of one engine
 constexpr int TOK_TILE = 64;       // tokens per router / permute tile
-constexpr int N_COUNTERS = 1 + 1024;  // [0]: decode front end; [1 + c]: column block c of the fused down+combine
 
 __host__ __device__ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 static inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -88,7 +87,6 @@ struct Engine {
   const float* gate_u = nullptr;   // [n_scored] or null
   const float* gate_b = nullptr;   // [n_scored] or null
   const float* lin_off = nullptr;  // [n_lin] or null
-  int32_t* counters = nullptr;     // [N_COUNTERS] arrival counters of the fused decode kernels: zero between calls
   int S_all() const { return n_always + S_dyn; }
 };
 
@@ -120,7 +118,6 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
 hipError_t launch_experts_simt(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                hipStream_t s, int stage);
 bool decode_front_ok(const Engine& e, int64_t T);
-bool decode_combine_fused(const Engine& e, int64_t T);   // the down kernel also does the combine
 hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
                                int32_t* topk_out, int32_t* outer_out, float* scores_out, int32_t* counts_out,
                                hipStream_t s);

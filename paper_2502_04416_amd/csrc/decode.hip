@@ -32,12 +32,6 @@ struct DecArgs {
   int ldw;                  // row stride of w1
   int64_t T;
   int single;
-  // fused gate-weighted combine (Eq. 4) in the down kernel: null counters = off
-  int32_t* counters;        // [d/16] arrival counters, zero between calls
-  const int32_t* tok2slot;  // [T][S_all]
-  const float* slot_w;      // [T][S_all]
-  bf16_t* y_out;            // [T][d]
-  int S_all;
 };
 
 __device__ __forceinline__ bf16x8_t ld_frag(const bf16_t* p) { return *reinterpret_cast<const bf16x8_t*>(p); }
@@ -202,41 +196,6 @@ __global__ __launch_bounds__(256) void decode_down_kernel(DecArgs p) {
     const float s = (red[0][tt][cc][tok] + red[1][tt][cc][tok]) + (red[2][tt][cc][tok] + red[3][tt][cc][tok]);
     p.y[(int64_t)(seg0 + col) * p.d + c0 + cc] = f32_to_bf16(s);
   }
-  if (!p.counters) return;
-  // Fused combine: the workgroup that completes this block of 16 columns last (over the groups that have
-  // tokens) adds up every token's slots for these columns.  Nobody waits; the others just exit.
-  __shared__ int last_flag;
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int n_active = p.work[p.G] / (p.d / 16);
-    const int old = atomicAdd(p.counters + local, 1);
-    last_flag = (old == n_active - 1) ? 1 : 0;
-    if (last_flag) p.counters[local] = 0;          // ready for the next call
-  }
-  __syncthreads();
-  if (!last_flag) return;
-  __threadfence();
-  // pairs of columns: 32-bit device-scope loads, because this CU's L1 may hold a stale copy of a line
-  // that a neighbouring column block's reader pulled in before this block's writers were done
-  for (int e = tid; e < (int)p.T * 8; e += 256) {
-    const int t = e >> 3, cp = e & 7;
-    float a0 = 0.0f, a1 = 0.0f;
-    for (int i = 0; i < p.S_all; ++i) {
-      const int slot = p.tok2slot[t * p.S_all + i];
-      const float w = p.slot_w[t * p.S_all + i];
-      const unsigned int* src = reinterpret_cast<const unsigned int*>(p.y + (int64_t)slot * p.d + c0 + cp * 2);
-      const unsigned int v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      a0 = fmaf(w, bf16_to_f32((bf16_t)(v & 0xffffu)), a0);
-      a1 = fmaf(w, bf16_to_f32((bf16_t)(v >> 16)), a1);
-    }
-    const unsigned int o = (unsigned int)f32_to_bf16(a0) | ((unsigned int)f32_to_bf16(a1) << 16);
-    *reinterpret_cast<unsigned int*>(p.y_out + (int64_t)t * p.d + c0 + cp * 2) = o;
-  }
-}
-
-bool decode_combine_fused(const Engine& e, int64_t T) {
-  return decode_path_ok(e, T) && e.S_all() > 1 && e.counters != nullptr && e.d / 16 <= N_COUNTERS - 1;
 }
 
 bool decode_path_ok(const Engine& e, int64_t T) {
@@ -281,13 +240,6 @@ hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
-  // fused combine: only when there is something to combine and the library owns zeroed counters
-  const bool fuse = e.S_all() > 1 && e.counters != nullptr && e.d / 16 <= N_COUNTERS - 1;
-  a.counters = fuse ? e.counters + 1 : nullptr;
-  a.tok2slot = reinterpret_cast<const int32_t*>(ws + L.tok2slot);
-  a.slot_w = reinterpret_cast<const float*>(ws + L.slot_w);
-  a.y_out = static_cast<bf16_t*>(y);
-  a.S_all = e.S_all();
   const bool two = T > 16;
   if (stage != 2) {
     a.work = reinterpret_cast<const int32_t*>(ws + L.work1);

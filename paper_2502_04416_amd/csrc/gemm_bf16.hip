@@ -2,7 +2,7 @@
 //   MODE 1  H_g = Swish(X_g Wgate_g) * (X_g Wup_g)     rows of X gathered through slot2tok, K = d
 //   MODE 2  Y_g = H_g Wdown_g                          K = width_pad(g), N = d
 // Both are C = A * B^T with K contiguous in A and in B, computed with v_mfma_f32_32x32x16_bf16 from
-// LDS-staged, XOR-swizzled tiles.  A work item is (group, row tile, column tile); the list of work
+// LDS-staged, XOR-swizzled tiles filled by direct global->LDS loads.  A work item is (group, row tile, column tile); the list of work
 // items is a device-side prefix array written by the permute kernel, so ragged, empty and skewed
 // groups need no host round trip.  Workgroups whose index is past the list exit at once.
 #include <cstdlib>
@@ -31,197 +31,9 @@ struct GemmArgs {
   int single;                // 1: one always-on group holding all T tokens; no device schedule is read
   int n_blocks;              // grid size (multiple of 8)
   int xcd_remap;             // 1: consecutive work items run on the same XCD
-  int dbg;                   // tuning aid: bit 0 skips the global->LDS loads, bit 1 skips LDS reads and MFMAs
-  unsigned long long* tstamps;   // tuning aid: per workgroup [8] clock samples (null = off)
 };
 
-constexpr int BK = 64;
-
-// element offset of 16-byte chunk c (0..7) of row `row` in a [rows][64] bf16 tile; the XOR spreads the
-// 16 rows that one ds_read_b128 wave-quarter touches over all 64 banks
-__device__ __forceinline__ int lds_off(int row, int c) { return row * BK + ((c ^ ((row >> 1) & 7)) << 3); }
-
-template <int BM, int BN, int WGM, int WGN, int MODE>
-__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16(GemmArgs p) {
-  constexpr int NT = WGM * WGN * 64;
-  constexpr int TM = BM / WGM, TN = BN / WGN, MI = TM / 32, NI = TN / 32;
-  constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;
-  static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "tile");
-  static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "loader");
-  static_assert(MODE != 1 || TN % 64 == 0, "gate/up pairs must stay inside a wave tile");
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  bf16_t* As = smem;                       // [2][BM*BK]
-  bf16_t* Bs = smem + 2 * BM * BK;         // [2][BN*BK]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
-  const int l32 = lane & 31, lh = lane >> 5;
-
-  // ---- which work item? ----
-  // Workgroup b runs on XCD b % 8.  With the remap, XCD x works through the contiguous range
-  // [x * ceil(W/8), (x+1) * ceil(W/8)) of the W work items, so tiles that share operands meet in one L2.
-  int g = 0, cnt, seg0 = 0, wp;
-  int64_t hoff = 0;
-  int n_work;
-  if (p.single) {
-    cnt = (int)p.T;
-    wp = p.groups[0].width_pad;
-    const int nc = (MODE == 1) ? 2 * wp : p.d;
-    n_work = ((cnt + BM - 1) / BM) * ((nc + BN - 1) / BN);
-  } else {
-    n_work = p.work[p.G];
-  }
-  int wid = blockIdx.x;
-  if (p.xcd_remap) {
-    const int chunk = (n_work + 7) >> 3;
-    if ((wid >> 3) >= chunk) return;
-    wid = (wid & 7) * chunk + (wid >> 3);
-  }
-  if (wid >= n_work) return;
-  int local = wid;
-  if (!p.single) {
-    // G is small: binary search over the prefix array
-    int lo = 0, hi = p.G;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (p.work[mid] <= wid) lo = mid; else hi = mid;
-    }
-    // skip empty groups that share the same prefix value
-    g = lo;
-    local = wid - p.work[g];
-    seg0 = p.seg_off[g];
-    cnt = p.seg_off[g + 1] - seg0;
-    wp = p.groups[g].width_pad;
-    hoff = p.h_off[g];
-  }
-  const int K = (MODE == 1) ? p.d : wp;
-  const int n_cols = (MODE == 1) ? 2 * wp : p.d;         // columns of C^T = rows of B
-  const int n_nt = (n_cols + BN - 1) / BN;
-  const int n_mt = (cnt + BM - 1) / BM;
-  // raster inside a group: super-rows of GM row tiles; inside a super-row the row tile runs fastest, so
-  // the (up to GM) tiles that read the same weight tile are neighbours in time and, with the XCD remap,
-  // in one L2
-  constexpr int GM = 8;
-  const int sr = local / (GM * n_nt);
-  const int rem = local - sr * (GM * n_nt);
-  const int rows_in_sr = (n_mt - sr * GM) < GM ? (n_mt - sr * GM) : GM;
-  const int mt = sr * GM + rem % rows_in_sr;
-  const int nt = rem / rows_in_sr;
-
-  // ---- per-thread global sources ----
-  const bf16_t* a_src[A_CH];
-  const bf16_t* b_src[B_CH];
-  int a_dst[A_CH], b_dst[B_CH];
-  const int cchunk = tid & 7;
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int row = (tid >> 3) + i * (NT >> 3);
-    int r = mt * BM + row;
-    if (r >= cnt) r = cnt - 1;
-    if (MODE == 1) {
-      const int64_t tok = p.slot2tok ? p.slot2tok[seg0 + r] : (seg0 + r);
-      a_src[i] = p.A + tok * p.d + cchunk * 8;
-    } else {
-      a_src[i] = p.A + hoff + (int64_t)r * wp + cchunk * 8;
-    }
-    a_dst[i] = lds_off(row, cchunk);
-  }
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int row = (tid >> 3) + i * (NT >> 3);
-    int n = nt * BN + row;
-    if (n >= n_cols) n = n_cols - 1;
-    if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + cchunk * 8;
-    else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + cchunk * 8;
-    b_dst[i] = lds_off(row, cchunk);
-  }
-
-  floatx16_t acc[MI][NI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
-
-  uint4 ra[A_CH], rb[B_CH];
-  const int KT = (K + BK - 1) / BK;
-  auto g_load = [&](int kt) {
-    const int k = kt * BK + cchunk * 8;
-    const bool ok = k < K;                       // K is a multiple of 8: a chunk is all in or all out
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) ra[i] = ok ? *reinterpret_cast<const uint4*>(a_src[i] + kt * BK) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = ok ? *reinterpret_cast<const uint4*>(b_src[i] + kt * BK) : make_uint4(0, 0, 0, 0);
-  };
-  auto s_store = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4*>(As + buf * BM * BK + a_dst[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(Bs + buf * BN * BK + b_dst[i]) = rb[i];
-  };
-
-  g_load(0);
-  s_store(0);
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) g_load(kt + 1);
-    const bf16_t* as = As + buf * BM * BK;
-    const bf16_t* bs = Bs + buf * BN * BK;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8_t af[MI], bfr[NI];
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-        af[mi] = *reinterpret_cast<const bf16x8_t*>(as + lds_off(wm * TM + mi * 32 + l32, ks * 2 + lh));
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-        bfr[ni] = *reinterpret_cast<const bf16x8_t*>(bs + lds_off(wn * TN + ni * 32 + l32, ks * 2 + lh));
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-    }
-    if (kt + 1 < KT) s_store(buf ^ 1);
-    __syncthreads();
-  }
-
-  // ---- epilogue ----
-  // accumulator element i of a 32x32 tile: row (i/4)*8 + (lane/32)*4 + i%4, column lane%32
-  if (MODE == 1) {
-    bf16_t* H = p.C + hoff;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-      for (int pi = 0; pi < NI / 2; ++pi) {
-        const int neuron = (nt * BN + wn * TN) / 2 + pi * 32 + l32;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = mt * BM + wm * TM + mi * 32 + (i / 4) * 8 + lh * 4 + (i % 4);
-          if (r < cnt && neuron < wp) {
-            const float gt = acc[mi][2 * pi][i], up = acc[mi][2 * pi + 1][i];
-            H[(int64_t)r * wp + neuron] = f32_to_bf16(silu_f32(gt) * up);
-          }
-        }
-      }
-  } else {
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int col = nt * BN + wn * TN + ni * 32 + l32;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = mt * BM + wm * TM + mi * 32 + (i / 4) * 8 + lh * 4 + (i % 4);
-          if (r < cnt && col < p.d) p.C[(int64_t)(seg0 + r) * p.d + col] = f32_to_bf16(acc[mi][ni][i]);
-        }
-      }
-  }
-}
-
-// ---- variant with direct global->LDS loads and a ring of STAGES tiles ------------------------------
+// ---- global->LDS loads and a ring of K tiles ------------------------------------------------------
 // Each global_load_lds_dwordx4 moves 64 lanes x 16 bytes into 1 KB of consecutive LDS (8 tile rows);
 // which global chunk a lane fetches is free, so the XOR swizzle is applied on the global side.  No
 // VGPRs are spent on staging, and STAGES-1 tiles are in flight while one is multiplied.
@@ -274,8 +86,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
   const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, lh = lane >> 5;
 
-  unsigned long long ts0 = 0, ts1 = 0, ts2 = 0, tw0 = 0;
-  if (p.tstamps) { ts0 = __builtin_amdgcn_s_memtime(); tw0 = wall_clock64(); }
   int g = 0, cnt, seg0 = 0, wp;
   int64_t hoff = 0;
   int n_work;
@@ -419,14 +229,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
       for (int ni = 0; ni < NI; ++ni)
         fb[ni] = *reinterpret_cast<const bf16x8_t*>(bs + lds_off_t<BKT>(wn * TN + ni * 32 + l32, ks * 2 + lh));
     };
-    if (!(p.dbg & 4)) load_frags(0, af[0], bfr[0]);
+    load_frags(0, af[0], bfr[0]);
 #pragma unroll
     for (int ks = 0; ks < BKT / 16; ++ks) {
       const int cur = ks & 1;
       __builtin_amdgcn_sched_barrier(0);
-      if (ks + 1 < BKT / 16 && !(p.dbg & 4)) load_frags(ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
+      if (ks + 1 < BKT / 16) load_frags(ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
       __builtin_amdgcn_sched_barrier(0);
-      if (AHEAD >= 1 && !(p.dbg & 1)) {
+      if (AHEAD >= 1) {
         if (HR) {                                    // spread over the K step: B half early, A half later
           if (ks == 0) issue_b(kt + 1);
           if (ks == (BKT / 16) / 2 && AHEAD >= 2) issue_a(kt + 2);
@@ -435,7 +245,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
           issue_b(kt + STAGES - 1);
         }
       }
-      if (p.dbg & 2) continue;
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -452,7 +261,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
       }
     }
   };
-  if (p.tstamps) ts1 = __builtin_amdgcn_s_memtime();
   int kt = 0;
   if (HR) {
     for (; kt + 2 < KT; ++kt) k_tile(kt, std::integral_constant<int, 2>{});
@@ -472,7 +280,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
   constexpr int CPRO = TNO / 8;                           // 16-byte pieces per strip row
   static_assert(NW * 32 * LDO <= RING_ELEMS, "epilogue strip must fit in the tile ring");
   __syncthreads();                                        // every wave is done reading the last tile
-  if (p.tstamps) ts2 = __builtin_amdgcn_s_memtime();
   bf16_t* strip = smem + wave * 32 * LDO;
   const int out_col0 = (MODE == 1) ? (nt * BN + wn * TN) / 2 : nt * BN + wn * TN;
   const int out_cols = (MODE == 1) ? wp : p.d;
@@ -507,38 +314,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // reads done before the strip is overwritten
   }
-  if (p.tstamps && tid == 0) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    unsigned long long* o = p.tstamps + (size_t)blockIdx.x * 8;
-    o[0] = ts0; o[1] = ts1; o[2] = ts2; o[3] = __builtin_amdgcn_s_memtime(); o[4] = tw0; o[5] = wall_clock64();
-    o[6] = (unsigned long long)wid; o[7] = (unsigned long long)KT;
-  }
 }
 
 // ---- tile configurations ---------------------------------------------------------------------
-struct TileCfg { int bm, bn, wgm, wgn, stages, bk; };   // stages 0: register-staged loads, >= 2: LDS-DMA ring
+// Tile shapes the tuning environment variables CMOE_GEMM1_CFG / CMOE_GEMM2_CFG can select.
+// stages >= 2: ring of whole K tiles; stages == 0: ring of five half tiles.
+struct TileCfg { int bm, bn, wgm, wgn, stages, bk; };
 static const TileCfg kCfgs[] = {
-    {256, 128, 2, 2, 0, 64},   // 0
-    {128, 128, 2, 2, 0, 64},   // 1
-    {256, 256, 2, 4, 0, 64},   // 2
-    {256, 128, 4, 2, 0, 64},   // 3
-    {128, 256, 2, 2, 0, 64},   // 4
-    {256, 256, 2, 4, 2, 64},   // 5
-    {256, 128, 2, 2, 3, 64},   // 6
-    {128, 128, 2, 2, 4, 64},   // 7
-    {256, 128, 4, 2, 3, 64},   // 8
-    {128, 128, 2, 2, 2, 64},   // 9
-    {128, 256, 2, 4, 3, 64},   // 10
-    {256, 256, 2, 4, 4, 32},   // 11
-    {256, 256, 2, 4, 3, 32},   // 12
-    {256, 128, 4, 2, 4, 32},   // 13
-    {128, 128, 2, 2, 4, 32},   // 14
-    {256, 256, 4, 2, 4, 32},   // 15
-    {256, 256, 2, 2, 2, 64},   // 16: four waves of 128x128
-    {128, 256, 2, 2, 3, 64},   // 17: four waves of 64x128, three stages
-    {256, 256, 2, 4, -1, 64},  // 18: ring of five half tiles
-    {128, 128, 2, 2, -1, 64},  // 19: ring of five half tiles, two workgroups per CU
-    {256, 256, 2, 2, -1, 64},  // 20: half-tile ring, four waves of 128x128
+    {256, 256, 2, 4, 0, 64},   // 0: half-tile ring, eight waves of 128x64 (default for gate/up)
+    {128, 128, 2, 2, 2, 64},   // 1: two stages, two workgroups per CU (default for down)
+    {256, 256, 2, 4, 2, 64},   // 2
+    {128, 128, 2, 2, 0, 64},   // 3
+    {256, 128, 4, 2, 3, 64},   // 4
+    {256, 256, 2, 4, 4, 32},   // 5
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -551,7 +339,7 @@ static int env_int(const char* name, int dflt) {
 static int cfg_index(int which) {
   // defaults: 256x256 tiles on the half-tile ring for the long-K gate/up contraction, 128x128 tiles
   // (two workgroups per CU) for the short-K, many-tile down contraction
-  const int dflt = which == 1 ? 18 : 9;
+  const int dflt = which == 1 ? 0 : 1;
   int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", dflt);
   if (c < 0 || c >= kNumCfgs) c = dflt;
   return c;
@@ -579,13 +367,6 @@ static hipError_t launch_kernel(K kern, size_t smem, int threads, bool& attr_don
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
-static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
-  static bool attr_done = false;
-  return launch_kernel(grouped_gemm_bf16<BM, BN, WGM, WGN, MODE>, 2 * (size_t)(BM + BN) * BK * sizeof(bf16_t),
-                       WGM * WGN * 64, attr_done, a, s);
-}
-
 template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE>
 static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   static bool attr_done = false;
@@ -596,27 +377,12 @@ static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
 template <int MODE>
 static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
   switch (ci) {
-    case 0: return launch_one<256, 128, 2, 2, MODE>(a, s);
-    case 1: return launch_one<128, 128, 2, 2, MODE>(a, s);
-    case 2: return launch_one<256, 256, 2, 4, MODE>(a, s);
-    case 3: return launch_one<256, 128, 4, 2, MODE>(a, s);
-    case 4: return launch_one<128, 256, 2, 2, MODE>(a, s);
-    case 5: return launch_dma<256, 256, 64, 2, 2, 4, MODE>(a, s);
-    case 6: return launch_dma<256, 128, 64, 3, 2, 2, MODE>(a, s);
-    case 7: return launch_dma<128, 128, 64, 4, 2, 2, MODE>(a, s);
-    case 8: return launch_dma<256, 128, 64, 3, 4, 2, MODE>(a, s);
-    case 9: return launch_dma<128, 128, 64, 2, 2, 2, MODE>(a, s);
-    case 10: return launch_dma<128, 256, 64, 3, 2, 4, MODE>(a, s);
-    case 11: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
-    case 12: return launch_dma<256, 256, 32, 3, 2, 4, MODE>(a, s);
-    case 13: return launch_dma<256, 128, 32, 4, 4, 2, MODE>(a, s);
-    case 14: return launch_dma<128, 128, 32, 4, 2, 2, MODE>(a, s);
-    case 15: return launch_dma<256, 256, 32, 4, 4, 2, MODE>(a, s);
-    case 16: return launch_dma<256, 256, 64, 2, 2, 2, MODE>(a, s);
-    case 17: return launch_dma<128, 256, 64, 3, 2, 2, MODE>(a, s);
-    case 18: return launch_dma<256, 256, 64, 0, 2, 4, MODE>(a, s);
-    case 19: return launch_dma<128, 128, 64, 0, 2, 2, MODE>(a, s);
-    default: return launch_dma<256, 256, 64, 0, 2, 2, MODE>(a, s);
+    case 0: return launch_dma<256, 256, 64, 0, 2, 4, MODE>(a, s);
+    case 1: return launch_dma<128, 128, 64, 2, 2, 2, MODE>(a, s);
+    case 2: return launch_dma<256, 256, 64, 2, 2, 4, MODE>(a, s);
+    case 3: return launch_dma<128, 128, 64, 0, 2, 2, MODE>(a, s);
+    case 4: return launch_dma<256, 128, 64, 3, 4, 2, MODE>(a, s);
+    default: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
   }
 }
 
@@ -633,9 +399,6 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.xcd_remap = remap;
-  a.dbg = env_int("CMOE_GEMM_DBG", 0);
-  a.tstamps = nullptr;
-  if (const char* tp = std::getenv("CMOE_GEMM_TSTAMPS")) a.tstamps = reinterpret_cast<unsigned long long*>(std::strtoull(tp, nullptr, 0));
   // gate/up
   a.A = static_cast<const bf16_t*>(x);
   a.B = static_cast<const bf16_t*>(e.w1);

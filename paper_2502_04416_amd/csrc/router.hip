@@ -373,27 +373,21 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
   for (int g = tid; g < G; g += 256) tile_counts[(int64_t)blockIdx.x * G + g] = hist[g];
 }
 
-// ---- decode front end: scoring, selection and permutation in one launch ---------------------------
-// For batches of at most 32 tokens the three steps are latency, not throughput, so they share one kernel.
-// Every workgroup scores 16 router rows for all tokens (v_mfma_f32_16x16x32_bf16, router rows as the A
-// operand, K split over the 8 waves, partials added in order through LDS) and publishes the 16 x T
-// pre-activations.  The workgroup that arrives last at a device-wide counter (no waiting: everybody else
-// simply exits) then routes every token, one per lane, and places the single 64-token tile.  The counter
-// lives in library-owned device memory, is zero between calls and is reset by the last workgroup.
+// ---- decode front end ------------------------------------------------------------------------------
+// For batches of at most 32 tokens scoring is one launch and selection + permutation a second one.
+// (Fusing all three behind a device-wide arrival counter was tried: on this multi-die part a device-scope
+// release/acquire pair writes back and invalidates the whole L2, which costs far more than a launch.)
+//
+// decode_score_kernel: every workgroup scores 16 router rows for all tokens (v_mfma_f32_16x16x32_bf16,
+// router rows as the A operand, K split over the 8 waves, partials added in order through LDS).
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 template <int NTT, int KSTEPS>
-__global__ __launch_bounds__(512) void decode_front_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
-                                                           const bf16_t* __restrict__ x,
-                                                           const bf16_t* __restrict__ wr, int d, int T,
-                                                           float* __restrict__ pre_g, int32_t* __restrict__ counter) {
+__global__ __launch_bounds__(512) void decode_score_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wr,
+                                                           int d, int T, int n_rows, float* __restrict__ pre_g) {
   __shared__ float red[8][NTT][16][17];
-  __shared__ int32_t hist[MAX_GROUPS];
-  __shared__ int last_flag;
-  extern __shared__ float pre[];                 // [T][n_rows + 1], only used by the last workgroup
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kq = lane >> 4;
-  const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int row0 = blockIdx.x * 16;
   const int kbase = wave * (KSTEPS * 32) + kq * 8;
   const bf16_t* wrow = wr + (int64_t)(row0 + r16) * d + kbase;
@@ -435,23 +429,25 @@ __global__ __launch_bounds__(512) void decode_front_kernel(RouterDev r, RouteIO 
     for (int w = 0; w < 8; ++w) v += red[w][tt][rr][tok];
     pre_g[(int64_t)col * n_rows + row0 + rr] = v;
   }
-  // publish, then count arrivals
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int old = atomicAdd(counter, 1);
-    last_flag = (old == (int)gridDim.x - 1) ? 1 : 0;
-  }
-  __syncthreads();
-  if (!last_flag) return;
-  __threadfence();
+}
+
+// route_place_kernel: a batch that fits one 64-token tile is selected and permuted by one workgroup:
+// the 256 threads add the K-slice partials of the pre-activations in slice order, then wave 0 routes one
+// token per lane and places the tile, with the histogram handed over in LDS.
+__global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
+                                                          const float* __restrict__ partial, int n_slices, int T) {
+  extern __shared__ float pre[];                 // [T][n_rows + 1]
+  __shared__ int32_t hist[MAX_GROUPS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int ld = n_rows + 1;
-  for (int i = tid; i < T * n_rows; i += 512) {
+  for (int i = tid; i < T * n_rows; i += 256) {
     const int row = i / n_rows, col = i - row * n_rows;
-    pre[row * ld + col] = __hip_atomic_load(pre_g + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    float v = 0.0f;
+    for (int ks = 0; ks < n_slices; ++ks) v += partial[(int64_t)ks * T * n_rows + i];
+    pre[row * ld + col] = v;
   }
-  for (int i = tid; i < MAX_GROUPS; i += 512) hist[i] = 0;
-  if (tid == 0) *counter = 0;                    // ready for the next call
+  for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
   if (wave == 0) {
     if (lane < T) route_token_lane(r, io, pre + lane * ld, lane, hist);
@@ -478,10 +474,10 @@ PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& 
 
 bool decode_front_ok(const Engine& e, int64_t T) {
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
-  return e.S_dyn > 0 && e.counters != nullptr && decode_path_ok(e, T) && n_rows % 16 == 0;
+  return e.S_dyn > 0 && decode_path_ok(e, T) && n_rows % 16 == 0;
 }
 
-// Router scoring + selection + permutation of a decode batch in one kernel (see decode_front_kernel).
+// Router scoring (one launch) and selection + permutation (one launch) of a decode batch.
 hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
                                int32_t* topk_out, int32_t* outer_out, float* scores_out, int32_t* counts_out,
                                hipStream_t s) {
@@ -498,29 +494,32 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   const PlaceArgs pl = make_place_args(e, T, ws, L, counts_out);
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
   float* pre_g = reinterpret_cast<float*>(ws + L.scores);
-  const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1);
   dim3 grid(n_rows / 16), block(512);
   const bf16_t* xx = static_cast<const bf16_t*>(x);
   const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
   const int ksteps = e.d / 256;
   const int Ti = (int)T;
-#define CMOE_FRONT(NTT, KS) hipLaunchKernelGGL((decode_front_kernel<NTT, KS>), grid, block, smem, s, e.r, io, pl, xx, ww, e.d, Ti, pre_g, e.counters)
+#define CMOE_SCORE(NTT, KS) hipLaunchKernelGGL((decode_score_kernel<NTT, KS>), grid, block, 0, s, xx, ww, e.d, Ti, n_rows, pre_g)
   if (T <= 16) {
     switch (ksteps) {
-      case 16: CMOE_FRONT(1, 16); break;
-      case 8: CMOE_FRONT(1, 8); break;
-      case 4: CMOE_FRONT(1, 4); break;
-      default: CMOE_FRONT(1, 2); break;
+      case 16: CMOE_SCORE(1, 16); break;
+      case 8: CMOE_SCORE(1, 8); break;
+      case 4: CMOE_SCORE(1, 4); break;
+      default: CMOE_SCORE(1, 2); break;
     }
   } else {
     switch (ksteps) {
-      case 16: CMOE_FRONT(2, 16); break;
-      case 8: CMOE_FRONT(2, 8); break;
-      case 4: CMOE_FRONT(2, 4); break;
-      default: CMOE_FRONT(2, 2); break;
+      case 16: CMOE_SCORE(2, 16); break;
+      case 8: CMOE_SCORE(2, 8); break;
+      case 4: CMOE_SCORE(2, 4); break;
+      default: CMOE_SCORE(2, 2); break;
     }
   }
-#undef CMOE_FRONT
+#undef CMOE_SCORE
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1);
+  hipLaunchKernelGGL(route_place_kernel, dim3(1), dim3(256), smem, s, e.r, io, pl, pre_g, 1, Ti);
   return hipGetLastError();
 }
 
