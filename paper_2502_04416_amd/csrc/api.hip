@@ -66,11 +66,13 @@ bool use_simt_experts(int dtype) {
   return dtype != CMOE_BF16 || force != 0;
 }
 
-int gemm_tile(int dtype, int which) { return use_simt_experts(dtype) ? simt_gemm_tile(which) : bf16_gemm_tile(which); }
+int gemm_tile(const Engine& e, int64_t T, int which) {
+  return use_simt_experts(e.dtype) ? simt_gemm_tile(which) : bf16_gemm_tile(which, e, T);
+}
 
 int64_t gemm_work_bound(const Engine& e, int64_t T, int which) {
-  const int bm = gemm_tile(e.dtype, which == 1 ? 1 : 2);
-  const int bn = gemm_tile(e.dtype, which == 1 ? 3 : 4);
+  const int bm = gemm_tile(e, T, which == 1 ? 1 : 2);
+  const int bn = gemm_tile(e, T, which == 1 ? 3 : 4);
   auto nt_of = [&](int g) { return which == 1 ? cdiv(2 * e.width_pad_host[g], bn) : cdiv(e.d, bn); };
   const int64_t mt_all = (T + bm - 1) / bm;
   int64_t total = 0;

@@ -109,9 +109,9 @@ hipError_t launch_combine(const Engine& e, int64_t T, char* ws, const WsLayout& 
 // Tile sizes of the two grouped GEMMs (the permute kernel builds their work lists from them):
 // which = 1: rows of a gate/up tile, 2: rows of a down tile, 3: packed gate/up rows (columns of the
 // product) of a gate/up tile, 4: columns of a down tile.
-int gemm_tile(int dtype, int which);
+int gemm_tile(const Engine& e, int64_t T, int which);
 bool use_simt_experts(int dtype);
-int bf16_gemm_tile(int which);
+int bf16_gemm_tile(int which, const Engine& e, int64_t T);
 int simt_gemm_tile(int which);
 hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                hipStream_t s, int stage);

@@ -334,24 +334,29 @@ static int env_int(const char* name, int dflt) {
   const char* v = std::getenv(name);
   return v ? std::atoi(v) : dflt;
 }
-// The environment is read at every call (a getenv is nothing next to a kernel launch) so that a tuning
-// script can switch tile shapes inside one process.
-static int cfg_index(int which) {
-  // defaults: 256x256 tiles on the half-tile ring for the long-K gate/up contraction, 128x128 tiles
-  // (two workgroups per CU) for the short-K, many-tile down contraction
-  const int dflt = which == 1 ? 0 : 1;
+// Which tile shape for contraction `which` (1: gate/up, 2: down) of a batch of T tokens.  The environment
+// is read at every call (a getenv is nothing next to a kernel launch) so that a tuning script can switch
+// tile shapes inside one process.  Defaults: 256x256 tiles on the half-tile ring for the long-K gate/up
+// contraction; for the short-K down contraction 256x256 tiles when there are enough of them to fill the
+// chip (>= 256), else 128x128 tiles with two workgroups per CU.
+static int cfg_index(int which, const Engine& e, int64_t T) {
+  int dflt = 0;
+  if (which == 2) {
+    const int64_t tiles_256 = ((T * e.S_all() + 255) / 256) * ((e.d + 255) / 256);
+    dflt = tiles_256 >= 256 ? 2 : 1;
+  }
   int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", dflt);
   if (c < 0 || c >= kNumCfgs) c = dflt;
   return c;
 }
 
 // which = 1: BM of gate/up, 2: BM of down, 3: BN of gate/up (packed rows), 4: BN of down
-int bf16_gemm_tile(int which) {
+int bf16_gemm_tile(int which, const Engine& e, int64_t T) {
   switch (which) {
-    case 1: return kCfgs[cfg_index(1)].bm;
-    case 2: return kCfgs[cfg_index(2)].bm;
-    case 3: return kCfgs[cfg_index(1)].bn;
-    default: return kCfgs[cfg_index(2)].bn;
+    case 1: return kCfgs[cfg_index(1, e, T)].bm;
+    case 2: return kCfgs[cfg_index(2, e, T)].bm;
+    case 3: return kCfgs[cfg_index(1, e, T)].bn;
+    default: return kCfgs[cfg_index(2, e, T)].bn;
   }
 }
 
@@ -407,7 +412,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
   a.n_blocks = (int)round_up64(gemm_work_bound(e, T, 1), 8);
   if (stage != 2) {
-    hipError_t err = launch_cfg<1>(cfg_index(1), a, s);
+    hipError_t err = launch_cfg<1>(cfg_index(1, e, T), a, s);
     if (err != hipSuccess || stage == 1) return err;
   }
   // down
@@ -417,7 +422,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.work = reinterpret_cast<const int32_t*>(ws + L.work2);
   a.slot2tok = nullptr;
   a.n_blocks = (int)round_up64(gemm_work_bound(e, T, 2), 8);
-  return launch_cfg<2>(cfg_index(2), a, s);
+  return launch_cfg<2>(cfg_index(2, e, T), a, s);
 }
 
 }  // namespace cmoe

@@ -39,10 +39,10 @@ PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& 
   p.n_always = e.n_always;
   p.S_dyn = e.S_dyn;
   p.n_tiles = L.n_tok_tiles;
-  p.bm1 = gemm_tile(e.dtype, 1);
-  p.bn1 = gemm_tile(e.dtype, 3);
-  p.bm2 = gemm_tile(e.dtype, 2);
-  p.bn2 = gemm_tile(e.dtype, 4);
+  p.bm1 = gemm_tile(e, T, 1);
+  p.bn1 = gemm_tile(e, T, 3);
+  p.bm2 = gemm_tile(e, T, 2);
+  p.bn2 = gemm_tile(e, T, 4);
   p.d = e.d;
   p.decode = (!use_simt_experts(e.dtype) && decode_path_ok(e, T)) ? 1 : 0;
   return p;

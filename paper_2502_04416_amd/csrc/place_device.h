@@ -39,6 +39,17 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
   __shared__ int32_t total[MAX_GROUPS];
   __shared__ int32_t wpad[MAX_GROUPS];      // padded widths (read once, in parallel)
   const int S_all = p.n_always + p.S_dyn;
+  const int64_t t = (int64_t)tile * TOK_TILE + lane;
+  const bool valid = t < p.T;
+  // this token's routed entries, requested first: nothing below depends on them until the group loop
+  int my_g[MAX_DYN];
+  float my_w[MAX_DYN];
+#pragma unroll
+  for (int i = 0; i < MAX_DYN; ++i) {
+    const bool ok = valid && i < p.S_dyn;
+    my_g[i] = ok ? p.sel_group[t * p.S_dyn + i] : -1;
+    my_w[i] = ok ? p.sel_weight[t * p.S_dyn + i] : 0.0f;
+  }
   // totals and the count of all preceding tiles, two groups per lane at most
   for (int g = lane; g < MAX_GROUPS; g += 64) {
     int tot = 0, prev = 0;
@@ -47,14 +58,14 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
         tot = (int)p.T;
         prev = 0;
       } else {
-        // independent loads, eight in flight at a time (the compiler does not batch them by itself)
+        // independent loads, sixteen in flight at a time (the compiler does not batch them by itself)
         int i = 0;
-        for (; i + 8 <= p.n_tiles; i += 8) {
-          int c[8];
+        for (; i + 16 <= p.n_tiles; i += 16) {
+          int c[16];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) c[k] = counts[(int64_t)(i + k) * p.G + g];
+          for (int k = 0; k < 16; ++k) c[k] = counts[(int64_t)(i + k) * p.G + g];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
+          for (int k = 0; k < 16; ++k) {
             tot += c[k];
             prev += (i + k < tile) ? c[k] : 0;
           }
@@ -105,8 +116,6 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     }
   }
   wave_lds_sync();
-  const int64_t t = (int64_t)tile * TOK_TILE + lane;
-  const bool valid = t < p.T;
   // always-on groups: identity segments
   if (valid)
     for (int a = 0; a < p.n_always; ++a) {
@@ -115,15 +124,6 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
       p.tok2slot[t * S_all + a] = slot;
       p.slot_w[t * S_all + a] = 1.0f;
     }
-  // this token's routed entries, loaded up front so that no load sits inside the group loop below
-  int my_g[MAX_DYN];
-  float my_w[MAX_DYN];
-#pragma unroll
-  for (int i = 0; i < MAX_DYN; ++i) {
-    const bool ok = valid && i < p.S_dyn;
-    my_g[i] = ok ? p.sel_group[t * p.S_dyn + i] : -1;
-    my_w[i] = ok ? p.sel_weight[t * p.S_dyn + i] : 0.0f;
-  }
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   for (int g = p.n_always; g < p.G; ++g) {
     int hit = -1;

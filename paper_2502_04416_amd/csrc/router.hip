@@ -158,25 +158,16 @@ __device__ __forceinline__ void lane_select_routed(const RouterDev& r, const Rou
   }
 }
 
-// `row` is the token's row of pre-activations in LDS; it is overwritten with the scores in place.
-__device__ __forceinline__ void route_token_lane(const RouterDev& r, const RouteIO& io, float* row, int64_t t,
-                                                 int32_t* hist) {
-  for (int j = 0; j < r.n_scored; ++j) {
-    const int blk = j / IL, c = j % IL;
-    const float g = row[blk * 2 * IL + c], u = row[blk * 2 * IL + IL + c];
-    const float s = silu_f32(g) * u;                                         // Eq. 8
-    if (io.scores_out) io.scores_out[t * r.n_scored + j] = s;
-    row[blk * 2 * IL + c] = s;
-  }
-  // compact the scores to row[0 .. n_scored): block b's scores sit at b*2*IL .. b*2*IL+IL-1
-  for (int j = IL; j < r.n_scored; ++j) row[j] = row[(j / IL) * 2 * IL + (j % IL)];
+// Selection for one token by one lane: `sc` holds the token's n_scored scores (Eq. 8), `lin` its linear
+// outer logits (hierarchy only).
+__device__ __forceinline__ void route_select_lane(const RouterDev& r, const RouteIO& io, const float* sc,
+                                                  const float* lin, int64_t t, int32_t* hist) {
   LaneSel st{0};
   if (r.outer_top_k == 0) {
-    lane_select_routed(r, io, row, 0, r.n_scored, 1.0f, r.n_always, t, st,
+    lane_select_routed(r, io, sc, 0, r.n_scored, 1.0f, r.n_always, t, st,
                        io.topk_out ? io.topk_out + t * r.top_k : nullptr, hist);
     return;
   }
-  const float* lin = row + r.n_sw_rows;
   int oe[MAX_TOPK];
   float ol[MAX_TOPK];
   uint32_t taken = 0u;
@@ -208,8 +199,22 @@ __device__ __forceinline__ void route_token_lane(const RouterDev& r, const Route
       ++st.n;
     }
     if (r.top_k > 0)
-      lane_select_routed(r, io, row, e * r.n_r_sub, r.n_r_sub, w_e, gbase + r.sub_has_shared, t, st,
+      lane_select_routed(r, io, sc, e * r.n_r_sub, r.n_r_sub, w_e, gbase + r.sub_has_shared, t, st,
                          io.topk_out ? io.topk_out + (t * r.outer_top_k + i) * r.top_k : nullptr, hist);
+  }
+}
+
+// Scores of a tile of tokens, all threads of the workgroup in parallel (the exponentials are the
+// expensive part of routing): sc[tok][j] = Swish(gate_j) * up_j from pre[tok][...] (Eq. 8).
+__device__ __forceinline__ void score_tile(const RouterDev& r, const RouteIO& io, const float* pre, int ld_pre,
+                                           float* sc, int ld_sc, int n_tok, int64_t t0, int tid, int n_threads) {
+  for (int idx = tid; idx < n_tok * r.n_scored; idx += n_threads) {
+    const int tok = idx / r.n_scored, j = idx - tok * r.n_scored;
+    const int blk = j / IL, c = j % IL;
+    const float g = pre[tok * ld_pre + blk * 2 * IL + c], u = pre[tok * ld_pre + blk * 2 * IL + IL + c];
+    const float s = silu_f32(g) * u;
+    sc[tok * ld_sc + j] = s;
+    if (io.scores_out) io.scores_out[(t0 + tok) * r.n_scored + j] = s;
   }
 }
 
@@ -324,11 +329,13 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(const bf16_t* __restri
 __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io, const float* __restrict__ partial,
                                                          int n_slices, int64_t T, int32_t* __restrict__ tile_counts,
                                                          int G) {
-  extern __shared__ float pre[];                 // [TOK_TILE][n_rows + 1]
+  extern __shared__ float pre[];                 // [TOK_TILE][n_rows + 1], then scores [TOK_TILE][MAX_SCORED + 1]
   __shared__ int32_t hist[MAX_GROUPS];
   const int tid = threadIdx.x;
   const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int ld = n_rows + 1;
+  float* sc = pre + TOK_TILE * ld;
+  constexpr int LDS_SC = MAX_SCORED + 1;
   const int64_t t0 = (int64_t)blockIdx.x * TOK_TILE;
   // n_rows is a multiple of 32: float4 loads, all slices of up to four vectors in flight together
   const int vec_per_row = n_rows >> 2;
@@ -368,7 +375,10 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
   }
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
-  if (tid < TOK_TILE && t0 + tid < T) route_token_lane(r, io, pre + tid * ld, t0 + tid, hist);
+  const int n_tok = (T - t0 < TOK_TILE) ? (int)(T - t0) : TOK_TILE;
+  score_tile(r, io, pre, ld, sc, LDS_SC, n_tok, t0, tid, 256);
+  __syncthreads();
+  if (tid < n_tok) route_select_lane(r, io, sc + tid * LDS_SC, pre + tid * ld + r.n_sw_rows, t0 + tid, hist);
   __syncthreads();
   for (int g = tid; g < G; g += 256) tile_counts[(int64_t)blockIdx.x * G + g] = hist[g];
 }
@@ -436,11 +446,13 @@ __global__ __launch_bounds__(512) void decode_score_kernel(const bf16_t* __restr
 // token per lane and places the tile, with the histogram handed over in LDS.
 __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
                                                           const float* __restrict__ partial, int n_slices, int T) {
-  extern __shared__ float pre[];                 // [T][n_rows + 1]
+  extern __shared__ float pre[];                 // [T][n_rows + 1], then scores [T][MAX_SCORED + 1]
   __shared__ int32_t hist[MAX_GROUPS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int ld = n_rows + 1;
+  float* sc = pre + T * ld;
+  constexpr int LDS_SC = MAX_SCORED + 1;
   for (int i = tid; i < T * n_rows; i += 256) {
     const int row = i / n_rows, col = i - row * n_rows;
     float v = 0.0f;
@@ -449,8 +461,10 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
   }
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
+  score_tile(r, io, pre, ld, sc, LDS_SC, T, 0, tid, 256);
+  __syncthreads();
   if (wave == 0) {
-    if (lane < T) route_token_lane(r, io, pre + lane * ld, lane, hist);
+    if (lane < T) route_select_lane(r, io, sc + lane * LDS_SC, pre + lane * ld + r.n_sw_rows, lane, hist);
     wave_lds_sync();
     place_tile(pl, 0, hist, lane);
   }
@@ -518,7 +532,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
 #undef CMOE_SCORE
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1);
+  const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
   hipLaunchKernelGGL(route_place_kernel, dim3(1), dim3(256), smem, s, e.r, io, pl, pre_g, 1, Ti);
   return hipGetLastError();
 }
@@ -559,7 +573,7 @@ hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, co
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    const size_t smem = sizeof(float) * (size_t)TOK_TILE * (n_rows + 1);
+    const size_t smem = sizeof(float) * (size_t)TOK_TILE * (n_rows + 1 + MAX_SCORED + 1);
     hipLaunchKernelGGL(route_tile_kernel, dim3(L.n_tok_tiles), dim3(256), smem, s, e.r, io, partial, n_slices, T,
                        tile_counts, e.G);
     return hipGetLastError();
