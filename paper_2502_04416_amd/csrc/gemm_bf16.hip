@@ -162,21 +162,24 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
   auto b_slot = [&](int kt) -> bf16_t* {
     return HR ? smem + ((2 * kt + 1) % 5) * HALF : smem + (kt % (HR ? 1 : STAGES)) * STAGE_ELEMS + BM * BKT;
   };
-  auto issue_a = [&](int kt) {
+  // part `part` of `parts` of the A (or B) half of tile kt: the DMA instructions are spread over the K step
+  auto issue_a = [&](int kt, int part, int parts) {
     bf16_t* as = a_slot(kt);
     const bool tail = k_ragged && kt == KT - 1;
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
+      if (i * parts / A_CH != part) continue;
       const void* src = a_src[i] + kt * BKT;
       if (tail && kt * BKT + a_coff[i] >= K) src = g_zero_chunk;
       dma16(src, as + (wave + i * NW) * RPI * BKT);
     }
   };
-  auto issue_b = [&](int kt) {
+  auto issue_b = [&](int kt, int part, int parts) {
     bf16_t* bs = b_slot(kt);
     const bool tail = k_ragged && kt == KT - 1;
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
+      if (i * parts / B_CH != part) continue;
       const void* src = b_src[i] + kt * BKT;
       if (tail && kt * BKT + b_coff[i] >= K) src = g_zero_chunk;
       dma16(src, bs + (wave + i * NW) * RPI * BKT);
@@ -193,13 +196,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
 
   // prologue
   if (HR) {
-    issue_a(0);
-    issue_b(0);
-    if (KT > 1) issue_a(1);
+    issue_a(0, 0, 1);
+    issue_b(0, 0, 1);
+    if (KT > 1) issue_a(1, 0, 1);
   } else {
 #pragma unroll
     for (int st = 0; st < STAGES - 1; ++st)
-      if (st < KT) { issue_a(st); issue_b(st); }
+      if (st < KT) { issue_a(st, 0, 1); issue_b(st, 0, 1); }
   }
 
   // One K tile: wait for it, multiply it and, in between the MFMAs of its first sub-step, issue the
@@ -236,13 +239,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
       __builtin_amdgcn_sched_barrier(0);
       if (ks + 1 < BKT / 16) load_frags(ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
       __builtin_amdgcn_sched_barrier(0);
+      constexpr int NKS = BKT / 16;
+      constexpr int HP = (NKS >= 4 && A_CH % 2 == 0 && B_CH % 2 == 0) ? 2 : 1;   // parts per half tile
       if (AHEAD >= 1) {
-        if (HR) {                                    // spread over the K step: B half early, A half later
-          if (ks == 0) issue_b(kt + 1);
-          if (ks == (BKT / 16) / 2 && AHEAD >= 2) issue_a(kt + 2);
+        if (HR) {                                    // spread over the K step: B half first, then the A half
+          if (ks < HP) issue_b(kt + 1, ks, HP);
+          if (AHEAD >= 2 && ks >= NKS / 2 && ks < NKS / 2 + HP) issue_a(kt + 2, ks - NKS / 2, HP);
         } else if (ks == 0) {
-          issue_a(kt + STAGES - 1);
-          issue_b(kt + STAGES - 1);
+          issue_a(kt + STAGES - 1, 0, 1);
+          issue_b(kt + STAGES - 1, 0, 1);
         }
       }
 #pragma unroll
@@ -250,8 +255,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mi], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
-      if (AHEAD >= 1 && (ks == 0 || (HR && AHEAD >= 2 && ks == (BKT / 16) / 2))) {
-        constexpr int N_LD = HR ? (A_CH > B_CH ? A_CH : B_CH) : LPT;
+      // issue order inside the sub-step: one MFMA, then its share of the DMA loads
+      const bool has_ld = AHEAD >= 1 && (HR ? (ks < HP || (AHEAD >= 2 && ks >= NKS / 2 && ks < NKS / 2 + HP)) : ks == 0);
+      if (has_ld) {
+        constexpr int N_LD = HR ? ((A_CH > B_CH ? A_CH : B_CH) / HP) : LPT;
         constexpr int PER = (N_LD + MI * NI - 1) / (MI * NI);
 #pragma unroll
         for (int i = 0; i < MI * NI; ++i) {

@@ -184,6 +184,36 @@ def test_small_bf16_decode_sizes(binding, T):
     layer.close()
 
 
+@pytest.mark.parametrize("dtype,T", [("bf16", 300), ("bf16", 9), ("fp32", 70)])
+def test_maximum_expert_counts(binding, dtype, T):
+    """The limits of the interface: 64 routed experts (one lane per expert in the wave-level top-k) and
+    top-8 selection, with a shared expert, on a prefill-sized and a decode-sized batch."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=256, d_ff=65 * 32, n_experts=65, n_shared=1, top_k=8, dtype=dtype,
+                       n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    _say("N_r=64 top-8 %s T=%d" % (dtype, T), check_flat(cfg, weights, part, x, layer.forward(x)))
+    u, b = synth.make_gate_params(cfg)
+    layer.set_gate_params(u, b)
+    _say("N_r=64 top-8 gate %s T=%d" % (dtype, T), check_flat(cfg, weights, part, x, layer.forward(x), u=u, b=b))
+    layer.close()
+
+
+def test_limits_are_rejected(binding):
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=64, d_ff=66 * 8, n_experts=66, n_shared=1, top_k=2)
+    with pytest.raises(binding.CmoeError, match="routed experts"):
+        binding.cmoe_build_from_partition(binding.make_config(cfg), *synth.make_weights(cfg),
+                                          synth.trivial_partition(cfg)["neuron_order"],
+                                          synth.trivial_partition(cfg)["rep_neuron"])
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=64, d_ff=20 * 8, n_experts=20, n_shared=1, top_k=9)
+    with pytest.raises(binding.CmoeError, match="top_k"):
+        binding.cmoe_build_from_partition(binding.make_config(cfg), *synth.make_weights(cfg),
+                                          synth.trivial_partition(cfg)["neuron_order"],
+                                          synth.trivial_partition(cfg)["rep_neuron"])
+
+
 def test_small_bf16_gate_params(binding):
     cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
     weights = synth.make_weights(cfg)
