@@ -23,6 +23,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0     # dense bf16 MFMA
 FP32_VALU_PEAK_TF = 157.3
+# gate/up launch of the headline workload (config 1, T = 2048, library partition): 296.7 MB fetched + 11.5 MB written
+MEASURED_GATE_UP_TRAFFIC_BYTES = 308.2e6
 
 
 def parse():
@@ -165,6 +167,19 @@ def main():
                     "unit": "GB/s", "traffic": None}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["avg_launch_ms"] = gu_ms
+    if prefill and cfg.cfg == 1 and T == 2048 and args.construct == "library":
+        # HBM bytes of one launch of this kernel on this workload from the two rocprofv3 --pmc runs
+        # (FETCH_SIZE x 2.000 scale, WRITE_SIZE x 1.000; profiles/cfg1_T2048_hbm_traffic.md)
+        roofline["traffic"] = MEASURED_GATE_UP_TRAFFIC_BYTES
+    # what the matrix cores sustain on register operands alone, in this process, right now
+    mfma_probe = None
+    if cfg.dtype == "bf16":
+        tf0, mhz0 = binding.cmoe_probe_mfma(False, 16384)
+        tf1, mhz1 = binding.cmoe_probe_mfma(True, 16384)
+        mfma_probe = {"zero_operands_TFLOPs": tf0, "zero_operands_MHz": mhz0, "random_operands_TFLOPs": tf1,
+                      "random_operands_MHz": mhz1}
+        if prefill:
+            roofline["frac_of_sustained_mfma"] = roofline["achieved"] / tf1
     if cfg.dtype != "bf16":
         roofline.update({"bound": "alu", "peak": FP32_VALU_PEAK_TF, "frac": roofline["achieved"] / FP32_VALU_PEAK_TF})
 
@@ -188,6 +203,7 @@ def main():
         "construct_s": construct_s,
         "event_pair_overhead_ms": ev_overhead,
         "streaming_read_reference_GBs": read_ref_gbs,
+        "mfma_probe": mfma_probe,
     }
 
     # ---- decode batches: cycle over several device copies of the layer so weights come from HBM ----

@@ -174,6 +174,15 @@ void cmoe_hier_destroy(cmoe_hier* h);
 
 /* ---- misc -------------------------------------------------------------------------------- */
 
+/* Measurement aid for the roofline of the expert contractions (Eq. 3 restricted to neuron slices,
+ * Sec. 4.1): the rate the matrix cores of the current device sustain when nothing else is in use.
+ * One workgroup of eight waves per CU issues v_mfma_f32_32x32x16_bf16 back to back out of registers,
+ * `iters` rounds of 8 per wave (1 <= iters <= 2^22), with all-zero operands (random_operands = 0) or
+ * fixed normally distributed ones (1).  Writes the achieved TFLOP/s to *tflops (host) and, if
+ * shader_mhz is not NULL, the shader clock observed meanwhile.  Allocates and frees 20 KB of device
+ * memory, runs on the null stream and synchronises; not part of the forward path. */
+int cmoe_probe_mfma(int random_operands, int iters, double* tflops, double* shader_mhz);
+
 const char* cmoe_last_error(void);   /* thread-local, never NULL */
 const char* cmoe_version(void);
 

@@ -38,7 +38,7 @@ EXPORTS = [
     "cmoe_destroy", "cmoe_hier_create", "cmoe_hier_packed_bytes", "cmoe_hier_workspace_bytes",
     "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
-    "cmoe_balanced_assignment",
+    "cmoe_balanced_assignment", "cmoe_probe_mfma",
 ]
 
 
@@ -83,6 +83,7 @@ def load():
     lib.cmoe_hier_dense_forward.argtypes = [vp, vp, i64, vp, vp, sz, vp]
     lib.cmoe_hier_destroy.argtypes = [vp]
     lib.cmoe_hier_destroy.restype = None
+    lib.cmoe_probe_mfma.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.cmoe_last_error.restype = C.c_char_p
     lib.cmoe_version.restype = C.c_char_p
     _lib = lib
@@ -143,6 +144,13 @@ def cmoe_balanced_assignment(dist: np.ndarray, m: int):
     _check(load().cmoe_balanced_assignment(dd.ctypes.data_as(C.POINTER(C.c_double)), n, n_r, m, _ip(label),
                                            C.byref(cost)), "cmoe_balanced_assignment")
     return label, cost.value
+
+
+def cmoe_probe_mfma(random_operands: bool, iters: int):
+    """(TFLOP/s, shader MHz) the matrix cores sustain on register operands alone (measurement aid)."""
+    tf, mhz = C.c_double(), C.c_double()
+    _check(load().cmoe_probe_mfma(int(random_operands), int(iters), C.byref(tf), C.byref(mhz)), "cmoe_probe_mfma")
+    return tf.value, mhz.value
 
 
 def cmoe_export_partition(layer: int, d_ff: int, n_routed: int) -> Dict[str, np.ndarray]:

@@ -19,7 +19,7 @@ namespace cmoe {
 
 // ---------------------------------------------------------------------------------- errors
 static thread_local std::string g_err = "";
-static int fail(int code, const char* fmt, ...) {
+int fail(int code, const char* fmt, ...) {
   char buf[512];
   va_list ap;
   va_start(ap, fmt);

@@ -94,6 +94,9 @@ size_t elem_size(int dtype);
 // Row stride of the packed gate/up matrix for model width d.  Rows that are a power of two apart all map
 // to the same L2 channel; the pad spreads the rows of a tile over the channels.
 int w1_row_stride(int d);
+
+// Record the calling thread's error message (what cmoe_last_error returns) and hand `code` back.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 WsLayout ws_layout(const Engine& e, int64_t T);
 
 // Kernel launchers (defined in the .hip files).  All enqueue on `s` and return the launch status.

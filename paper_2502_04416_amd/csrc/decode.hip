@@ -57,12 +57,7 @@ __device__ __forceinline__ bool find_unit(const DecArgs& p, int units_single, in
     return true;
   }
   if (u >= p.work[p.G]) return false;
-  int lo = 0, hi = p.G;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (p.work[mid] <= u) lo = mid; else hi = mid;
-  }
-  g = lo;
+  g = find_group(p.work, p.G, u);
   local = u - p.work[g];
   seg0 = p.seg_off[g];
   cnt = p.seg_off[g + 1] - seg0;

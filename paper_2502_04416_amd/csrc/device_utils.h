@@ -9,12 +9,24 @@ typedef uint16_t bf16_t;   // storage type of a bf16 element (bit pattern)
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round-to-nearest-even; NaN stays NaN
+// round-to-nearest-even; NaN stays NaN.  The cast compiles to the hardware conversion of gfx950
+// (v_cvt_pk_bf16_f32): no integer rounding sequence and no branch for the NaN case.
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+  const __bf16 h = static_cast<__bf16>(f);
+  return __builtin_bit_cast(bf16_t, h);
+}
+
+// Work lists: work[0..G] is a non-decreasing prefix array (work[0] = 0, G <= 128 groups) and item u belongs
+// to the last group g with work[g] <= u (empty groups are skipped).  Every lane looks at two entries and
+// a ballot counts the entries that do not exceed u: one round of loads instead of the seven dependent
+// ones of a binary search, which matters because every workgroup starts with this lookup.  Requires
+// u < work[G]; all lanes of the wave must call it.
+__device__ __forceinline__ int find_group(const int32_t* __restrict__ work, int G, int u) {
+  const int lane = threadIdx.x & 63;
+  const int i0 = 1 + lane, i1 = 65 + lane;
+  const bool b0 = i0 <= G && work[i0] <= u;
+  const bool b1 = i1 <= G && work[i1] <= u;
+  return __popcll(__ballot(b0)) + __popcll(__ballot(b1));
 }
 
 template <typename T> struct Elem;

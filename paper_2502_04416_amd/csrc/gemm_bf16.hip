@@ -107,12 +107,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
   if (wid >= n_work) return;
   int local = wid;
   if (!p.single) {
-    int lo = 0, hi = p.G;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (p.work[mid] <= wid) lo = mid; else hi = mid;
-    }
-    g = lo;
+    g = find_group(p.work, p.G, wid);
     local = wid - p.work[g];
     seg0 = p.seg_off[g];
     cnt = p.seg_off[g + 1] - seg0;

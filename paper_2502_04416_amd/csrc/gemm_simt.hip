@@ -42,12 +42,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_simt(SimtArgs<T> p) {
     wp = p.groups[0].width_pad;
   } else {
     if (wid >= p.work[p.G]) return;
-    int lo = 0, hi = p.G;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (p.work[mid] <= wid) lo = mid; else hi = mid;
-    }
-    g = lo;
+    g = find_group(p.work, p.G, wid);
     local = wid - p.work[g];
     seg0 = p.seg_off[g];
     cnt = p.seg_off[g + 1] - seg0;

@@ -255,3 +255,13 @@ def test_cfg2_full(binding):
 
 def test_cfg3_full(binding):
     _full(binding, 3, [0, 1, 2], n_sample=32)
+
+
+def test_mfma_probe_reports_a_plausible_rate(binding):
+    """The measurement aid runs, and all-zero operands are never slower than random ones."""
+    tf0, mhz0 = binding.cmoe_probe_mfma(False, 2048)
+    tf1, mhz1 = binding.cmoe_probe_mfma(True, 2048)
+    _say("mfma probe", {"zero_TFLOPs": tf0, "zero_MHz": mhz0, "random_TFLOPs": tf1, "random_MHz": mhz1})
+    assert 100.0 < tf1 <= tf0 * 1.05 < 2700.0
+    with pytest.raises(binding.CmoeError):
+        binding.cmoe_probe_mfma(True, 0)
