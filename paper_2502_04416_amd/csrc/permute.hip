@@ -16,7 +16,8 @@
 namespace cmoe {
 
 __global__ __launch_bounds__(64) void place_kernel(PlaceArgs p) {
-  place_tile(p, blockIdx.x, p.tile_counts, threadIdx.x);
+  const LaneWidths lw = load_lane_widths(p, threadIdx.x);
+  place_tile(p, blockIdx.x, p.tile_counts, threadIdx.x, p.sel_group, p.sel_weight, lw);
 }
 
 PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& L, int32_t* counts_out) {

@@ -32,64 +32,123 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_wave_barrier();
 }
 
+// Padded widths of the (at most two) groups a lane looks after in place_tile; a caller with other work to
+// do first requests them early so that their latency is hidden.
+struct LaneWidths { int w[MAX_GROUPS / 64]; };
+__device__ __forceinline__ LaneWidths load_lane_widths(const PlaceArgs& p, int lane) {
+  LaneWidths lw;
+#pragma unroll
+  for (int k = 0; k < MAX_GROUPS / 64; ++k) {
+    const int g = lane + 64 * k;
+    lw.w[k] = (g < p.G) ? p.groups[g].width_pad : 0;
+  }
+  return lw;
+}
+
+// Inclusive prefix sums over the 64 lanes of a wave (six exchange steps).
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int n = __shfl_up(v, o, 64);
+    if (lane >= o) v += n;
+  }
+  return v;
+}
+__device__ __forceinline__ long long wave_incl_scan(long long v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const long long n = __shfl_up(v, o, 64);
+    if (lane >= o) v += n;
+  }
+  return v;
+}
+
 // One wave places one 64-token tile.  `counts` is the per-tile histogram table [n_tiles][G] (global memory, or
-// LDS when the caller is the single-tile decode front end).  Must be called by exactly 64 threads (lane = id).
-__device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const int32_t* counts, int lane) {
-  __shared__ int32_t base[MAX_GROUPS];      // next free slot of each group for this tile
-  __shared__ int32_t total[MAX_GROUPS];
-  __shared__ int32_t wpad[MAX_GROUPS];      // padded widths (read once, in parallel)
+// LDS when the caller is the single-tile decode front end); sel_g / sel_w are the routed entries
+// [T][S_dyn] (the workspace arrays, or an LDS copy of the caller).  Must be called by exactly 64 threads
+// (lane = id).  Cost is O(S_dyn + G/64) per lane: the prefix over groups is a wave scan (two groups per
+// lane), and the rank of a token inside its group comes from a 64-bit presence mask per group that the
+// lanes build with LDS atomics, not from a pass over all groups.
+__device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const int32_t* counts, int lane,
+                                           const int32_t* sel_g, const float* sel_w, const LaneWidths& lw) {
+  constexpr int GPL = MAX_GROUPS / 64;      // groups per lane
+  __shared__ int32_t base[MAX_GROUPS];      // first slot of each group for this tile
+  __shared__ uint32_t present[MAX_GROUPS][2];   // which lanes (tokens of the tile) have an entry for the group
   const int S_all = p.n_always + p.S_dyn;
   const int64_t t = (int64_t)tile * TOK_TILE + lane;
   const bool valid = t < p.T;
-  // this token's routed entries, requested first: nothing below depends on them until the group loop
+  // this token's routed entries, requested first: nothing below depends on them until the marking pass
   int my_g[MAX_DYN];
   float my_w[MAX_DYN];
 #pragma unroll
   for (int i = 0; i < MAX_DYN; ++i) {
     const bool ok = valid && i < p.S_dyn;
-    my_g[i] = ok ? p.sel_group[t * p.S_dyn + i] : -1;
-    my_w[i] = ok ? p.sel_weight[t * p.S_dyn + i] : 0.0f;
+    my_g[i] = ok ? sel_g[t * p.S_dyn + i] : -1;
+    my_w[i] = ok ? sel_w[t * p.S_dyn + i] : 0.0f;
   }
-  // totals and the count of all preceding tiles, two groups per lane at most
-  for (int g = lane; g < MAX_GROUPS; g += 64) {
-    int tot = 0, prev = 0;
+#pragma unroll
+  for (int k = 0; k < GPL; ++k) {
+    present[lane + 64 * k][0] = 0u;
+    present[lane + 64 * k][1] = 0u;
+  }
+  // totals and the count of all preceding tiles for this lane's groups
+  int tot[GPL], prev[GPL];
+#pragma unroll
+  for (int k = 0; k < GPL; ++k) {
+    const int g = lane + 64 * k;
+    tot[k] = 0;
+    prev[k] = 0;
     if (g < p.G) {
       if (g < p.n_always) {
-        tot = (int)p.T;
-        prev = 0;
+        tot[k] = (int)p.T;
       } else {
         // independent loads, sixteen in flight at a time (the compiler does not batch them by itself)
         int i = 0;
         for (; i + 16 <= p.n_tiles; i += 16) {
           int c[16];
 #pragma unroll
-          for (int k = 0; k < 16; ++k) c[k] = counts[(int64_t)(i + k) * p.G + g];
+          for (int q = 0; q < 16; ++q) c[q] = counts[(int64_t)(i + q) * p.G + g];
 #pragma unroll
-          for (int k = 0; k < 16; ++k) {
-            tot += c[k];
-            prev += (i + k < tile) ? c[k] : 0;
+          for (int q = 0; q < 16; ++q) {
+            tot[k] += c[q];
+            prev[k] += (i + q < tile) ? c[q] : 0;
           }
         }
         for (; i < p.n_tiles; ++i) {
           const int c = counts[(int64_t)i * p.G + g];
-          tot += c;
-          prev += (i < tile) ? c : 0;
+          tot[k] += c;
+          prev[k] += (i < tile) ? c : 0;
         }
       }
     }
-    total[g] = tot;
-    base[g] = prev;
-    wpad[g] = (g < p.G) ? p.groups[g].width_pad : 0;
   }
-  wave_lds_sync();
-  // exclusive scan over groups (G <= 128: a serial pass by lane 0 is a few hundred cycles)
-  if (lane == 0) {
-    int run = 0, w1 = 0, w2 = 0;
-    int64_t h = 0;
-    for (int g = 0; g < p.G; ++g) {
-      const int cnt = total[g];
-      const int wp = wpad[g];
-      base[g] += run;
+  wave_lds_sync();                          // the cleared masks are visible to every lane
+#pragma unroll
+  for (int i = 0; i < MAX_DYN; ++i)
+    if (my_g[i] >= 0) atomicOr(&present[my_g[i]][lane >> 5], 1u << (lane & 31));
+  // exclusive prefix over groups of: slots, work items of the two contractions, hidden-buffer elements
+  int run0 = 0, w1_0 = 0, w2_0 = 0;
+  long long h0 = 0;
+#pragma unroll
+  for (int k = 0; k < GPL; ++k) {
+    const int g = lane + 64 * k;
+    const int cnt = tot[k], wp = lw.w[k];
+    int a1, a2;
+    if (p.decode) {
+      a1 = cnt > 0 ? wp / 16 : 0;
+      a2 = cnt > 0 ? p.d / 16 : 0;
+    } else {
+      a1 = cdiv(cnt, p.bm1) * cdiv(2 * wp, p.bn1);
+      a2 = cdiv(cnt, p.bm2) * cdiv(p.d, p.bn2);
+    }
+    if (g >= p.G) { a1 = 0; a2 = 0; }
+    const long long ah = (long long)cnt * wp;
+    const int run_i = wave_incl_scan(cnt, lane), w1_i = wave_incl_scan(a1, lane), w2_i = wave_incl_scan(a2, lane);
+    const long long h_i = wave_incl_scan(ah, lane);
+    const int run = run0 + run_i - cnt, w1 = w1_0 + w1_i - a1, w2 = w2_0 + w2_i - a2;
+    const long long h = h0 + h_i - ah;
+    if (g < p.G) {
+      base[g] = run + prev[k];
       if (tile == 0) {
         p.seg_off[g] = run;
         p.counts[g] = cnt;
@@ -98,24 +157,19 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
         p.h_off[g] = h;
         if (p.counts_out && g >= p.n_always) p.counts_out[g - p.n_always] = cnt;
       }
-      run += cnt;
-      if (p.decode) {
-        w1 += cnt > 0 ? wp / 16 : 0;
-        w2 += cnt > 0 ? p.d / 16 : 0;
-      } else {
-        w1 += cdiv(cnt, p.bm1) * cdiv(2 * wp, p.bn1);
-        w2 += cdiv(cnt, p.bm2) * cdiv(p.d, p.bn2);
-      }
-      h += (int64_t)cnt * wp;
     }
-    if (tile == 0) {
-      p.seg_off[p.G] = run;
-      p.work1[p.G] = w1;
-      p.work2[p.G] = w2;
-      p.h_off[p.G] = h;
-    }
+    run0 += __shfl(run_i, 63, 64);
+    w1_0 += __shfl(w1_i, 63, 64);
+    w2_0 += __shfl(w2_i, 63, 64);
+    h0 += __shfl(h_i, 63, 64);
   }
-  wave_lds_sync();
+  if (tile == 0 && lane == 0) {
+    p.seg_off[p.G] = run0;
+    p.work1[p.G] = w1_0;
+    p.work2[p.G] = w2_0;
+    p.h_off[p.G] = h0;
+  }
+  wave_lds_sync();                          // base[] and present[] are complete
   // always-on groups: identity segments
   if (valid)
     for (int a = 0; a < p.n_always; ++a) {
@@ -124,25 +178,17 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
       p.tok2slot[t * S_all + a] = slot;
       p.slot_w[t * S_all + a] = 1.0f;
     }
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  for (int g = p.n_always; g < p.G; ++g) {
-    int hit = -1;
-    float hit_w = 0.0f;
+  // routed entries: stable (token-ascending) rank inside the group = lower lanes present in its mask
+  const uint32_t lt_lo = lane >= 32 ? 0xffffffffu : ((1u << lane) - 1u);
+  const uint32_t lt_hi = lane > 32 ? ((1u << (lane - 32)) - 1u) : 0u;
 #pragma unroll
-    for (int i = 0; i < MAX_DYN; ++i) {
-      const bool m = my_g[i] == g;
-      hit = m ? i : hit;
-      hit_w = m ? my_w[i] : hit_w;
-    }
-    const uint64_t mask = __ballot(hit >= 0);
-    if (mask == 0ull) continue;
-    const int b = base[g];
-    if (hit >= 0) {
-      const int slot = b + __popcll(mask & lt_mask);
-      p.slot2tok[slot] = (int)t;
-      p.tok2slot[t * S_all + p.n_always + hit] = slot;
-      p.slot_w[t * S_all + p.n_always + hit] = hit_w;
-    }
+  for (int i = 0; i < MAX_DYN; ++i) {
+    const int g = my_g[i];
+    if (g < 0) continue;
+    const int slot = base[g] + __popc(present[g][0] & lt_lo) + __popc(present[g][1] & lt_hi);
+    p.slot2tok[slot] = (int)t;
+    p.tok2slot[t * S_all + p.n_always + i] = slot;
+    p.slot_w[t * S_all + p.n_always + i] = my_w[i];
   }
 }
 

@@ -110,62 +110,95 @@ __device__ __forceinline__ void route_token(const RouterDev& r, const RouteIO& i
   }
 }
 
-// ---- lane-per-token routing (prefill tiles) -------------------------------------------------------
-// The cross-lane arg-max above costs a chain of dependent lane exchanges per token, which is what a
-// single decode token wants but is slow when one wave has to route many tokens in turn.  Here every
-// lane of the wave routes its own token with plain loops over the (at most 64) scores of that token's
-// row in LDS, so 64 tokens are selected at once.  Same semantics: descending key, ties to the lowest id.
-struct LaneSel {
+// ---- team-per-token routing (tiles of tokens) -------------------------------------------------------
+// The cross-lane arg-max above costs a chain of dependent lane exchanges per token, which is fine for one
+// token per workgroup but slow when a wave has to route many tokens in turn.  Here four consecutive lanes
+// (a team) route one token: lane q of the team keeps the scores of experts q, q+4, q+8, ... of the
+// token's row in registers (at most 16), finds its best candidate with straight-line compares, and two
+// lane exchanges pick the team's winner.  Same semantics: descending key, ties to the lowest expert id.
+constexpr int TEAM = 4;
+constexpr int TEAM_SLOTS = MAX_SCORED / TEAM;
+
+struct TeamSel {
   int n;                   // entries written so far
 };
 
-__device__ __forceinline__ void lane_select_routed(const RouterDev& r, const RouteIO& io, const float* sc, int lo,
-                                                   int n, float scale, int group_base, int64_t t, LaneSel& st,
-                                                   int32_t* topk_ptr, int32_t* hist) {
-  float mx = -INFINITY, sum = 1.0f;
-  if (r.use_gate) {
-    for (int j = 0; j < n; ++j) mx = fmaxf(mx, r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j]);
-    sum = 0.0f;
-    for (int j = 0; j < n; ++j) sum += expf((r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j]) - mx);
+__device__ __forceinline__ void team_select_routed(const RouterDev& r, const RouteIO& io, const float* sc, int lo,
+                                                   int n, float scale, int group_base, int64_t t, TeamSel& st,
+                                                   int32_t* topk_ptr, int32_t* hist, int q) {
+  float key[TEAM_SLOTS], sp[TEAM_SLOTS];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < TEAM_SLOTS; ++u) {
+    const int j = q + TEAM * u;
+    const float s = j < n ? (r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j]) : -INFINITY;
+    key[u] = s;
+    sp[u] = 0.0f;
+    mx = fmaxf(mx, s);
   }
-  uint64_t taken = 0ull;
+  if (r.use_gate) {
+    mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+    float sum = 0.0f;
+#pragma unroll
+    for (int u = 0; u < TEAM_SLOTS; ++u) {
+      sp[u] = (q + TEAM * u < n) ? expf(key[u] - mx) : 0.0f;
+      sum += sp[u];
+    }
+    sum += __shfl_xor(sum, 1, 64);
+    sum += __shfl_xor(sum, 2, 64);
+#pragma unroll
+    for (int u = 0; u < TEAM_SLOTS; ++u) {
+      const int j = q + TEAM * u;
+      sp[u] = sp[u] / sum;
+      key[u] = j < n ? sp[u] + (io.gate_b ? io.gate_b[lo + j] : 0.0f) : -INFINITY;
+    }
+  }
+  uint32_t taken = 0u;
   for (int k = 0; k < r.top_k; ++k) {
     float best = -INFINITY, best_sp = 0.0f;
-    int bj = -1;
-    for (int j = 0; j < n; ++j) {
-      const float sk = r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j];
-      float key = sk, sp = 0.0f;
-      if (r.use_gate) {
-        sp = expf(sk - mx) / sum;
-        key = sp + (io.gate_b ? io.gate_b[lo + j] : 0.0f);
-      }
-      const bool free_j = ((taken >> j) & 1ull) == 0ull;
-      if (free_j && (bj < 0 || key > best)) {
-        best = key;
-        best_sp = sp;
+    int bj = 0x7fffffff;
+#pragma unroll
+    for (int u = 0; u < TEAM_SLOTS; ++u) {
+      const int j = q + TEAM * u;
+      const bool cand = j < n && ((taken >> u) & 1u) == 0u;
+      if (cand && (bj == 0x7fffffff || key[u] > best)) {
+        best = key[u];
+        best_sp = sp[u];
         bj = j;
       }
     }
-    taken |= 1ull << bj;
-    float gate = 1.0f;
-    if (r.use_gate && io.gate_u) gate = 1.0f + best_sp * io.gate_u[lo + bj];
-    const int g = group_base + bj;
-    io.sel_group[t * io.S_dyn + st.n] = g;
-    io.sel_weight[t * io.S_dyn + st.n] = scale * gate;
-    if (topk_ptr) topk_ptr[k] = bj;
-    atomicAdd(&hist[g], 1);
+#pragma unroll
+    for (int o = 1; o < TEAM; o <<= 1) {
+      const float ob = __shfl_xor(best, o, 64), osp = __shfl_xor(best_sp, o, 64);
+      const int oj = __shfl_xor(bj, o, 64);
+      const bool take = oj != 0x7fffffff && (bj == 0x7fffffff || ob > best || (ob == best && oj < bj));
+      best = take ? ob : best;
+      best_sp = take ? osp : best_sp;
+      bj = take ? oj : bj;
+    }
+    if ((bj & (TEAM - 1)) == q) taken |= 1u << (bj / TEAM);
+    if (q == 0) {
+      float gate = 1.0f;
+      if (r.use_gate && io.gate_u) gate = 1.0f + best_sp * io.gate_u[lo + bj];
+      const int g = group_base + bj;
+      io.sel_group[t * io.S_dyn + st.n] = g;
+      io.sel_weight[t * io.S_dyn + st.n] = scale * gate;
+      if (topk_ptr) topk_ptr[k] = bj;
+      atomicAdd(&hist[g], 1);
+    }
     ++st.n;
   }
 }
 
-// Selection for one token by one lane: `sc` holds the token's n_scored scores (Eq. 8), `lin` its linear
-// outer logits (hierarchy only).
-__device__ __forceinline__ void route_select_lane(const RouterDev& r, const RouteIO& io, const float* sc,
-                                                  const float* lin, int64_t t, int32_t* hist) {
-  LaneSel st{0};
+// Selection for one token by one team: `sc` holds the token's n_scored scores (Eq. 8), `lin` its linear
+// outer logits (hierarchy only; every lane of the team evaluates the few outer logits itself).
+__device__ __forceinline__ void route_select_team(const RouterDev& r, const RouteIO& io, const float* sc,
+                                                  const float* lin, int64_t t, int32_t* hist, int q) {
+  TeamSel st{0};
   if (r.outer_top_k == 0) {
-    lane_select_routed(r, io, sc, 0, r.n_scored, 1.0f, r.n_always, t, st,
-                       io.topk_out ? io.topk_out + t * r.top_k : nullptr, hist);
+    team_select_routed(r, io, sc, 0, r.n_scored, 1.0f, r.n_always, t, st,
+                       io.topk_out ? io.topk_out + t * r.top_k : nullptr, hist, q);
     return;
   }
   int oe[MAX_TOPK];
@@ -191,16 +224,18 @@ __device__ __forceinline__ void route_select_lane(const RouterDev& r, const Rout
     const int e = oe[i];
     const float w_e = expf(ol[i] - ol[0]) / den;
     const int gbase = e * r.groups_per_outer;
-    if (io.outer_out) io.outer_out[t * r.outer_top_k + i] = e;
+    if (q == 0 && io.outer_out) io.outer_out[t * r.outer_top_k + i] = e;
     if (r.sub_has_shared) {
-      io.sel_group[t * io.S_dyn + st.n] = gbase;
-      io.sel_weight[t * io.S_dyn + st.n] = w_e;
-      atomicAdd(&hist[gbase], 1);
+      if (q == 0) {
+        io.sel_group[t * io.S_dyn + st.n] = gbase;
+        io.sel_weight[t * io.S_dyn + st.n] = w_e;
+        atomicAdd(&hist[gbase], 1);
+      }
       ++st.n;
     }
     if (r.top_k > 0)
-      lane_select_routed(r, io, sc, e * r.n_r_sub, r.n_r_sub, w_e, gbase + r.sub_has_shared, t, st,
-                         io.topk_out ? io.topk_out + (t * r.outer_top_k + i) * r.top_k : nullptr, hist);
+      team_select_routed(r, io, sc, e * r.n_r_sub, r.n_r_sub, w_e, gbase + r.sub_has_shared, t, st,
+                         io.topk_out ? io.topk_out + (t * r.outer_top_k + i) * r.top_k : nullptr, hist, q);
   }
 }
 
@@ -325,7 +360,7 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(const bf16_t* __restri
 }
 
 // Sum the K-slice partials in slice order, then score, select and histogram a 64-token tile: the
-// 256 threads load and add the partials, then wave 0 routes the tile with one token per lane.
+// 256 threads load and add the partials, then route the tile's 64 tokens in teams of four lanes.
 __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io, const float* __restrict__ partial,
                                                          int n_slices, int64_t T, int32_t* __restrict__ tile_counts,
                                                          int G) {
@@ -378,7 +413,10 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
   const int n_tok = (T - t0 < TOK_TILE) ? (int)(T - t0) : TOK_TILE;
   score_tile(r, io, pre, ld, sc, LDS_SC, n_tok, t0, tid, 256);
   __syncthreads();
-  if (tid < n_tok) route_select_lane(r, io, sc + tid * LDS_SC, pre + tid * ld + r.n_sw_rows, t0 + tid, hist);
+  {
+    const int tok = tid / TEAM;                    // 256 threads = 64 tokens x 4 lanes
+    if (tok < n_tok) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, t0 + tok, hist, tid % TEAM);
+  }
   __syncthreads();
   for (int g = tid; g < G; g += 256) tile_counts[(int64_t)blockIdx.x * G + g] = hist[g];
 }
@@ -388,18 +426,22 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
 // (Fusing all three behind a device-wide arrival counter was tried: on this multi-die part a device-scope
 // release/acquire pair writes back and invalidates the whole L2, which costs far more than a launch.)
 //
-// decode_score_kernel: every workgroup scores 16 router rows for all tokens (v_mfma_f32_16x16x32_bf16,
-// router rows as the A operand, K split over the 8 waves, partials added in order through LDS).
+// decode_score_kernel: one wave per (16 router rows, eighth of K): v_mfma_f32_16x16x32_bf16 with the router rows
+// as the A operand, all loads of the wave in flight at once; the eight K-slice partials of a row go to
+// pre_g[slice][token][row] and are added in slice order by route_place_kernel.  Eight times as many
+// workgroups as a K loop inside the workgroup would give: the router matrix (0.5 MB at d = 4096) comes
+// cold from HBM, so the launch is one memory latency long instead of several.
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+constexpr int DEC_SLICES = 8;
 
 template <int NTT, int KSTEPS>
-__global__ __launch_bounds__(512) void decode_score_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wr,
-                                                           int d, int T, int n_rows, float* __restrict__ pre_g) {
-  __shared__ float red[8][NTT][16][17];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__global__ __launch_bounds__(64) void decode_score_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wr,
+                                                          int d, int T, int n_rows, float* __restrict__ pre_g) {
+  const int lane = threadIdx.x;
+  const int slice = blockIdx.y;
   const int r16 = lane & 15, kq = lane >> 4;
   const int row0 = blockIdx.x * 16;
-  const int kbase = wave * (KSTEPS * 32) + kq * 8;
+  const int kbase = slice * (KSTEPS * 32) + kq * 8;
   const bf16_t* wrow = wr + (int64_t)(row0 + r16) * d + kbase;
   floatx4_t acc[NTT];
 #pragma unroll
@@ -425,49 +467,53 @@ __global__ __launch_bounds__(512) void decode_score_kernel(const bf16_t* __restr
       acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], b, acc[tt], 0, 0, 0);
     }
   }
+  // D layout: lane holds rows kq*4 .. kq*4+3 of column (token) r16
 #pragma unroll
-  for (int tt = 0; tt < NTT; ++tt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) red[wave][tt][kq * 4 + i][r16] = acc[tt][i];
-  __syncthreads();
-  for (int e = tid; e < NTT * 256; e += 512) {
-    const int tt = e >> 8, tok = (e >> 4) & 15, rr = e & 15;
-    const int col = tt * 16 + tok;
-    if (col >= T) continue;
-    float v = 0.0f;
-#pragma unroll
-    for (int w = 0; w < 8; ++w) v += red[w][tt][rr][tok];
-    pre_g[(int64_t)col * n_rows + row0 + rr] = v;
+  for (int tt = 0; tt < NTT; ++tt) {
+    const int col = tt * 16 + r16;
+    if (col < T) *reinterpret_cast<floatx4_t*>(pre_g + ((int64_t)slice * T + col) * n_rows + row0 + kq * 4) = acc[tt];
   }
 }
 
 // route_place_kernel: a batch that fits one 64-token tile is selected and permuted by one workgroup:
-// the 256 threads add the K-slice partials of the pre-activations in slice order, then wave 0 routes one
-// token per lane and places the tile, with the histogram handed over in LDS.
+// the 256 threads add the K-slice partials of the pre-activations in slice order and route the tokens in
+// teams of four lanes, then wave 0 places the tile.  Histogram and routed entries are handed over in LDS (the
+// workspace copies of the entries are not written: nothing after this kernel reads them).
 __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
                                                           const float* __restrict__ partial, int n_slices, int T) {
   extern __shared__ float pre[];                 // [T][n_rows + 1], then scores [T][MAX_SCORED + 1]
   __shared__ int32_t hist[MAX_GROUPS];
+  __shared__ int32_t sel_g[32 * MAX_DYN];
+  __shared__ float sel_w[32 * MAX_DYN];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int ld = n_rows + 1;
   float* sc = pre + T * ld;
   constexpr int LDS_SC = MAX_SCORED + 1;
+  LaneWidths lw;
+  if (wave == 0) lw = load_lane_widths(pl, lane);          // needed last, requested first
   for (int i = tid; i < T * n_rows; i += 256) {
     const int row = i / n_rows, col = i - row * n_rows;
-    float v = 0.0f;
-    for (int ks = 0; ks < n_slices; ++ks) v += partial[(int64_t)ks * T * n_rows + i];
-    pre[row * ld + col] = v;
+    float v[DEC_SLICES];
+#pragma unroll
+    for (int ks = 0; ks < DEC_SLICES; ++ks) v[ks] = ks < n_slices ? partial[(int64_t)ks * T * n_rows + i] : 0.0f;
+    float acc = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < DEC_SLICES; ++ks) acc += v[ks];
+    pre[row * ld + col] = acc;
   }
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
   score_tile(r, io, pre, ld, sc, LDS_SC, T, 0, tid, 256);
   __syncthreads();
-  if (wave == 0) {
-    if (lane < T) route_select_lane(r, io, sc + lane * LDS_SC, pre + lane * ld + r.n_sw_rows, lane, hist);
-    wave_lds_sync();
-    place_tile(pl, 0, hist, lane);
+  io.sel_group = sel_g;
+  io.sel_weight = sel_w;
+  {
+    const int tok = tid / TEAM;                    // T <= 32 tokens x 4 lanes: the first two waves
+    if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM);
   }
+  __syncthreads();
+  if (wave == 0) place_tile(pl, 0, hist, lane, sel_g, sel_w, lw);
 }
 
 // Per-tile histogram of the routed entries (used when the scoring kernel did not produce one).
@@ -508,10 +554,10 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   const PlaceArgs pl = make_place_args(e, T, ws, L, counts_out);
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
   float* pre_g = reinterpret_cast<float*>(ws + L.scores);
-  dim3 grid(n_rows / 16), block(512);
+  dim3 grid(n_rows / 16, DEC_SLICES), block(64);
   const bf16_t* xx = static_cast<const bf16_t*>(x);
   const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
-  const int ksteps = e.d / 256;
+  const int ksteps = e.d / 256;                 // K steps of 32 per slice: d / (8 slices * 32)
   const int Ti = (int)T;
 #define CMOE_SCORE(NTT, KS) hipLaunchKernelGGL((decode_score_kernel<NTT, KS>), grid, block, 0, s, xx, ww, e.d, Ti, n_rows, pre_g)
   if (T <= 16) {
@@ -533,7 +579,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
-  hipLaunchKernelGGL(route_place_kernel, dim3(1), dim3(256), smem, s, e.r, io, pl, pre_g, 1, Ti);
+  hipLaunchKernelGGL(route_place_kernel, dim3(1), dim3(256), smem, s, e.r, io, pl, pre_g, DEC_SLICES, Ti);
   return hipGetLastError();
 }
 
