@@ -102,8 +102,8 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
   L.tile_counts = take(sizeof(int32_t) * (size_t)L.n_tok_tiles * e.G);
   L.seg_off = take(sizeof(int32_t) * (e.G + 1));
   L.counts = take(sizeof(int32_t) * (e.G + 1));
-  L.work1 = take(sizeof(int32_t) * (e.G + 1));
-  L.work2 = take(sizeof(int32_t) * (e.G + 1));
+  L.work1 = take(sizeof(int32_t) * (e.G + 1 + 9));       // + first work item of each XCD's share
+  L.work2 = take(sizeof(int32_t) * (e.G + 1 + 9));
   L.h_off = take(sizeof(int64_t) * (e.G + 1));
   L.slot2tok = take(sizeof(int32_t) * L.n_slots);
   L.tok2slot = take(sizeof(int32_t) * L.n_slots);

@@ -55,7 +55,8 @@ struct WsLayout {
   size_t sel_group, sel_weight;      // [T][S_dyn] int32 / float   (router -> permute)
   size_t tile_counts;                // [n_tok_tiles][G] int32
   size_t seg_off, counts;            // [G+1] / [G] int32
-  size_t work1, work2;               // [G+1] int32: prefix of work items of the two grouped GEMMs
+  size_t work1, work2;               // [G+1] int32: prefix of work items of the two grouped GEMMs, then [9]: first
+                                     // item of each XCD's contiguous share
   size_t h_off;                      // [G+1] int64: element offset of each group's rows in H
   size_t slot2tok;                   // [n_slots] int32
   size_t tok2slot, slot_w;           // [T][S_all] int32 / float

@@ -98,11 +98,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
   } else {
     n_work = p.work[p.G];
   }
+  // Workgroup b runs on XCD b % 8 (own L2).  Each XCD works through a contiguous range of the list so that
+  // tiles sharing an operand meet in one L2: equal parts of a single-group problem, and for work lists the
+  // shares of equal estimated cost that the permutation kernel left behind the prefix array.
   int wid = blockIdx.x;
   if (p.xcd_remap) {
-    const int chunk = (n_work + 7) >> 3;
-    if ((wid >> 3) >= chunk) return;
-    wid = (wid & 7) * chunk + (wid >> 3);
+    if (p.single) {
+      const int chunk = (n_work + 7) >> 3;
+      if ((wid >> 3) >= chunk) return;
+      wid = (wid & 7) * chunk + (wid >> 3);
+    } else {
+      const int first = p.work[p.G + 1 + (wid & 7)], end = p.work[p.G + 2 + (wid & 7)];
+      wid = first + (wid >> 3);
+      if (wid >= end) return;
+    }
   }
   if (wid >= n_work) return;
   int local = wid;
@@ -359,8 +368,10 @@ static int env_int(const char* name, int dflt) {
 static int cfg_index(int which, const Engine& e, int64_t T) {
   int dflt = 0;
   if (which == 2) {
+    // the largest tile that still gives every CU one: 256x256, else 256x128, else 128x128 (measured on
+    // T = 2048..8192: a half-empty chip costs more than the smaller tile's lower arithmetic intensity)
     const int64_t tiles_256 = ((T * e.S_all() + 255) / 256) * ((e.d + 255) / 256);
-    dflt = tiles_256 >= 256 ? 2 : 1;
+    dflt = tiles_256 >= 256 ? 0 : (2 * tiles_256 >= 256 ? 4 : 3);
   }
   int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", dflt);
   if (c < 0 || c >= kNumCfgs) c = dflt;
@@ -438,7 +449,19 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.C = (e.S_all() == 1) ? static_cast<bf16_t*>(y) : reinterpret_cast<bf16_t*>(ws + L.y_slots);
   a.work = reinterpret_cast<const int32_t*>(ws + L.work2);
   a.slot2tok = nullptr;
-  a.n_blocks = (int)round_up64(gemm_work_bound(e, T, 2), 8);
+  {
+    // An XCD's share of the down list has equal cost, not equal length: with groups of unequal width the
+    // share made of the cheapest tiles is longer than an eighth of the list.
+    const int64_t bound = gemm_work_bound(e, T, 2);
+    int c_min = 1 << 30, c_max = 1;
+    for (int g = 0; g < e.G; ++g) {
+      const int c = cdiv(e.width_pad_host[g], 64) + 4;
+      c_min = std::min(c_min, c);
+      c_max = std::max(c_max, c);
+    }
+    const int64_t share = std::min<int64_t>(bound, (bound * c_max + 8 * c_min - 1) / (8 * c_min) + 2);
+    a.n_blocks = (int)(remap && !a.single ? 8 * share : round_up64(bound, 8));
+  }
   return launch_cfg<2>(cfg_index(2, e, T), a, s);
 }
 

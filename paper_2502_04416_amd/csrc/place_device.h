@@ -5,6 +5,9 @@
 
 namespace cmoe {
 
+constexpr int N_XCD = 8;              // dies with an L2 of their own; workgroup b runs on die b % 8
+constexpr int TILE_FIXED_COST = 4;    // prologue + epilogue of a tile, in units of one 64-deep K step
+
 struct PlaceArgs {
   const int32_t* sel_group;    // [T][S_dyn]
   const float* sel_weight;     // [T][S_dyn]
@@ -12,8 +15,8 @@ struct PlaceArgs {
   const GroupDev* groups;
   int32_t* seg_off;            // [G+1]
   int32_t* counts;             // [G]
-  int32_t* work1;              // [G+1]
-  int32_t* work2;              // [G+1]
+  int32_t* work1;              // [G+1] prefix of work items, then [N_XCD+1] first item of each die's share
+  int32_t* work2;              // same for the down contraction
   int64_t* h_off;              // [G+1]
   int32_t* slot2tok;           // [n_slots]
   int32_t* tok2slot;           // [T][S_all]
@@ -129,6 +132,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
   // exclusive prefix over groups of: slots, work items of the two contractions, hidden-buffer elements
   int run0 = 0, w1_0 = 0, w2_0 = 0;
   long long h0 = 0;
+  int n1[GPL], n2[GPL], w1x[GPL], w2x[GPL];     // work items of this lane's groups and their exclusive prefix
 #pragma unroll
   for (int k = 0; k < GPL; ++k) {
     const int g = lane + 64 * k;
@@ -147,6 +151,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     const long long h_i = wave_incl_scan(ah, lane);
     const int run = run0 + run_i - cnt, w1 = w1_0 + w1_i - a1, w2 = w2_0 + w2_i - a2;
     const long long h = h0 + h_i - ah;
+    n1[k] = a1; n2[k] = a2; w1x[k] = w1; w2x[k] = w2;
     if (g < p.G) {
       base[g] = run + prev[k];
       if (tile == 0) {
@@ -163,11 +168,49 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     w2_0 += __shfl(w2_i, 63, 64);
     h0 += __shfl(h_i, 63, 64);
   }
-  if (tile == 0 && lane == 0) {
-    p.seg_off[p.G] = run0;
-    p.work1[p.G] = w1_0;
-    p.work2[p.G] = w2_0;
-    p.h_off[p.G] = h0;
+  if (tile == 0) {
+    if (lane == 0) {
+      p.seg_off[p.G] = run0;
+      p.work1[p.G] = w1_0;
+      p.work2[p.G] = w2_0;
+      p.h_off[p.G] = h0;
+    }
+    // Where each XCD's share of a work list starts (entries G+1 .. G+9 of the list): contiguous ranges of
+    // equal estimated cost, so that the tiles sharing operands stay in one L2 while the eight dies finish
+    // together.  The gate/up tiles all have the full depth d; a down tile costs its group's width
+    // (the shared group is N_s times as deep as a routed expert) plus a fixed part for prologue and epilogue.
+    __shared__ int32_t xs[2][N_XCD + 1];
+    if (lane <= N_XCD) {
+      xs[0][lane] = lane == N_XCD ? w1_0 : 0;
+      xs[1][lane] = lane == N_XCD ? w2_0 : 0;
+    }
+    wave_lds_sync();
+    int cx[GPL], c2[GPL];
+    int c0 = 0;
+#pragma unroll
+    for (int k = 0; k < GPL; ++k) {
+      c2[k] = cdiv(lw.w[k], 64) + TILE_FIXED_COST;
+      const int cost = n2[k] * c2[k];
+      const int ci = wave_incl_scan(cost, lane);
+      cx[k] = c0 + ci - cost;
+      c0 += __shfl(ci, 63, 64);
+    }
+#pragma unroll
+    for (int x = 1; x < N_XCD; ++x) {
+#pragma unroll
+      for (int k = 0; k < GPL; ++k) {
+        // list 1: equal item counts; list 2: equal cost
+        const int t1 = (int)((long long)x * w1_0 / N_XCD);
+        if (n1[k] > 0 && w1x[k] <= t1 && t1 < w1x[k] + n1[k]) xs[0][x] = t1;
+        const int t2 = (int)((long long)x * c0 / N_XCD);
+        if (n2[k] > 0 && cx[k] <= t2 && t2 < cx[k] + n2[k] * c2[k]) xs[1][x] = w2x[k] + (t2 - cx[k]) / c2[k];
+      }
+    }
+    wave_lds_sync();
+    if (lane <= N_XCD) {
+      p.work1[p.G + 1 + lane] = xs[0][lane];
+      p.work2[p.G + 1 + lane] = xs[1][lane];
+    }
   }
   wave_lds_sync();                          // base[] and present[] are complete
   // always-on groups: identity segments
