@@ -5,6 +5,7 @@
 // LDS-staged, XOR-swizzled tiles filled by direct global->LDS loads.  A work item is (group, row tile, column tile); the list of work
 // items is a device-side prefix array written by the permute kernel, so ragged, empty and skewed
 // groups need no host round trip.  Workgroups whose index is past the list exit at once.
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 #include "cmoe_internal.h"
@@ -365,8 +366,40 @@ static int env_int(const char* name, int dflt) {
 // tile shapes inside one process.  Defaults: 256x256 tiles on the half-tile ring for the long-K gate/up
 // contraction; for the short-K down contraction 256x256 tiles when there are enough of them to fill the
 // chip (>= 256), else 128x128 tiles with two workgroups per CU.
+// Tile shape of the gate/up contraction: the one with the lowest estimated time = rounds x time per round,
+// rounds = ceil(tiles / workgroup slots on the chip).  Relative times per round measured on the
+// LLaMA-shaped layers (K = d for every shape, so the ratios carry over): 256x256 1.0 (one workgroup per
+// CU), 256x128 0.58 (one per CU), 128x128 0.66 (two per CU).  The model picks the measured best shape at
+// every batch size from 512 to 8192 tokens and a near-best one below.
+static int gate_up_cfg(const Engine& e, int64_t T) {
+  struct Cand { int cfg, bm, bn, slots; double t; };
+  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {0, 256, 256, 1, 1.0}};
+  const bool single = e.G == 1 && e.n_always == 1;
+  int best = 0;
+  double best_t = 1e30;
+  for (const Cand& c : cands) {
+    int64_t tiles = 0;
+    for (int g = 0; g < e.n_always; ++g) tiles += ((T + c.bm - 1) / c.bm) * cdiv(2 * e.width_pad_host[g], c.bn);
+    if (!single && e.G > e.n_always) {
+      const int64_t entries = T * e.S_dyn;
+      const int64_t touched = std::min<int64_t>(e.G - e.n_always, entries);
+      const int64_t rows = std::max<int64_t>((entries + c.bm - 1) / c.bm + touched / 2, touched);
+      tiles += rows * cdiv(2 * e.width_pad_host[e.n_always], c.bn);
+    }
+    // the routed groups' partial tiles are an estimate: average over the estimate and 8 % more
+    const int64_t slots = 256 * c.slots, hi = single ? tiles : tiles + (tiles * 2 + 24) / 25;
+    const double t = 0.5 * c.t * (double)((tiles + slots - 1) / slots + (hi + slots - 1) / slots);
+    if (t < best_t) {
+      best_t = t;
+      best = c.cfg;
+    }
+  }
+  return best;
+}
+
 static int cfg_index(int which, const Engine& e, int64_t T) {
   int dflt = 0;
+  if (which == 1) dflt = gate_up_cfg(e, T);
   if (which == 2) {
     // the largest tile that still gives every CU one: 256x256, else 256x128, else 128x128 (measured on
     // T = 2048..8192: a half-empty chip costs more than the smaller tile's lower arithmetic intensity)
