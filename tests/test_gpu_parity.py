@@ -228,15 +228,16 @@ def test_small_bf16_gate_params(binding):
 
 # ---------------------------------------------------------------------------------- full-size configs
 
-def _full(binding, ci, batches, n_sample=48):
+def _full(binding, ci, batches, n_sample=48, sizes=None):
+    """Full-size layer `ci` on its evaluation batches, or (sizes) on the first `n` tokens of batch 0."""
     cfg = synth.CONFIGS[ci]
     weights = synth.make_weights(cfg)
     part = synth.trivial_partition(cfg)
     src = synth.make_token_source(cfg)
     layer = _layer(binding, cfg, weights, part)
     rng = np.random.Generator(np.random.PCG64(99 + ci))
-    for bi in batches:
-        x = src.eval_batch(bi)
+    for bi in (batches if sizes is None else sizes):
+        x = src.eval_batch(bi) if sizes is None else src.eval_batch(0, n=bi)
         T = x.shape[0]
         sample = np.sort(rng.choice(T, size=min(T, n_sample), replace=False))
         out = layer.forward(x)
@@ -247,6 +248,12 @@ def _full(binding, ci, batches, n_sample=48):
 
 def test_cfg1_full(binding):
     _full(binding, 1, [0, 1, 2])
+
+
+def test_cfg1_mid_batches(binding):
+    """Batch sizes between the decode path and the large-tile regime: the contraction kernels run their
+    128x128 and 256x128 tile shapes at the layer's real depth."""
+    _full(binding, 1, None, n_sample=32, sizes=[33, 300, 1000, 3072])
 
 
 def test_cfg2_full(binding):
