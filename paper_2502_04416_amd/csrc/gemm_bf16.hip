@@ -348,12 +348,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
 // stages >= 2: ring of whole K tiles; stages == 0: ring of five half tiles.
 struct TileCfg { int bm, bn, wgm, wgn, stages, bk; };
 static const TileCfg kCfgs[] = {
-    {256, 256, 2, 4, 0, 64},   // 0: half-tile ring, eight waves of 128x64 (default for gate/up)
-    {128, 128, 2, 2, 2, 64},   // 1: two stages, two workgroups per CU (default for down)
+    {256, 256, 2, 4, 0, 64},   // 0: half-tile ring, eight waves of 128x64
+    {128, 128, 2, 2, 2, 64},   // 1: two stages, two workgroups per CU
     {256, 256, 2, 4, 2, 64},   // 2
     {128, 128, 2, 2, 0, 64},   // 3
     {256, 128, 4, 2, 3, 64},   // 4
     {256, 256, 2, 4, 4, 32},   // 5
+    {256, 256, 2, 2, 0, 64},   // 6: half-tile ring, four waves of 128x128, one per SIMD: a third less LDS read
+                               //    traffic than 0, 5-8 % faster under the power limit (the large-tile default)
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -368,12 +370,13 @@ static int env_int(const char* name, int dflt) {
 // chip (>= 256), else 128x128 tiles with two workgroups per CU.
 // Tile shape of the gate/up contraction: the one with the lowest estimated time = rounds x time per round,
 // rounds = ceil(tiles / workgroup slots on the chip).  Relative times per round measured on the
-// LLaMA-shaped layers (K = d for every shape, so the ratios carry over): 256x256 1.0 (one workgroup per
-// CU), 256x128 0.58 (one per CU), 128x128 0.66 (two per CU).  The model picks the measured best shape at
+// LLaMA-shaped layers (K = d for every shape, so the ratios carry over), in units of the eight-wave
+// 256x256 tile: 256x256 with four waves 0.95 (one workgroup per CU), 256x128 0.58 (one per CU), 128x128
+// 0.66 (two per CU).  The model picks the measured best shape at
 // every batch size from 512 to 8192 tokens and a near-best one below.
 static int gate_up_cfg(const Engine& e, int64_t T) {
   struct Cand { int cfg, bm, bn, slots; double t; };
-  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {0, 256, 256, 1, 1.0}};
+  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}};
   const bool single = e.G == 1 && e.n_always == 1;
   int best = 0;
   double best_t = 1e30;
@@ -404,7 +407,10 @@ static int cfg_index(int which, const Engine& e, int64_t T) {
     // the largest tile that still gives every CU one: 256x256, else 256x128, else 128x128 (measured on
     // T = 2048..8192: a half-empty chip costs more than the smaller tile's lower arithmetic intensity)
     const int64_t tiles_256 = ((T * e.S_all() + 255) / 256) * ((e.d + 255) / 256);
-    dflt = tiles_256 >= 256 ? 0 : (2 * tiles_256 >= 256 ? 4 : 3);
+    // 256x256: four waves when the contraction is deep (dense FFN: K = d_h), eight when it is an expert's
+    // width (a few K steps per tile: the eight-wave tile gets through prologue and epilogue faster)
+    const int big = e.max_width_pad >= 2048 ? 6 : 0;
+    dflt = tiles_256 >= 256 ? big : (2 * tiles_256 >= 256 ? 4 : 3);
   }
   int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", dflt);
   if (c < 0 || c >= kNumCfgs) c = dflt;
@@ -448,6 +454,7 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
     case 2: return launch_dma<256, 256, 64, 2, 2, 4, MODE>(a, s);
     case 3: return launch_dma<128, 128, 64, 0, 2, 2, MODE>(a, s);
     case 4: return launch_dma<256, 128, 64, 3, 4, 2, MODE>(a, s);
+    case 6: return launch_dma<256, 256, 64, 0, 2, 2, MODE>(a, s);
     default: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
   }
 }
