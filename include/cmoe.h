@@ -103,6 +103,17 @@ int cmoe_export_partition(const cmoe_layer* layer, int32_t* neuron_order, int32_
  * May be called before or after cmoe_upload; takes effect at the next forward. */
 int cmoe_set_gate_params(cmoe_layer* layer, const float* u, const float* b);
 
+/* Copies the current gate parameters to host arrays u [N_r], b [N_r] (either may be NULL). */
+int cmoe_get_gate_params(const cmoe_layer* layer, float* u, float* b);
+
+/* One load-balancing step of Sec. 4.3 (text after Eq. 9) from the per-expert token counts a forward
+ * returned (host int32 [N_r], e.g. a copy of cmoe_forward's counts_dev): with p_i = counts_i / sum(counts)
+ * and the uniform target p* = 1/N_r, b_i decreases by gamma where p_i > p*, increases by gamma where
+ * p_i < p*, and is unchanged where they are equal or when no token was routed.  The paper uses
+ * gamma = 1e-3.  u is kept.  Same rules as cmoe_set_gate_params (takes effect at the next forward;
+ * not for layers inside a hierarchy).  CMOE_EINVAL on a negative count or a negative gamma. */
+int cmoe_update_bias(cmoe_layer* layer, const int32_t* counts, float gamma);
+
 /* Bytes of device memory cmoe_upload needs for the packed weights (expert-sliced copy for the
  * MoE forward, an unpadded copy for the dense baseline, and the router columns). */
 size_t cmoe_packed_bytes(const cmoe_layer* layer);

@@ -319,6 +319,22 @@ def moe_forward_one_token(x_row, w_gate, w_up, w_down, neuron_order, rep_neuron,
     return {k: v[0] for k, v in out.items()}
 
 
+def bias_update(b: np.ndarray, counts: np.ndarray, gamma: float = 1e-3) -> np.ndarray:
+    """One load-balancing step (Sec. 4.3, text after Eq. 9): with p_i = counts_i / sum(counts) the
+    utilisation of routed expert i and p* = 1/N_r, b_i decreases by gamma where p_i > p*, increases by
+    gamma where p_i < p*, and stays where p_i = p*.  Nothing changes when no token was routed.
+    The comparison is done on integers (counts_i * N_r against sum(counts)), which is the same test."""
+    b = np.asarray(b, dtype=F64).copy()
+    c = np.asarray(counts, dtype=np.int64)
+    total = int(c.sum())
+    if total == 0:
+        return b
+    n_r = c.shape[0]
+    b[c * n_r > total] -= gamma
+    b[c * n_r < total] += gamma
+    return b
+
+
 # --------------------------------------------------------------------------- hierarchical
 
 def outer_route(x, w_router, offsets, outer_top_k: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:

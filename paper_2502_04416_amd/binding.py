@@ -38,7 +38,7 @@ EXPORTS = [
     "cmoe_destroy", "cmoe_hier_create", "cmoe_hier_packed_bytes", "cmoe_hier_workspace_bytes",
     "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
-    "cmoe_balanced_assignment", "cmoe_probe_mfma",
+    "cmoe_balanced_assignment", "cmoe_probe_mfma", "cmoe_get_gate_params", "cmoe_update_bias",
 ]
 
 
@@ -62,6 +62,8 @@ def load():
                                              C.POINTER(C.c_double)]
     lib.cmoe_export_partition.argtypes = [vp, i32p, i32p, f32p, C.POINTER(C.c_double)]
     lib.cmoe_set_gate_params.argtypes = [vp, f32p, f32p]
+    lib.cmoe_get_gate_params.argtypes = [vp, f32p, f32p]
+    lib.cmoe_update_bias.argtypes = [vp, i32p, C.c_float]
     lib.cmoe_packed_bytes.argtypes = [vp]
     lib.cmoe_packed_bytes.restype = sz
     lib.cmoe_workspace_bytes.argtypes = [vp, i64]
@@ -166,6 +168,18 @@ def cmoe_set_gate_params(layer: int, u, b) -> None:
     uu = None if u is None else _f32(u)
     bb = None if b is None else _f32(b)
     _check(load().cmoe_set_gate_params(layer, _fp(uu), _fp(bb)), "cmoe_set_gate_params")
+
+
+def cmoe_get_gate_params(layer: int, n_routed: int):
+    u = np.empty(n_routed, dtype=np.float32)
+    b = np.empty(n_routed, dtype=np.float32)
+    _check(load().cmoe_get_gate_params(layer, _fp(u), _fp(b)), "cmoe_get_gate_params")
+    return u, b
+
+
+def cmoe_update_bias(layer: int, counts, gamma: float = 1e-3) -> None:
+    c = np.ascontiguousarray(counts, dtype=np.int32)
+    _check(load().cmoe_update_bias(layer, _ip(c), float(gamma)), "cmoe_update_bias")
 
 
 def cmoe_packed_bytes(layer: int) -> int:
@@ -325,6 +339,14 @@ class Layer(_DeviceMixin):
 
     def set_gate_params(self, u, b):
         cmoe_set_gate_params(self.h, u, b)
+
+    def gate_params(self):
+        """(u, b) as currently stored in the layer."""
+        return cmoe_get_gate_params(self.h, self.cfg.n_routed)
+
+    def update_bias(self, counts, gamma: float = 1e-3):
+        """One load-balancing step of Sec. 4.3 from the per-expert token counts of a forward."""
+        cmoe_update_bias(self.h, counts, gamma)
 
     def forward_device(self, x_dev, y_dev, topk=None, scores=None, counts=None):
         """x_dev, y_dev: torch cuda tensors [T, d] in the layer dtype; enqueues only."""

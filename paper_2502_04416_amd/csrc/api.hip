@@ -439,6 +439,34 @@ int cmoe_set_gate_params(cmoe_layer* L, const float* u, const float* b) {
   return CMOE_OK;
 }
 
+int cmoe_get_gate_params(const cmoe_layer* L, float* u, float* b) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  for (int j = 0; j < L->n_r; ++j) {
+    if (u) u[j] = L->u[j];
+    if (b) b[j] = L->b[j];
+  }
+  return CMOE_OK;
+}
+
+int cmoe_update_bias(cmoe_layer* L, const int32_t* counts, float gamma) {
+  if (!L || !counts) return fail(CMOE_EINVAL, "null argument");
+  if (!(gamma >= 0.0f)) return fail(CMOE_EINVAL, "gamma must be non-negative");
+  int64_t total = 0;
+  for (int j = 0; j < L->n_r; ++j) {
+    if (counts[j] < 0) return fail(CMOE_EINVAL, "counts[%d] is negative", j);
+    total += counts[j];
+  }
+  if (total == 0) return CMOE_OK;
+  std::vector<float> b(L->b.begin(), L->b.begin() + L->n_r);
+  for (int j = 0; j < L->n_r; ++j) {
+    const int64_t c = (int64_t)counts[j] * L->n_r;       // p_j > 1/N_r  <=>  counts_j * N_r > total
+    if (c > total) b[j] -= gamma;
+    else if (c < total) b[j] += gamma;
+  }
+  std::vector<float> u(L->u.begin(), L->u.begin() + L->n_r);
+  return cmoe_set_gate_params(L, L->has_u ? u.data() : nullptr, b.data());
+}
+
 // device buffer of a flat layer: [moe W1][moe W2][dense W1][dense W2][router][moe groups][dense groups][u][b]
 struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, total; };
 static FlatOffsets flat_offsets(const cmoe_layer* L) {

@@ -226,6 +226,32 @@ def test_small_bf16_gate_params(binding):
     layer.close()
 
 
+def test_bias_update_loop_balances_the_load(binding):
+    """Sec. 4.3: forward -> per-expert counts -> cmoe_update_bias, repeated on one batch.  The library's
+    biases follow the oracle's step applied to the same counts, the most loaded expert's share falls,
+    and the forward with the final biases still matches the oracle."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=777)
+    layer = _layer(binding, cfg, weights, part)
+    layer.set_gate_params(None, np.zeros(cfg.n_routed, dtype=np.float32))
+    ref_b = np.zeros(cfg.n_routed)
+    shares = []
+    for _ in range(120):
+        counts = layer.forward(x)["counts"]
+        assert counts.sum() == 777 * cfg.top_k
+        shares.append(counts.max() / counts.sum())
+        layer.update_bias(counts, 2e-3)
+        ref_b = O.bias_update(ref_b, counts, 2e-3)
+    u, b = layer.gate_params()
+    assert np.abs(b.astype(np.float64) - ref_b).max() < 1e-5
+    _say("bias loop", {"share_first": shares[0], "share_last": shares[-1], "uniform": 1.0 / cfg.n_routed})
+    assert shares[-1] < 0.65 * shares[0]
+    _say("bias loop parity", check_flat(cfg, weights, part, x, layer.forward(x), u=None, b=b))
+    layer.close()
+
+
 # ---------------------------------------------------------------------------------- full-size configs
 
 def _full(binding, ci, batches, n_sample=48, sizes=None):

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "cmoe.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(cmoe_[a-z_]+)\s*\(", header))
-    assert len(declared) >= 22
+    assert len(declared) >= 25
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -96,3 +96,28 @@ def test_generator_rounding_matches_torch():
     import torch
     x = (np.random.default_rng(0).standard_normal(100000) * 3).astype(np.float32)
     assert np.array_equal(synth.round_to_bf16(x), torch.from_numpy(x).bfloat16().float().numpy())
+
+
+def test_update_bias_matches_the_oracle_on_the_host(lib):
+    """cmoe_update_bias is host arithmetic (Sec. 4.3): same result as the oracle's step, fp32 vs fp64."""
+    from oracle import cmoe_oracle as O
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=16, d_ff=48, n_experts=6, n_shared=1, top_k=2)
+    w, p = synth.make_weights(cfg), synth.trivial_partition(cfg)
+    h = binding.cmoe_build_from_partition(binding.make_config(cfg), *w, p["neuron_order"], p["rep_neuron"])
+    u0 = np.linspace(-0.5, 0.5, cfg.n_routed).astype(np.float32)
+    b0 = np.linspace(0.3, -0.3, cfg.n_routed).astype(np.float32)
+    binding.cmoe_set_gate_params(h, u0, b0)
+    ref = b0.astype(np.float64)
+    rng = np.random.Generator(np.random.PCG64(3))
+    for _ in range(5):
+        counts = rng.integers(0, 50, size=cfg.n_routed)
+        binding.cmoe_update_bias(h, counts, 1e-3)
+        ref = O.bias_update(ref, counts, 1e-3)
+    u, b = binding.cmoe_get_gate_params(h, cfg.n_routed)
+    assert np.array_equal(u, u0)
+    assert np.abs(b.astype(np.float64) - ref).max() < 1e-6
+    binding.cmoe_update_bias(h, np.zeros(cfg.n_routed, dtype=np.int32), 1e-3)        # no routed token: unchanged
+    assert np.array_equal(binding.cmoe_get_gate_params(h, cfg.n_routed)[1], b)
+    with pytest.raises(binding.CmoeError):
+        binding.cmoe_update_bias(h, -np.ones(cfg.n_routed, dtype=np.int32), 1e-3)
+    binding.cmoe_destroy(h)

@@ -467,3 +467,34 @@ def test_flop_bookkeeping_ratio():
     moe, dense = O.layer_flops_per_token(d, d_h // 8, 3, 5, 3)
     assert dense == 6 * d * d_h
     assert moe / dense == pytest.approx(0.75 + 4 * 5 / (6 * d_h), rel=1e-12)
+
+
+# ---- load-balancing step (Sec. 4.3, text after Eq. 9) ---------------------------------------------
+
+def test_bias_update_worked_by_hand():
+    # N_r = 3, p* = 1/3; counts 5, 1, 2 of 8: p = 0.625 (over), 0.125 (under), 0.25 (under)
+    b = O.bias_update(np.array([0.0, 0.5, -0.25]), np.array([5, 1, 2]), gamma=1e-3)
+    assert np.allclose(b, [-0.001, 0.501, -0.249], atol=1e-15)
+    # exactly at the target nothing moves; with no routed token nothing moves
+    assert np.array_equal(O.bias_update(np.array([0.1, 0.2]), np.array([4, 4]), 1e-3), [0.1, 0.2])
+    assert np.array_equal(O.bias_update(np.array([0.1, 0.2]), np.array([0, 0]), 1e-3), [0.1, 0.2])
+    # mixed: N_r = 4, counts 3, 1, 1, 3 of 8: p* = 0.25 -> over, under, under, over
+    b = O.bias_update(np.zeros(4), np.array([3, 1, 1, 3]), gamma=0.5)
+    assert np.array_equal(b, [-0.5, 0.5, 0.5, -0.5])
+
+
+def test_bias_update_balances_a_skewed_router():
+    """Repeated steps on a fixed batch: the selection key is s' + b (Eq. 9), so lowering b of the overloaded
+    experts must spread the load; the most loaded expert's share falls towards 1/N_r."""
+    rng = np.random.Generator(np.random.PCG64(5))
+    n_r, k, T = 6, 2, 600
+    s = rng.normal(size=(T, n_r)) + np.array([1.5, 1.0, 0.0, 0.0, -0.5, -1.0])     # skewed scores
+    b = np.zeros(n_r)
+    shares = []
+    for _ in range(400):
+        key = O.softmax_rows(s) + b
+        sel, _ = O.select_top_k(key, k)
+        counts = np.bincount(sel.ravel(), minlength=n_r)
+        shares.append(counts.max() / counts.sum())
+        b = O.bias_update(b, counts, gamma=2e-3)
+    assert shares[0] > 0.28 and shares[-1] < 0.19 and shares[-1] < shares[0]
