@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference reading for HBM byte counters)")
     ap.add_argument("--layer-copies", type=int, default=8, help="device copies of the layer cycled at decode")
+    ap.add_argument("--sweep", action="store_true",
+                    help="the paper's expert configurations SxAyEz at 75 %% active and the sparsity ladder with 16 "
+                         "experts, on the config's dense layer (speedup vs dense at two batch sizes)")
     return ap.parse_args()
 
 
@@ -114,6 +117,63 @@ def bench_hier(args, cfg, np, torch, binding, synth):
     print(json.dumps(out))
 
 
+# SxAyEz shapes of the paper's configuration study (all 75 % of the neurons active) and its sparsity ladder
+# with 16 experts (fraction of inactive neurons 0.75 ... 0.125; the split into shared and routed experts
+# is not given there: a quarter of the active experts, at least one, are shared here)
+SWEEP_SHAPES = [("S1A5E8", 8, 1, 5), ("S3A3E8", 8, 3, 3), ("S2A4E8", 8, 2, 4), ("S4A8E16", 16, 4, 8),
+                ("S6A6E16", 16, 6, 6), ("S3A9E16", 16, 3, 9),
+                ("S1A3E16", 16, 1, 3), ("S2A4E16", 16, 2, 4), ("S2A6E16", 16, 2, 6), ("S3A7E16", 16, 3, 7),
+                ("S4A10E16", 16, 4, 10)]
+
+
+def bench_sweep(args, base, np, torch, binding, synth):
+    """Speedup of the restructured layer over the dense one as a function of the expert configuration
+    (Sec. 5, expert-configuration and sparsity studies), arbitrary partitions of the config's dense layer."""
+    dev = torch.device("cuda:0")
+    t_setup = time.time()
+    weights = synth.make_weights(base)
+    src = synth.make_token_source(base)
+    batches = [args.batch] if args.batch else [2048, 8192]
+    xs = {T: torch.from_numpy(src.eval_batch(0, n=T)).to(dev, torch.bfloat16) for T in batches}
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    rows = []
+    dense_ms = {}
+    for name, n, n_s, n_k in SWEEP_SHAPES:
+        cfg = synth.scaled(base, n_experts=n, n_shared=n_s, top_k=n_k)
+        part = synth.trivial_partition(cfg)
+        layer = binding.Layer.from_partition(cfg, *weights, part["neuron_order"], part["rep_neuron"])
+        for T in batches:
+            y = torch.empty_like(xs[T])
+            if T not in dense_ms:
+                dense_ms[T] = timed(lambda: layer.dense_forward_device(xs[T], y), args.steps, args.warmup)
+            ms = timed(lambda: layer.forward_device(xs[T], y), args.steps, args.warmup)
+            rows.append({"shape": name, "T": T, "active_fraction": (n_s + n_k) / n, "ms_per_step": ms,
+                         "tokens_per_s": T / (ms * 1e-3), "dense_ms_per_step": dense_ms[T],
+                         "speedup_vs_dense": dense_ms[T] / ms})
+        layer.close()
+    head = rows[0]
+    out = {
+        "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": base.dtype, "data": "synthetic",
+        "config": {"workload": "sweep of expert configurations on cfg%d %s (d=%d d_ff=%d); headline fields are %s at T=%d"
+                   % (base.cfg, base.name, base.d_model, base.d_ff, head["shape"], head["T"]), "partition": "arbitrary"},
+        "sweep": rows, "setup_s": time.time() - t_setup,
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -130,6 +190,9 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if cfg.n_outer:
         bench_hier(args, cfg, np, torch, binding, synth)
+        return
+    if args.sweep:
+        bench_sweep(args, cfg, np, torch, binding, synth)
         return
     T = args.batch if args.batch else max(cfg.eval_batches)
     dev = torch.device("cuda:0")

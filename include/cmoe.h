@@ -57,7 +57,7 @@ typedef struct {
   int32_t d_ff;          /* d_h; must be a multiple of n_experts (m = d_h / N, Sec. 4.1)    */
   int32_t n_experts;     /* N                                                               */
   int32_t n_shared;      /* N_s, 0 <= N_s < N                                               */
-  int32_t top_k;         /* N_k, 1 <= N_k <= N_r; N_r <= 64                                 */
+  int32_t top_k;         /* N_k, 1 <= N_k <= min(N_r, 16); N_r <= 64                        */
   int32_t k_act;         /* K_a (the paper uses 10); only used by cmoe_build                */
   int32_t kmeans_iters;  /* assignment + centroid-update rounds, >= 1; only cmoe_build      */
   int32_t dtype;         /* CMOE_F32 or CMOE_BF16                                           */

@@ -634,7 +634,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
                      const float* logit_offset, cmoe_hier** out) {
   if (!experts || !w_router || !out) return fail(CMOE_EINVAL, "null argument");
   if (n_outer < 1 || n_outer > IL) return fail(CMOE_EINVAL, "need 1 <= n_outer <= %d", IL);
-  if (outer_top_k < 1 || outer_top_k > n_outer || outer_top_k > MAX_TOPK) return fail(CMOE_EINVAL, "bad outer_top_k");
+  if (outer_top_k < 1 || outer_top_k > n_outer || outer_top_k > MAX_OUTER_TOPK) return fail(CMOE_EINVAL, "bad outer_top_k");
   for (int e = 0; e < n_outer; ++e) {
     if (!experts[e]) return fail(CMOE_EINVAL, "expert %d is null", e);
     if (experts[e]->uploaded || experts[e]->in_hier) return fail(CMOE_ESTATE, "expert %d is already uploaded or owned", e);

@@ -15,7 +15,8 @@ constexpr int IL = 32;
 // Expert widths are padded with zero neurons to a multiple of WPAD (zero gate/up rows give h = 0,
 // zero down columns multiply it: the padded neurons contribute exactly nothing).
 constexpr int WPAD = 32;
-constexpr int MAX_TOPK = 8;        // N_k, and outer_top_k
+constexpr int MAX_TOPK = 16;       // N_k of a flat layer or of the sub-experts
+constexpr int MAX_OUTER_TOPK = 8;  // outer_top_k of the hierarchy
 constexpr int MAX_DYN = 24;        // routed slots per token (hierarchy: outer_top_k * (1 + N_k))
 constexpr int MAX_SCORED = 64;     // routed experts scored by one router (one lane per expert)
 constexpr int MAX_GROUPS = 128;    // expert groups of one engine

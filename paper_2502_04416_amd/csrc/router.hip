@@ -81,8 +81,8 @@ __device__ __forceinline__ void route_token(const RouterDev& r, const RouteIO& i
   float logit = -INFINITY;
   bool active = lane < r.n_lin;
   if (active) logit = pre[r.n_sw_rows + lane] + (io.lin_off ? io.lin_off[lane] : 0.0f);
-  int oe[MAX_TOPK];
-  float ol[MAX_TOPK];
+  int oe[MAX_OUTER_TOPK];
+  float ol[MAX_OUTER_TOPK];
   for (int i = 0; i < r.outer_top_k; ++i) {
     const int w = wave_argmax(logit, active);
     oe[i] = w;
@@ -201,8 +201,8 @@ __device__ __forceinline__ void route_select_team(const RouterDev& r, const Rout
                        io.topk_out ? io.topk_out + t * r.top_k : nullptr, hist, q);
     return;
   }
-  int oe[MAX_TOPK];
-  float ol[MAX_TOPK];
+  int oe[MAX_OUTER_TOPK];
+  float ol[MAX_OUTER_TOPK];
   uint32_t taken = 0u;
   for (int i = 0; i < r.outer_top_k; ++i) {
     float best = -INFINITY;

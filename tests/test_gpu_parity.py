@@ -187,17 +187,17 @@ def test_small_bf16_decode_sizes(binding, T):
 @pytest.mark.parametrize("dtype,T", [("bf16", 300), ("bf16", 9), ("fp32", 70)])
 def test_maximum_expert_counts(binding, dtype, T):
     """The limits of the interface: 64 routed experts (one lane per expert in the wave-level top-k) and
-    top-8 selection, with a shared expert, on a prefill-sized and a decode-sized batch."""
-    cfg = synth.scaled(synth.CONFIGS[1], d_model=256, d_ff=65 * 32, n_experts=65, n_shared=1, top_k=8, dtype=dtype,
+    top-16 selection, with a shared expert, on a prefill-sized and a decode-sized batch."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=256, d_ff=65 * 32, n_experts=65, n_shared=1, top_k=16, dtype=dtype,
                        n_centres=16)
     weights = synth.make_weights(cfg)
     part = synth.trivial_partition(cfg)
     x = synth.make_token_source(cfg).eval_batch(0, n=T)
     layer = _layer(binding, cfg, weights, part)
-    _say("N_r=64 top-8 %s T=%d" % (dtype, T), check_flat(cfg, weights, part, x, layer.forward(x)))
+    _say("N_r=64 top-16 %s T=%d" % (dtype, T), check_flat(cfg, weights, part, x, layer.forward(x)))
     u, b = synth.make_gate_params(cfg)
     layer.set_gate_params(u, b)
-    _say("N_r=64 top-8 gate %s T=%d" % (dtype, T), check_flat(cfg, weights, part, x, layer.forward(x), u=u, b=b))
+    _say("N_r=64 top-16 gate %s T=%d" % (dtype, T), check_flat(cfg, weights, part, x, layer.forward(x), u=u, b=b))
     layer.close()
 
 
@@ -207,7 +207,7 @@ def test_limits_are_rejected(binding):
         binding.cmoe_build_from_partition(binding.make_config(cfg), *synth.make_weights(cfg),
                                           synth.trivial_partition(cfg)["neuron_order"],
                                           synth.trivial_partition(cfg)["rep_neuron"])
-    cfg = synth.scaled(synth.CONFIGS[0], d_model=64, d_ff=20 * 8, n_experts=20, n_shared=1, top_k=9)
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=64, d_ff=20 * 8, n_experts=20, n_shared=1, top_k=17)
     with pytest.raises(binding.CmoeError, match="top_k"):
         binding.cmoe_build_from_partition(binding.make_config(cfg), *synth.make_weights(cfg),
                                           synth.trivial_partition(cfg)["neuron_order"],
@@ -254,9 +254,10 @@ def test_bias_update_loop_balances_the_load(binding):
 
 # ---------------------------------------------------------------------------------- full-size configs
 
-def _full(binding, ci, batches, n_sample=48, sizes=None):
-    """Full-size layer `ci` on its evaluation batches, or (sizes) on the first `n` tokens of batch 0."""
-    cfg = synth.CONFIGS[ci]
+def _full(binding, ci, batches, n_sample=48, sizes=None, **scale):
+    """Full-size layer `ci` on its evaluation batches, or (sizes) on the first `n` tokens of batch 0;
+    `scale` replaces fields of the configuration (e.g. another expert split of the same dense layer)."""
+    cfg = synth.CONFIGS[ci] if not scale else synth.scaled(synth.CONFIGS[ci], **scale)
     weights = synth.make_weights(cfg)
     part = synth.trivial_partition(cfg)
     src = synth.make_token_source(cfg)
@@ -280,6 +281,12 @@ def test_cfg1_mid_batches(binding):
     """Batch sizes between the decode path and the large-tile regime: the contraction kernels run their
     128x128 and 256x128 tile shapes at the layer's real depth."""
     _full(binding, 1, None, n_sample=32, sizes=[33, 300, 1000, 3072])
+
+
+@pytest.mark.parametrize("n,n_s,n_k", [(8, 1, 5), (16, 3, 9), (16, 6, 6)])
+def test_paper_expert_configurations(binding, n, n_s, n_k):
+    """SxAyEz splits of the paper's configuration study (75 % of the neurons active) on the full-size layer."""
+    _full(binding, 1, None, n_sample=24, sizes=[700], n_experts=n, n_shared=n_s, top_k=n_k)
 
 
 def test_cfg2_full(binding):
