@@ -34,8 +34,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--batch", type=int, default=None, help="token count (default: the config's largest eval batch)")
-    ap.add_argument("--construct", choices=["library", "arbitrary"], default="library",
-                    help="partition from cmoe_build on the calibration set, or a seeded arbitrary one")
+    ap.add_argument("--construct", choices=["library", "gpu", "arbitrary"], default="library",
+                    help="partition from cmoe_build on the calibration set (host), from cmoe_build_gpu (activation "
+                         "profiling on the device), or a seeded arbitrary one")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-batch measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-dense", action="store_true",
@@ -200,10 +201,10 @@ def main():
     weights = synth.make_weights(cfg)
     src = synth.make_token_source(cfg)
     construct_s = None
-    if args.construct == "library":
+    if args.construct in ("library", "gpu"):
         t0 = time.time()
         try:
-            layer = binding.Layer.build(cfg, *weights, src.calibration())
+            layer = binding.Layer.build(cfg, *weights, src.calibration(), on_gpu=(args.construct == "gpu"))
             construct_s = time.time() - t0
         except binding.CmoeError as e:
             print("bench.py: cmoe_build unavailable (%s); using an arbitrary partition" % e, file=sys.stderr)
@@ -298,7 +299,7 @@ def main():
                     "unit": "GB/s", "traffic": None}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["avg_launch_ms"] = gu_ms
-    if prefill and cfg.cfg == 1 and T == 2048 and args.construct == "library":
+    if prefill and cfg.cfg == 1 and T == 2048 and args.construct in ("library", "gpu"):
         # HBM bytes of one launch of this kernel on this workload from the two rocprofv3 --pmc runs
         # (FETCH_SIZE x 2.000 scale, WRITE_SIZE x 1.000; profiles/cfg1_T2048_hbm_traffic.md)
         roofline["traffic"] = MEASURED_GATE_UP_TRAFFIC_BYTES

@@ -77,6 +77,22 @@ typedef struct {
 int cmoe_build(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
                const float* calib_x, int64_t q, cmoe_layer** out);
 
+/* cmoe_build with App. A.2 steps 1-2 (hidden states of the calibration tokens and their per-token
+ * top-K_a) computed on the current HIP device instead of the host: bf16 MFMA with fp32 accumulation,
+ * same tie rule (lowest index).  Everything else, and every argument, as cmoe_build.  Needs a bf16 layer
+ * with d_model a multiple of 64; allocates and frees its own device memory (about
+ * 4*d_model*d_ff + 4*q*d_ff bytes) and synchronises.  A token whose K_a-th and (K_a+1)-th largest |h|
+ * differ by less than fp32 accumulation error may get a different index set than on the host. */
+int cmoe_build_gpu(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
+                   const float* calib_x, int64_t q, cmoe_layer** out);
+
+/* App. A.2 steps 1-2 on their own: active_out [q, k_act] (host int32) receives, for every calibration
+ * token, the k_act neurons of largest |h| in descending order of magnitude (ties to the lowest index);
+ * on_gpu = 0 computes on the host (fp64 accumulation), 1 on the current HIP device as in cmoe_build_gpu.
+ * Uses d_model, d_ff, k_act and dtype of the configuration. */
+int cmoe_profile_activations(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* calib_x,
+                             int64_t q, int on_gpu, int32_t* active_out);
+
 /* The balanced assignment step of App. A.3 on its own: given dist [n, n_r] (host, row-major,
  * n = n_r * m) find label[i] in [0, n_r) minimising sum_i dist[i, label[i]] with exactly m rows per
  * cluster.  Exact (successive shortest paths on the transportation problem; same optimum as the

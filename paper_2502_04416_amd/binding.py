@@ -39,6 +39,7 @@ EXPORTS = [
     "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
     "cmoe_balanced_assignment", "cmoe_probe_mfma", "cmoe_get_gate_params", "cmoe_update_bias",
+    "cmoe_build_gpu", "cmoe_profile_activations",
 ]
 
 
@@ -57,6 +58,8 @@ def load():
     vp, i32p, f32p, i64, sz = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int64, C.c_size_t
     cfgp = C.POINTER(cmoe_config)
     lib.cmoe_build.argtypes = [cfgp, f32p, f32p, f32p, f32p, i64, C.POINTER(vp)]
+    lib.cmoe_build_gpu.argtypes = [cfgp, f32p, f32p, f32p, f32p, i64, C.POINTER(vp)]
+    lib.cmoe_profile_activations.argtypes = [cfgp, f32p, f32p, f32p, i64, C.c_int, i32p]
     lib.cmoe_build_from_partition.argtypes = [cfgp, f32p, f32p, f32p, i32p, i32p, C.POINTER(vp)]
     lib.cmoe_balanced_assignment.argtypes = [C.POINTER(C.c_double), C.c_int32, C.c_int32, C.c_int32, i32p,
                                              C.POINTER(C.c_double)]
@@ -126,6 +129,23 @@ def cmoe_build(cfg: cmoe_config, w_gate, w_up, w_down, calib_x) -> int:
     h = C.c_void_p()
     _check(load().cmoe_build(C.byref(cfg), _fp(wg), _fp(wu), _fp(wd), _fp(cx), cx.shape[0], C.byref(h)), "cmoe_build")
     return h.value
+
+
+def cmoe_build_gpu(cfg: cmoe_config, w_gate, w_up, w_down, calib_x) -> int:
+    wg, wu, wd, cx = _f32(w_gate), _f32(w_up), _f32(w_down), _f32(calib_x)
+    h = C.c_void_p()
+    _check(load().cmoe_build_gpu(C.byref(cfg), _fp(wg), _fp(wu), _fp(wd), _fp(cx), cx.shape[0], C.byref(h)),
+           "cmoe_build_gpu")
+    return h.value
+
+
+def cmoe_profile_activations(cfg: cmoe_config, w_gate, w_up, calib_x, on_gpu: bool) -> np.ndarray:
+    """active [q, k_act]: per calibration token the k_act neurons of largest |h| (App. A.2 steps 1-2)."""
+    wg, wu, cx = _f32(w_gate), _f32(w_up), _f32(calib_x)
+    out = np.empty((cx.shape[0], cfg.k_act), dtype=np.int32)
+    _check(load().cmoe_profile_activations(C.byref(cfg), _fp(wg), _fp(wu), _fp(cx), cx.shape[0], int(on_gpu), _ip(out)),
+           "cmoe_profile_activations")
+    return out
 
 
 def cmoe_build_from_partition(cfg: cmoe_config, w_gate, w_up, w_down, neuron_order, rep_neuron) -> int:
@@ -319,8 +339,9 @@ class Layer(_DeviceMixin):
         return self
 
     @classmethod
-    def build(cls, cfg, w_gate, w_up, w_down, calib_x, kmeans_iters=1, dist_mode=0, upload=True):
-        h = cmoe_build(make_config(cfg, kmeans_iters, dist_mode), w_gate, w_up, w_down, calib_x)
+    def build(cls, cfg, w_gate, w_up, w_down, calib_x, kmeans_iters=1, dist_mode=0, upload=True, on_gpu=False):
+        make = cmoe_build_gpu if on_gpu else cmoe_build
+        h = make(make_config(cfg, kmeans_iters, dist_mode), w_gate, w_up, w_down, calib_x)
         self = cls(h, cfg)
         if upload:
             self.upload()

@@ -313,7 +313,7 @@ static void fill_flat_engines(cmoe_layer* L) {
 
 static int build_common(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
                         const float* calib_x, int64_t q, const int32_t* order_in, const int32_t* rep_in,
-                        cmoe_layer** out) {
+                        cmoe_layer** out, bool profile_on_gpu = false) {
   int rc = check_config(cfg);
   if (rc) return rc;
   if (!w_gate || !w_up || !w_down || !out) return fail(CMOE_EINVAL, "null weight or output pointer");
@@ -348,9 +348,18 @@ static int build_common(const cmoe_config* cfg, const float* w_gate, const float
       std::string msg;
       L->neuron_order.resize(d_ff);
       L->rep_neuron.resize(n_r);
-      if (!host_construct(*cfg, rd, calib_x, q, L->neuron_order.data(), L->rep_neuron.data(), L->mu.data(),
-                          &L->cost, &msg))
+      if (profile_on_gpu) {
+        std::vector<int32_t> active((size_t)q * cfg->k_act);
+        const int herr = gpu_profile(*cfg, rd, calib_x, q, active.data(), &msg);
+        if (herr != 0)
+          return fail(herr == (int)hipErrorInvalidValue ? CMOE_EINVAL : CMOE_EHIP, "GPU profiling failed: %s", msg.c_str());
+        if (!host_construct_from_active(*cfg, q, active.data(), L->neuron_order.data(), L->rep_neuron.data(),
+                                        L->mu.data(), &L->cost, &msg))
+          return fail(CMOE_EINVAL, "construction failed: %s", msg.c_str());
+      } else if (!host_construct(*cfg, rd, calib_x, q, L->neuron_order.data(), L->rep_neuron.data(), L->mu.data(),
+                                 &L->cost, &msg)) {
         return fail(CMOE_EINVAL, "construction failed: %s", msg.c_str());
+      }
     }
     // expert groups: one shared group of N_s*m neurons (if any), then the routed experts
     L->moe.dtype = cfg->dtype;
@@ -390,6 +399,36 @@ int cmoe_build(const cmoe_config* cfg, const float* w_gate, const float* w_up, c
                const float* calib_x, int64_t q, cmoe_layer** out) {
   if (!calib_x) return fail(CMOE_EINVAL, "calib_x is null");
   return build_common(cfg, w_gate, w_up, w_down, calib_x, q, nullptr, nullptr, out);
+}
+
+int cmoe_build_gpu(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* w_down,
+                   const float* calib_x, int64_t q, cmoe_layer** out) {
+  if (!calib_x) return fail(CMOE_EINVAL, "calib_x is null");
+  return build_common(cfg, w_gate, w_up, w_down, calib_x, q, nullptr, nullptr, out, true);
+}
+
+int cmoe_profile_activations(const cmoe_config* cfg, const float* w_gate, const float* w_up, const float* calib_x,
+                             int64_t q, int on_gpu, int32_t* active_out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!w_gate || !w_up || !calib_x || !active_out) return fail(CMOE_EINVAL, "null argument");
+  if (q < 1) return fail(CMOE_EINVAL, "calibration set is empty");
+  if (cfg->k_act < 1 || cfg->k_act > cfg->d_ff) return fail(CMOE_EINVAL, "need 1 <= k_act <= d_ff");
+  try {
+    RoundedDense rd;
+    rd.from_fp32(cfg->dtype, cfg->d_model, cfg->d_ff, w_gate, w_up, w_up);   // the down matrix plays no part here
+    if (on_gpu) {
+      std::string msg;
+      const int herr = gpu_profile(*cfg, rd, calib_x, q, active_out, &msg);
+      if (herr != 0)
+        return fail(herr == (int)hipErrorInvalidValue ? CMOE_EINVAL : CMOE_EHIP, "GPU profiling failed: %s", msg.c_str());
+    } else {
+      host_profile(*cfg, rd, calib_x, q, active_out);
+    }
+  } catch (const std::bad_alloc&) {
+    return fail(CMOE_ENOMEM, "out of host memory");
+  }
+  return CMOE_OK;
 }
 
 int cmoe_balanced_assignment(const double* dist, int32_t n, int32_t n_r, int32_t m, int32_t* label_out,

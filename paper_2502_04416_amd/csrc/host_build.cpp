@@ -179,11 +179,8 @@ bool solve_balanced_assignment(const double* dist, int n, int n_r, int m, int32_
   return true;
 }
 
-bool host_construct(const cmoe_config& cfg, const RoundedDense& rd, const float* calib_x, int64_t q,
-                    int32_t* neuron_order, int32_t* rep_neuron, float* mu_out, double* cost_out, std::string* msg) {
-  const int d = cfg.d_model, d_ff = cfg.d_ff, N = cfg.n_experts, m = d_ff / N;
-  const int n_s = cfg.n_shared, n_r = N - n_s, k_act = cfg.k_act;
-  const int n = n_r * m;
+void host_profile(const cmoe_config& cfg, const RoundedDense& rd, const float* calib_x, int64_t q, int32_t* active) {
+  const int d = cfg.d_model, d_ff = cfg.d_ff, k_act = cfg.k_act;
 
   // calibration tokens rounded to the layer dtype, weights as floats (exact for bf16)
   std::vector<float> xs((size_t)q * d);
@@ -199,7 +196,6 @@ bool host_construct(const cmoe_config& cfg, const RoundedDense& rd, const float*
   });
 
   // (A) profiling: per token, the K_a neurons of largest |h| (App. A.2 steps 1-2); A kept as per-token lists
-  std::vector<int32_t> active((size_t)q * k_act);
   parallel_for(q, [&](int64_t t) {
     const float* x = &xs[(size_t)t * d];
     std::vector<double> keep_v(k_act, -1.0);
@@ -224,6 +220,20 @@ bool host_construct(const cmoe_config& cfg, const RoundedDense& rd, const float*
     }
     for (int k = 0; k < k_act; ++k) active[(size_t)t * k_act + k] = keep_i[k];
   });
+}
+
+bool host_construct(const cmoe_config& cfg, const RoundedDense& rd, const float* calib_x, int64_t q,
+                    int32_t* neuron_order, int32_t* rep_neuron, float* mu_out, double* cost_out, std::string* msg) {
+  std::vector<int32_t> active((size_t)q * cfg.k_act);
+  host_profile(cfg, rd, calib_x, q, active.data());
+  return host_construct_from_active(cfg, q, active.data(), neuron_order, rep_neuron, mu_out, cost_out, msg);
+}
+
+bool host_construct_from_active(const cmoe_config& cfg, int64_t q, const int32_t* active, int32_t* neuron_order,
+                                int32_t* rep_neuron, float* mu_out, double* cost_out, std::string* msg) {
+  const int d_ff = cfg.d_ff, N = cfg.n_experts, m = d_ff / N;
+  const int n_s = cfg.n_shared, n_r = N - n_s, k_act = cfg.k_act;
+  const int n = n_r * m;
   // feature vectors c_i as sorted token lists; rates mu_i (App. A.2 step 3)
   std::vector<std::vector<int32_t>> feat(d_ff);
   for (int64_t t = 0; t < q; ++t)

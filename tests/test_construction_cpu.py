@@ -149,3 +149,17 @@ def test_build_argument_errors():
         binding.cmoe_build(c, *w, x)
     with pytest.raises(binding.CmoeError, match="empty"):
         binding.cmoe_build(binding.make_config(cfg), *w, np.zeros((0, 16), dtype=np.float32))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_profile_activations_on_the_host_matches_the_oracle(dtype):
+    """App. A.2 steps 1-2 on their own: the per-token index sets are the rows of the oracle's ATopK matrix."""
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=64, d_ff=384, n_experts=8, n_shared=1, top_k=2, dtype=dtype,
+                       n_calib=96, k_act=7)
+    wg, wu, _ = synth.make_weights(cfg)
+    x = synth.make_token_source(cfg).calibration()
+    active = binding.cmoe_profile_activations(binding.make_config(cfg), wg, wu, x, on_gpu=False)
+    a = O.atopk_matrix(O.hidden_states(x, wg, wu), cfg.k_act)
+    assert active.shape == (x.shape[0], cfg.k_act)
+    for t in range(x.shape[0]):
+        assert set(active[t].tolist()) == set(np.nonzero(a[t])[0].tolist())
