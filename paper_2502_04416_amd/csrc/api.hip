@@ -111,6 +111,8 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
   L.scores = take(sizeof(float) * 8 * Tn * std::max(e.r.n_sw_rows + e.r.n_lin_rows, 1));   // router K-slice partials
   L.h = take(es * (size_t)Tn * (size_t)e.h_per_token);
   L.y_slots = take(S_all == 1 ? 0 : es * (size_t)L.n_slots * e.d);
+  // reserved in full whenever a smaller batch could split K, so that the size grows with T
+  L.splitk = take((!use_simt_experts(e.dtype) && Tn > 32) ? bf16_splitk_bytes(e, Tn) : 0);
   L.total = off;
   return L;
 }

@@ -64,6 +64,7 @@ struct WsLayout {
   size_t scores;                     // [8][T][router rows] float: K-slice partial pre-activations of the router
   size_t h;                          // hidden activations, ragged: rows of group g are width_pad(g) wide
   size_t y_slots;                    // [n_slots][d]; unused when S_all == 1 (written straight to y)
+  size_t splitk;                     // fp32 partial sums of a K-split contraction (small batches only)
   size_t total;
   int64_t n_slots;
   int n_tok_tiles;
@@ -117,6 +118,9 @@ hipError_t launch_combine(const Engine& e, int64_t T, char* ws, const WsLayout& 
 int gemm_tile(const Engine& e, int64_t T, int which);
 bool use_simt_experts(int dtype);
 int bf16_gemm_tile(int which, const Engine& e, int64_t T);
+// K split of the bf16 contractions at small batches (1 = none) and the bytes of fp32 partial sums it needs.
+int bf16_splitk(const Engine& e, int64_t T, int which);
+size_t bf16_splitk_bytes(const Engine& e, int64_t T);
 int simt_gemm_tile(int which);
 hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                hipStream_t s, int stage);

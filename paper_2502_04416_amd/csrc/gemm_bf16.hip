@@ -30,8 +30,16 @@ struct GemmArgs {
   int ldb;                   // row stride of B in MODE 1 (packed gate/up rows)
   int64_t T;
   int single;                // 1: one always-on group holding all T tokens; no device schedule is read
-  int n_blocks;              // grid size (multiple of 8)
+  int n_blocks;              // grid size (multiple of 8) before the K split
   int xcd_remap;             // 1: consecutive work items run on the same XCD
+  // K split: k_split > 1 workgroups share one tile, each multiplies a contiguous range of K tiles and
+  // stores its fp32 partial sums to P [k_split][p_rows][ldp] (row = slot, column = column of the tile
+  // grid); a finishing kernel adds the parts in order and applies the epilogue.  Used when a launch has
+  // too few tiles to fill the chip (batches of a few hundred tokens).
+  int k_split;
+  float* P;
+  int64_t p_rows;
+  int ldp;
 };
 
 // ---- global->LDS loads and a ring of K tiles ------------------------------------------------------
@@ -103,6 +111,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
   // tiles sharing an operand meet in one L2: equal parts of a single-group problem, and for work lists the
   // shares of equal estimated cost that the permutation kernel left behind the prefix array.
   int wid = blockIdx.x;
+  int k_part = 0;
+  if (p.k_split > 1) {
+    k_part = wid % p.k_split;
+    wid /= p.k_split;
+  }
   if (p.xcd_remap) {
     if (p.single) {
       const int chunk = (n_work + 7) >> 3;
@@ -124,7 +137,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     wp = p.groups[g].width_pad;
     hoff = p.h_off[g];
   }
-  const int K = (MODE == 1) ? p.d : wp;
+  // this workgroup's range of K tiles (all of them without a K split); from here on K and the tile
+  // index count from the start of that range and the source pointers are shifted accordingly
+  const int K_full = (MODE == 1) ? p.d : wp;
+  int K = K_full, k_first = 0;
+  if (p.k_split > 1) {
+    const int kt_all = (K_full + BKT - 1) / BKT;
+    const int per = (kt_all + p.k_split - 1) / p.k_split;
+    k_first = (k_part * per < kt_all ? k_part * per : kt_all) * BKT;
+    const int k_end = ((k_part + 1) * per < kt_all) ? (k_part + 1) * per * BKT : K_full;
+    K = k_end > k_first ? k_end - k_first : 0;
+  }
   const int n_cols = (MODE == 1) ? 2 * wp : p.d;
   const int n_nt = (n_cols + BN - 1) / BN;
   const int n_mt = (cnt + BM - 1) / BM;
@@ -148,9 +171,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     if (r >= cnt) r = cnt - 1;
     if (MODE == 1) {
       const int64_t tok = p.slot2tok ? p.slot2tok[seg0 + r] : (seg0 + r);
-      a_src[i] = p.A + tok * p.d + a_coff[i];
+      a_src[i] = p.A + tok * p.d + a_coff[i] + k_first;
     } else {
-      a_src[i] = p.A + hoff + (int64_t)r * wp + a_coff[i];
+      a_src[i] = p.A + hoff + (int64_t)r * wp + a_coff[i] + k_first;
     }
   }
 #pragma unroll
@@ -159,8 +182,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     b_coff[i] = (((lane % CPR) ^ ((row >> SWZ_SHIFT) & (CPR - 1))) << 3);
     int n = nt * BN + row;
     if (n >= n_cols) n = n_cols - 1;
-    if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + b_coff[i];
-    else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + b_coff[i];
+    if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + b_coff[i] + k_first;
+    else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + b_coff[i] + k_first;
   }
   const int KT = (K + BKT - 1) / BKT;
   const bool k_ragged = (K % BKT) != 0;
@@ -198,10 +221,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.0f;
 
-  // prologue
+  // prologue (a K part can be empty when the split does not divide the K tiles)
   if (HR) {
-    issue_tile_a(0);
-    issue_tile_b(0);
+    if (KT > 0) {
+      issue_tile_a(0);
+      issue_tile_b(0);
+    }
     if (KT > 1) issue_tile_a(1);
   } else {
 #pragma unroll
@@ -299,6 +324,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     for (; kt < KT; ++kt) k_tile(kt, integral_constant<int, 0>{}, false_type{});
   }
 
+  // ---- K split: the raw fp32 partial sums go to this part's slab; 32 consecutive lanes hold 32
+  // consecutive columns of a row, so the stores are 128-byte segments ----
+  if (p.k_split > 1) {
+    float* slab = p.P + (int64_t)k_part * p.p_rows * p.ldp;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int r = mt * BM + wm * TM + mi * 32 + (i / 4) * 8 + lh * 4 + (i % 4);
+        if (r >= cnt) continue;
+        float* prow = slab + (int64_t)(seg0 + r) * p.ldp;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+          const int col = nt * BN + wn * TN + ni * 32 + l32;
+          if (col < n_cols) prow[col] = acc[mi][ni][i];
+        }
+      }
+    return;
+  }
   // ---- epilogue: through LDS, so that global stores are 16-byte vectors along the rows ----
   // Each wave stages 32 rows of its tile at a time in a private LDS strip (row stride padded by 16 bytes
   // against bank conflicts), then every lane copies 16-byte pieces of rows out to global memory.
@@ -427,6 +471,99 @@ int bf16_gemm_tile(int which, const Engine& e, int64_t T) {
   }
 }
 
+// Estimated number of tiles of contraction `which` (1 gate/up, 2 down) with bm x bn tiles: exact for the
+// always-on groups, and for the routed groups the full row tiles plus half a tile per touched group.
+static int64_t est_tiles(const Engine& e, int64_t T, int which, int bm, int bn) {
+  auto cols = [&](int g) { return which == 1 ? cdiv(2 * e.width_pad_host[g], bn) : cdiv(e.d, bn); };
+  int64_t tiles = 0;
+  for (int g = 0; g < e.n_always; ++g) tiles += ((T + bm - 1) / bm) * cols(g);
+  if (e.G > e.n_always && e.S_dyn > 0) {
+    const int64_t entries = T * e.S_dyn;
+    const int64_t touched = std::min<int64_t>(e.G - e.n_always, entries);
+    const int64_t rows = std::max<int64_t>((entries + bm - 1) / bm + touched / 2, touched);
+    tiles += rows * cols(e.n_always);
+  }
+  return tiles;
+}
+
+// K split of contraction `which`: with too few tiles to give every CU one (batches of a few hundred
+// tokens) several workgroups share a tile.  Powers of two up to 8, at least four K tiles per part, at
+// most 64 MB of partial sums.
+constexpr size_t SPLITK_MAX_BYTES = 64u << 20;
+static int64_t splitk_rows(const Engine& e, int64_t T) { return T * e.S_all(); }
+static int splitk_ldp(const Engine& e, int which) { return which == 1 ? 2 * e.max_width_pad : e.d; }
+
+int bf16_splitk(const Engine& e, int64_t T, int which) {
+  if (T < 1 || T > 1024 || env_int("CMOE_SPLITK", 1) == 0) return 1;
+  const TileCfg& c = kCfgs[cfg_index(which, e, T)];
+  const int64_t tiles = est_tiles(e, T, which, c.bm, c.bn);
+  int k_min = e.d;
+  if (which == 2) {
+    k_min = 1 << 30;
+    for (int g = 0; g < e.G; ++g) k_min = std::min(k_min, e.width_pad_host[g]);
+  }
+  const int kt = cdiv(k_min, c.bk);
+  const size_t per_part = (size_t)splitk_rows(e, T) * splitk_ldp(e, which) * sizeof(float);
+  int ks = 1;
+  // Split only while the launch stays well inside one round of workgroups (two 128x128 tiles fit a CU, one of
+  // the larger shapes): measured at 64..512 tokens, splitting a launch that already has a tile for most
+  // CUs costs more (partial sums, a second launch) than the shorter K loop saves.
+  const int64_t slots = (c.bm == 128 && c.bn == 128) ? 2 : 1;
+  while (ks < 8 && tiles * ks * 2 <= 192 * slots && kt / (ks * 2) >= 4 && per_part * ks * 2 <= SPLITK_MAX_BYTES) ks *= 2;
+  return ks;
+}
+
+// Bytes to reserve for the partial sums in a workspace for up to T tokens: the cap, because a smaller
+// batch may split further than the largest one does.
+size_t bf16_splitk_bytes(const Engine& e, int64_t T) {
+  (void)e;
+  return T > 32 ? SPLITK_MAX_BYTES : 0;
+}
+
+// Finish of a K-split gate/up contraction: one workgroup per slot row adds the parts in order and applies
+// Swish(g) * u (Eq. 3, first line) with the same arithmetic as the fused epilogue.
+__global__ __launch_bounds__(256) void splitk_finish_gate_up(const float* __restrict__ P, int k_split, int64_t p_rows,
+                                                             int ldp, const GroupDev* __restrict__ groups,
+                                                             const int32_t* __restrict__ seg_off,
+                                                             const int64_t* __restrict__ h_off, int G, int single,
+                                                             bf16_t* __restrict__ H) {
+  const int64_t row = blockIdx.x;
+  int g = 0, seg0 = 0;
+  int64_t hoff = 0;
+  if (!single) {
+    g = find_group(seg_off, G, (int)row);       // the group whose slot segment holds this row
+    seg0 = seg_off[g];
+    hoff = h_off[g];
+  }
+  const int wp = groups[g].width_pad;
+  for (int n = threadIdx.x; n < wp; n += 256) {
+    const int gc = (n / IL) * 2 * IL + (n % IL);
+    float gt = 0.0f, up = 0.0f;
+    for (int k = 0; k < k_split; ++k) {
+      const float* prow = P + ((int64_t)k * p_rows + row) * ldp;
+      gt += prow[gc];
+      up += prow[gc + IL];
+    }
+    const float sg = gt * __frcp_rn(1.0f + __expf(-gt));
+    H[hoff + (row - seg0) * wp + n] = f32_to_bf16(sg * up);
+  }
+}
+
+// Finish of a K-split down contraction: C[row][c] = sum of the parts, four columns per thread.
+__global__ __launch_bounds__(256) void splitk_finish_down(const float* __restrict__ P, int k_split, int64_t p_rows,
+                                                          int d, bf16_t* __restrict__ C) {
+  const int64_t row = blockIdx.x;
+  for (int c = threadIdx.x * 4; c < d; c += 1024) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k = 0; k < k_split; ++k) {
+      const float4 v = *reinterpret_cast<const float4*>(P + ((int64_t)k * p_rows + row) * d + c);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    bf16_t out[4] = {f32_to_bf16(acc.x), f32_to_bf16(acc.y), f32_to_bf16(acc.z), f32_to_bf16(acc.w)};
+    *reinterpret_cast<uint2*>(C + row * d + c) = *reinterpret_cast<const uint2*>(out);
+  }
+}
+
 template <typename K>
 static hipError_t launch_kernel(K kern, size_t smem, int threads, bool& attr_done, const GemmArgs& a, hipStream_t s) {
   if (!attr_done) {
@@ -435,7 +572,7 @@ static hipError_t launch_kernel(K kern, size_t smem, int threads, bool& attr_don
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.n_blocks), dim3(threads), smem, s, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)a.n_blocks * (unsigned)(a.k_split > 1 ? a.k_split : 1)), dim3(threads), smem, s, a);
   return hipGetLastError();
 }
 
@@ -479,8 +616,17 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.work = reinterpret_cast<const int32_t*>(ws + L.work1);
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
   a.n_blocks = (int)round_up64(gemm_work_bound(e, T, 1), 8);
+  a.P = reinterpret_cast<float*>(ws + L.splitk);
+  a.p_rows = splitk_rows(e, T);
+  a.k_split = bf16_splitk(e, T, 1);
+  a.ldp = splitk_ldp(e, 1);
   if (stage != 2) {
     hipError_t err = launch_cfg<1>(cfg_index(1, e, T), a, s);
+    if (err == hipSuccess && a.k_split > 1) {
+      hipLaunchKernelGGL(splitk_finish_gate_up, dim3((unsigned)a.p_rows), dim3(256), 0, s, a.P, a.k_split, a.p_rows, a.ldp,
+                         a.groups, a.seg_off, a.h_off, a.G, a.single, a.C);
+      err = hipGetLastError();
+    }
     if (err != hipSuccess || stage == 1) return err;
   }
   // down
@@ -502,7 +648,14 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
     const int64_t share = std::min<int64_t>(bound, (bound * c_max + 8 * c_min - 1) / (8 * c_min) + 2);
     a.n_blocks = (int)(remap && !a.single ? 8 * share : round_up64(bound, 8));
   }
-  return launch_cfg<2>(cfg_index(2, e, T), a, s);
+  a.k_split = bf16_splitk(e, T, 2);
+  a.ldp = splitk_ldp(e, 2);
+  hipError_t err = launch_cfg<2>(cfg_index(2, e, T), a, s);
+  if (err == hipSuccess && a.k_split > 1) {
+    hipLaunchKernelGGL(splitk_finish_down, dim3((unsigned)a.p_rows), dim3(256), 0, s, a.P, a.k_split, a.p_rows, e.d, a.C);
+    err = hipGetLastError();
+  }
+  return err;
 }
 
 }  // namespace cmoe

@@ -226,6 +226,22 @@ def test_small_bf16_gate_params(binding):
     layer.close()
 
 
+@pytest.mark.parametrize("T", [40, 130, 500])
+def test_k_split_batches(binding, T):
+    """Batches of a few hundred tokens on a layer deep enough (d = 2048) that the contractions split K
+    over several workgroups and a finishing kernel adds the parts."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=2048, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    out = layer.forward(x)
+    _say("k-split T=%d" % T, check_flat(cfg, weights, part, x, out))
+    _say("k-split T=%d dense" % T, check_dense(cfg, weights, x, layer.dense_forward(x)))
+    assert np.array_equal(out["y"], layer.forward(x)["y"])
+    layer.close()
+
+
 def test_bias_update_loop_balances_the_load(binding):
     """Sec. 4.3: forward -> per-expert counts -> cmoe_update_bias, repeated on one batch.  The library's
     biases follow the oracle's step applied to the same counts, the most loaded expert's share falls,
