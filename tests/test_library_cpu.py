@@ -121,3 +121,13 @@ def test_update_bias_matches_the_oracle_on_the_host(lib):
     with pytest.raises(binding.CmoeError):
         binding.cmoe_update_bias(h, -np.ones(cfg.n_routed, dtype=np.int32), 1e-3)
     binding.cmoe_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: the bench says so and exits instead of launching ranks."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
