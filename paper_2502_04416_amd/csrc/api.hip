@@ -108,6 +108,7 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
   L.slot2tok = take(sizeof(int32_t) * L.n_slots);
   L.tok2slot = take(sizeof(int32_t) * L.n_slots);
   L.slot_w = take(sizeof(float) * L.n_slots);
+  L.w_by_slot = take(sizeof(float) * L.n_slots);
   L.scores = take(sizeof(float) * 8 * Tn * std::max(e.r.n_sw_rows + e.r.n_lin_rows, 1));   // router K-slice partials
   L.h = take(es * (size_t)Tn * (size_t)e.h_per_token);
   L.y_slots = take(S_all == 1 ? 0 : es * (size_t)L.n_slots * e.d);

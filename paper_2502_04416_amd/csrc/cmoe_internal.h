@@ -61,6 +61,7 @@ struct WsLayout {
   size_t h_off;                      // [G+1] int64: element offset of each group's rows in H
   size_t slot2tok;                   // [n_slots] int32
   size_t tok2slot, slot_w;           // [T][S_all] int32 / float
+  size_t w_by_slot;                  // [n_slots] float: the combine weight of each slot (decode batches)
   size_t scores;                     // [8][T][router rows] float: K-slice partial pre-activations of the router
   size_t h;                          // hidden activations, ragged: rows of group g are width_pad(g) wide
   size_t y_slots;                    // [n_slots][d]; unused when S_all == 1 (written straight to y)
@@ -132,6 +133,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
                                hipStream_t s);
 // Decode batches (bf16, T <= 32): weight-streaming expert kernels, see decode.hip.
 bool decode_path_ok(const Engine& e, int64_t T);
+bool decode_fuses_combine(const Engine& e, int64_t T);   // the down kernel also does the weighted sum over slots
 hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                  hipStream_t s, int stage);
 // Upper bound of work items of grouped GEMM `which` (1: gate/up, 2: down) for T tokens.

@@ -9,6 +9,7 @@
 // This is the per-neuron form of the FFN, F(x) = sum_i h_i w_i (Eq. 1), evaluated only for the
 // neurons of the experts some token selected (Eq. 4).
 #include <algorithm>
+#include <cstdlib>
 #include "cmoe_internal.h"
 #include "device_utils.h"
 
@@ -193,11 +194,100 @@ __global__ __launch_bounds__(256) void decode_down_kernel(DecArgs p) {
   }
 }
 
+// ---- down + combine: y[t][c] = sum over the token's slots of weight * sum_n H[slot][n] * Wdown[n][c] ---------
+// One workgroup owns 16 output columns of every token, so the weighted sum over a token's experts (Eq. 4,
+// Eq. 10) needs no second pass and no per-slot outputs in memory.  Its work items are (non-empty group,
+// chunk of DC_CH K steps); wave w takes items w, w + 16, ... and adds its weighted partial products into
+// accumulators of its own in LDS, which are summed in wave order at the end: the result does not depend on
+// timing.  All loads of an item are in flight together.
+constexpr int DC_CH = 8;
+constexpr int DC_WAVES = 16;
+template <int NTT>
+__global__ __launch_bounds__(DC_WAVES * 64) void decode_down_combine_kernel(DecArgs p, const float* __restrict__ w_by_slot,
+                                                                            bf16_t* __restrict__ y_out) {
+  __shared__ float yacc[DC_WAVES][NTT * 16][17];
+  __shared__ int32_t item0[MAX_GROUPS + 1];       // prefix of work items over groups
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int c0 = blockIdx.x * 16;
+  float* mine = &yacc[wave][0][0];
+  for (int e = lane; e < NTT * 16 * 17; e += 64) mine[e] = 0.0f;
+  if (wave == 0) {
+    int run0 = 0;
+#pragma unroll
+    for (int k = 0; k < MAX_GROUPS / 64; ++k) {
+      const int g = lane + 64 * k;
+      int n = 0;
+      if (g < p.G && p.seg_off[g + 1] > p.seg_off[g]) n = cdiv(p.groups[g].width_pad / 32, DC_CH);
+      const int inc = wave_incl_scan(n, lane);
+      if (g < p.G) item0[g] = run0 + inc - n;
+      run0 += __shfl(inc, 63, 64);
+    }
+    if (lane == 0) item0[p.G] = run0;
+  }
+  __syncthreads();
+  const int n_items = item0[p.G];
+  for (int u = wave; u < n_items; u += DC_WAVES) {
+    const int g = find_group(item0, p.G, u);
+    const int ks0 = (u - item0[g]) * DC_CH;
+    const int seg0 = p.seg_off[g], cnt = p.seg_off[g + 1] - seg0;
+    const int wp = p.groups[g].width_pad;
+    const int ns = min(DC_CH, wp / 32 - ks0);
+    const bf16_t* wrow = p.w2 + p.groups[g].w2_off + (int64_t)(c0 + r16) * wp + kq * 8 + ks0 * 32;
+    const bf16_t* hbase = p.h + p.h_off[g] + kq * 8 + ks0 * 32;
+    bf16x8_t a[DC_CH], b[NTT][DC_CH];
+    int tok[NTT];
+    float wt[NTT];
+#pragma unroll
+    for (int s = 0; s < DC_CH; ++s) a[s] = s < ns ? ld_frag(wrow + s * 32) : zero_frag();
+#pragma unroll
+    for (int tt = 0; tt < NTT; ++tt) {
+      const int col = tt * 16 + r16;
+      const bool ok = col < cnt;
+      const bf16_t* hrow = hbase + (int64_t)(ok ? col : 0) * wp;
+#pragma unroll
+      for (int s = 0; s < DC_CH; ++s) b[tt][s] = (ok && s < ns) ? ld_frag(hrow + s * 32) : zero_frag();
+      tok[tt] = ok ? p.slot2tok[seg0 + col] : -1;
+      wt[tt] = ok ? w_by_slot[seg0 + col] : 0.0f;
+    }
+#pragma unroll
+    for (int tt = 0; tt < NTT; ++tt) {
+      floatx4_t acc;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = 0.0f;
+#pragma unroll
+      for (int s = 0; s < DC_CH; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], b[tt][s], acc, 0, 0, 0);
+      // accumulator element i: output column (lane/16)*4 + i, token of segment position lane%16
+      if (tok[tt] >= 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) yacc[wave][tok[tt]][kq * 4 + i] += wt[tt] * acc[i];
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < (int)p.T * 16; e += DC_WAVES * 64) {
+    const int t = e >> 4, cc = e & 15;
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < DC_WAVES; ++w) s += yacc[w][t][cc];
+    y_out[(int64_t)t * p.d + c0 + cc] = f32_to_bf16(s);
+  }
+}
+
+
 bool decode_path_ok(const Engine& e, int64_t T) {
   if (e.dtype != 1 || T < 1 || T > 32) return false;
   if (e.d % 256 != 0) return false;
   const int ksteps = e.d / 256;
   return ksteps == 16 || ksteps == 8 || ksteps == 4 || ksteps == 2;
+}
+
+// The fused kernel serves every routed decode batch with more than one slot per token (CMOE_DECODE_FUSE=0
+// selects the two-kernel path, for comparison).
+bool decode_fuses_combine(const Engine& e, int64_t T) {
+  static const bool off = [] { const char* v = getenv("CMOE_DECODE_FUSE"); return v && v[0] == '0'; }();
+  if (off || use_simt_experts(e.dtype) || !decode_path_ok(e, T)) return false;
+  return !(e.G == 1 && e.n_always == 1) && e.S_all() > 1;
 }
 
 int64_t decode_unit_bound(const Engine& e, int64_t T, int which) {
@@ -241,6 +331,13 @@ hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char
     const int64_t nb = a.single ? e.max_width_pad / 16 : decode_unit_bound(e, T, 1);
     hipError_t err = two ? launch_gate_up<2>(a, e.d / 256, nb, s) : launch_gate_up<1>(a, e.d / 256, nb, s);
     if (err != hipSuccess || stage == 1) return err;
+  }
+  if (decode_fuses_combine(e, T)) {
+    const float* wbs = reinterpret_cast<const float*>(ws + L.w_by_slot);
+    bf16_t* yo = static_cast<bf16_t*>(y);
+    if (two) hipLaunchKernelGGL((decode_down_combine_kernel<2>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
+    else hipLaunchKernelGGL((decode_down_combine_kernel<1>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
+    return hipGetLastError();
   }
   a.work = reinterpret_cast<const int32_t*>(ws + L.work2);
   const int64_t nb = a.single ? e.d / 16 : decode_unit_bound(e, T, 2);

@@ -21,6 +21,7 @@ struct PlaceArgs {
   int32_t* slot2tok;           // [n_slots]
   int32_t* tok2slot;           // [T][S_all]
   float* slot_w;               // [T][S_all]
+  float* w_by_slot;            // [n_slots] the same weights indexed by slot
   int32_t* counts_out;         // optional user output: counts of the routed groups [G - n_always]
   int64_t T;
   int G, n_always, S_dyn, n_tiles;
@@ -46,24 +47,6 @@ __device__ __forceinline__ LaneWidths load_lane_widths(const PlaceArgs& p, int l
     lw.w[k] = (g < p.G) ? p.groups[g].width_pad : 0;
   }
   return lw;
-}
-
-// Inclusive prefix sums over the 64 lanes of a wave (six exchange steps).
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int n = __shfl_up(v, o, 64);
-    if (lane >= o) v += n;
-  }
-  return v;
-}
-__device__ __forceinline__ long long wave_incl_scan(long long v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const long long n = __shfl_up(v, o, 64);
-    if (lane >= o) v += n;
-  }
-  return v;
 }
 
 // One wave places one 64-token tile.  `counts` is the per-tile histogram table [n_tiles][G] (global memory, or
@@ -220,6 +203,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
       p.slot2tok[slot] = (int)t;
       p.tok2slot[t * S_all + a] = slot;
       p.slot_w[t * S_all + a] = 1.0f;
+      p.w_by_slot[slot] = 1.0f;
     }
   // routed entries: stable (token-ascending) rank inside the group = lower lanes present in its mask
   const uint32_t lt_lo = lane >= 32 ? 0xffffffffu : ((1u << lane) - 1u);
@@ -232,6 +216,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     p.slot2tok[slot] = (int)t;
     p.tok2slot[t * S_all + p.n_always + i] = slot;
     p.slot_w[t * S_all + p.n_always + i] = my_w[i];
+    p.w_by_slot[slot] = my_w[i];
   }
 }
 
