@@ -422,7 +422,7 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
 }
 
 // ---- decode front end ------------------------------------------------------------------------------
-// For batches of at most 32 tokens scoring is one launch and selection + permutation a second one.
+// For batches of at most 16 tokens scoring is one launch and selection + permutation a second one.
 // (Fusing all three behind a device-wide arrival counter was tried: on this multi-die part a device-scope
 // release/acquire pair writes back and invalidates the whole L2, which costs far more than a launch.)
 //
@@ -483,8 +483,8 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
                                                           const float* __restrict__ partial, int n_slices, int T) {
   extern __shared__ float pre[];                 // [T][n_rows + 1], then scores [T][MAX_SCORED + 1]
   __shared__ int32_t hist[MAX_GROUPS];
-  __shared__ int32_t sel_g[32 * MAX_DYN];
-  __shared__ float sel_w[32 * MAX_DYN];
+  __shared__ int32_t sel_g[16 * MAX_DYN];
+  __shared__ float sel_w[16 * MAX_DYN];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int ld = n_rows + 1;
@@ -509,7 +509,7 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
   io.sel_group = sel_g;
   io.sel_weight = sel_w;
   {
-    const int tok = tid / TEAM;                    // T <= 32 tokens x 4 lanes: the first two waves
+    const int tok = tid / TEAM;                    // T <= 16 tokens x 4 lanes: the first wave
     if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM);
   }
   __syncthreads();
@@ -532,9 +532,13 @@ __global__ __launch_bounds__(64) void tile_count_kernel(const int32_t* __restric
 
 PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& L, int32_t* counts_out);
 
+// Up to 16 tokens (one MFMA token tile): there the two launches beat the general scorer + tile router +
+// placement by 3-4 us; from 17 tokens on the general path, whose scorer spreads over hundreds of
+// workgroups, is 3-6 us faster (measured at d = 4096, 13 routed experts).
+constexpr int FRONT_MAX_T = 16;
 bool decode_front_ok(const Engine& e, int64_t T) {
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
-  return e.S_dyn > 0 && decode_path_ok(e, T) && n_rows % 16 == 0;
+  return e.S_dyn > 0 && T <= FRONT_MAX_T && decode_path_ok(e, T) && n_rows % 16 == 0;
 }
 
 // Router scoring (one launch) and selection + permutation (one launch) of a decode batch.
@@ -560,20 +564,11 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   const int ksteps = e.d / 256;                 // K steps of 32 per slice: d / (8 slices * 32)
   const int Ti = (int)T;
 #define CMOE_SCORE(NTT, KS) hipLaunchKernelGGL((decode_score_kernel<NTT, KS>), grid, block, 0, s, xx, ww, e.d, Ti, n_rows, pre_g)
-  if (T <= 16) {
-    switch (ksteps) {
-      case 16: CMOE_SCORE(1, 16); break;
-      case 8: CMOE_SCORE(1, 8); break;
-      case 4: CMOE_SCORE(1, 4); break;
-      default: CMOE_SCORE(1, 2); break;
-    }
-  } else {
-    switch (ksteps) {
-      case 16: CMOE_SCORE(2, 16); break;
-      case 8: CMOE_SCORE(2, 8); break;
-      case 4: CMOE_SCORE(2, 4); break;
-      default: CMOE_SCORE(2, 2); break;
-    }
+  switch (ksteps) {
+    case 16: CMOE_SCORE(1, 16); break;
+    case 8: CMOE_SCORE(1, 8); break;
+    case 4: CMOE_SCORE(1, 4); break;
+    default: CMOE_SCORE(1, 2); break;
   }
 #undef CMOE_SCORE
   hipError_t err = hipGetLastError();

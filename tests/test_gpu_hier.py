@@ -81,7 +81,7 @@ def test_hier_small(binding):
     hier.close()
 
 
-@pytest.mark.parametrize("T", [1, 7, 20, 32, 33])
+@pytest.mark.parametrize("T", [1, 7, 20, 32, 33, 64, 65])
 def test_hier_decode_batches(binding, T):
     """Small batches take the fused decode kernels (one launch scores, selects and permutes; the down
     kernel also combines); 33 tokens is the first size back on the tiled path."""

@@ -164,10 +164,11 @@ def test_small_bf16(binding, name, d, d_ff, N, N_s, N_k, T):
     layer.close()
 
 
-@pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 31, 32, 33, 64])
+@pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 31, 32, 33, 48, 64, 65])
 def test_small_bf16_decode_sizes(binding, T):
-    """Every batch size around the decode/tiled switch (32) and the 16-token MFMA tile, run twice so that
-    the self-resetting arrival counters of the fused decode kernels are exercised."""
+    """Every batch size around the decode/tiled switch of the expert kernels (32), the 16-token MFMA tile
+    and the one-tile limit of the two-launch routing front end (64); each runs twice and must give
+    identical bits."""
     cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
     weights = synth.make_weights(cfg)
     part = synth.trivial_partition(cfg)
@@ -296,7 +297,7 @@ def test_cfg1_full(binding):
 def test_cfg1_mid_batches(binding):
     """Batch sizes between the decode path and the large-tile regime: the contraction kernels run their
     128x128 and 256x128 tile shapes at the layer's real depth."""
-    _full(binding, 1, None, n_sample=32, sizes=[33, 300, 1000, 3072])
+    _full(binding, 1, None, n_sample=32, sizes=[33, 64, 65, 300, 1000, 3072])
 
 
 @pytest.mark.parametrize("n,n_s,n_k", [(8, 1, 5), (16, 3, 9), (16, 6, 6)])
