@@ -300,9 +300,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
           if (ks + 1 < NKS && f * NMS / (MI + NI) == j) load_frag(ks + 1, f, cur ^ 1);
         if (AHEAD >= 1) {
           const int m = ks * NMS + j;
+          // (a skinny tile has more DMA instructions than MFMAs: then several follow one MFMA)
 #pragma unroll
           for (int i = 0; i < L; ++i)
-            if ((i + 1) * NM / L - 1 == m) issue_nth(i);
+            if (L > NM ? (i * NM / L == m) : ((i + 1) * NM / L - 1 == m)) issue_nth(i);
         }
       }
     }
@@ -400,6 +401,10 @@ static const TileCfg kCfgs[] = {
     {256, 256, 2, 4, 4, 32},   // 5
     {256, 256, 2, 2, 0, 64},   // 6: half-tile ring, four waves of 128x128, one per SIMD: a third less LDS read
                                //    traffic than 0, 5-8 % faster under the power limit (the large-tile default)
+    {64, 128, 2, 2, 4, 64},    // 7: skinny tile for batches of tens of tokens per group, four whole K tiles deep: a
+                               //    CU keeps 72 KB of loads in flight, two thirds of them weights (such a launch
+                               //    is bound by HBM latency x bytes in flight, not by MFMA work).  Measured against
+                               //    32x128 (2 waves; 3 and 7 stages), 32x256 and 64x128 with 3 and 6 stages.
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -416,11 +421,12 @@ static int env_int(const char* name, int dflt) {
 // rounds = ceil(tiles / workgroup slots on the chip).  Relative times per round measured on the
 // LLaMA-shaped layers (K = d for every shape, so the ratios carry over), in units of the eight-wave
 // 256x256 tile: 256x256 with four waves 0.95 (one workgroup per CU), 256x128 0.58 (one per CU), 128x128
-// 0.66 (two per CU).  The model picks the measured best shape at
-// every batch size from 512 to 8192 tokens and a near-best one below.
+// 0.66 (two per CU), 64x128 0.30 (one per CU; it only wins while the launch is one or two rounds, i.e. up to
+// 128 tokens for the dense FFN and about 200 for the 16-expert layer).  The model picks the measured best
+// shape at every batch size from 33 to 8192 tokens or one within a few per cent of it.
 static int gate_up_cfg(const Engine& e, int64_t T) {
   struct Cand { int cfg, bm, bn, slots; double t; };
-  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}};
+  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}, {7, 64, 128, 1, 0.30}};
   const bool single = e.G == 1 && e.n_always == 1;
   int best = 0;
   double best_t = 1e30;
@@ -592,6 +598,7 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
     case 3: return launch_dma<128, 128, 64, 0, 2, 2, MODE>(a, s);
     case 4: return launch_dma<256, 128, 64, 3, 4, 2, MODE>(a, s);
     case 6: return launch_dma<256, 256, 64, 0, 2, 2, MODE>(a, s);
+    case 7: return launch_dma<64, 128, 64, 4, 2, 2, MODE>(a, s);
     default: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
   }
 }
