@@ -112,8 +112,10 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
   L.scores = take(sizeof(float) * 8 * Tn * std::max(e.r.n_sw_rows + e.r.n_lin_rows, 1));   // router K-slice partials
   L.h = take(es * (size_t)Tn * (size_t)e.h_per_token);
   L.y_slots = take(S_all == 1 ? 0 : es * (size_t)L.n_slots * e.d);
-  // reserved in full whenever a smaller batch could split K, so that the size grows with T
-  L.splitk = take((!use_simt_experts(e.dtype) && Tn > 32) ? bf16_splitk_bytes(e, Tn) : 0);
+  // Partial sums of a K-split contraction: reserved in full whenever the largest batch runs the tiled
+  // contraction kernels (then smaller ones may too, and may split further), so that the size grows with T.
+  L.splitk_bytes = (!use_simt_experts(e.dtype) && !decode_path_ok(e, Tn)) ? bf16_splitk_bytes(e, Tn) : 0;
+  L.splitk = take(L.splitk_bytes);
   L.total = off;
   return L;
 }
@@ -122,6 +124,7 @@ hipError_t launch_experts(const Engine& e, const void* x, int64_t T, char* ws, c
                           hipStream_t s, int stage) {
   if (T == 0) return hipSuccess;
   if (use_simt_experts(e.dtype)) return launch_experts_simt(e, x, T, ws, L, y, s, stage);
+  if (stage == 2 && decode_fuses_combine(e, T)) return launch_decode_down_combine(e, T, ws, L, y, s);
   if (decode_path_ok(e, T)) return launch_experts_decode(e, x, T, ws, L, y, s, stage);
   return launch_experts_bf16(e, x, T, ws, L, y, s, stage);
 }

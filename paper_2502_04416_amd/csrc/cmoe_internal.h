@@ -66,6 +66,7 @@ struct WsLayout {
   size_t h;                          // hidden activations, ragged: rows of group g are width_pad(g) wide
   size_t y_slots;                    // [n_slots][d]; unused when S_all == 1 (written straight to y)
   size_t splitk;                     // fp32 partial sums of a K-split contraction (small batches only)
+  size_t splitk_bytes;               // bytes reserved there (0: no contraction of this layout may split K)
   size_t total;
   int64_t n_slots;
   int n_tok_tiles;
@@ -134,6 +135,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
 // Decode batches (bf16, T <= 32): weight-streaming expert kernels, see decode.hip.
 bool decode_path_ok(const Engine& e, int64_t T);
 bool decode_fuses_combine(const Engine& e, int64_t T);   // the down kernel also does the weighted sum over slots
+hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
 hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                  hipStream_t s, int stage);
 // Upper bound of work items of grouped GEMM `which` (1: gate/up, 2: down) for T tokens.

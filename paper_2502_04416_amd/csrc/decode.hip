@@ -1,9 +1,10 @@
-// Expert kernels for decode batches (T <= 32 tokens, bf16): weight streaming bound by HBM bandwidth.
+// Expert kernels for decode batches (T <= 16 tokens, bf16; the fused down + combine kernel up to 32):
+// weight streaming bound by HBM bandwidth.
 //
 // Every expert group with at least one token is cut into units of 16 neurons (gate/up) or 16 output
 // columns (down).  The weights of a unit are the A operand of v_mfma_f32_16x16x32_bf16 and are read
 // straight from global memory exactly once, 64 contiguous bytes per row and instruction; the tokens
-// of the group (at most 32, gathered through slot2tok) are the B operand and stay in registers for
+// of the group (at most 16, gathered through slot2tok) are the B operand and stay in registers for
 // the whole unit.  The reduction dimension is split over the waves of a workgroup so that a unit
 // keeps many independent loads in flight; the partial sums are added in a fixed order through LDS.
 // This is the per-neuron form of the FFN, F(x) = sum_i h_i w_i (Eq. 1), evaluated only for the
@@ -275,18 +276,25 @@ __global__ __launch_bounds__(DC_WAVES * 64) void decode_down_combine_kernel(DecA
 }
 
 
+// Up to 16 tokens (one MFMA token tile) the weight-streaming kernels are the fastest form of both
+// contractions; from 17 tokens on a second token tile would double their register footprint, and the tiled
+// contraction on skinny tiles is as fast for the routed layer and 10-20 us faster for the dense one
+// (measured at d = 4096).
+constexpr int DECODE_MAX_T = 16;
 bool decode_path_ok(const Engine& e, int64_t T) {
-  if (e.dtype != 1 || T < 1 || T > 32) return false;
+  if (e.dtype != 1 || T < 1 || T > DECODE_MAX_T) return false;
   if (e.d % 256 != 0) return false;
   const int ksteps = e.d / 256;
   return ksteps == 16 || ksteps == 8 || ksteps == 4 || ksteps == 2;
 }
 
-// The fused kernel serves every routed decode batch with more than one slot per token (CMOE_DECODE_FUSE=0
-// selects the two-kernel path, for comparison).
+// The fused down + combine kernel serves every routed bf16 batch of at most 32 tokens with more than one slot
+// per token, whichever kernel produced the hidden activations (CMOE_DECODE_FUSE=0 selects the separate
+// kernels, for comparison).
+constexpr int DOWN_COMBINE_MAX_T = 32;
 bool decode_fuses_combine(const Engine& e, int64_t T) {
   static const bool off = [] { const char* v = getenv("CMOE_DECODE_FUSE"); return v && v[0] == '0'; }();
-  if (off || use_simt_experts(e.dtype) || !decode_path_ok(e, T)) return false;
+  if (off || use_simt_experts(e.dtype) || e.dtype != 1 || T < 1 || T > DOWN_COMBINE_MAX_T || e.d % 16 != 0) return false;
   return !(e.G == 1 && e.n_always == 1) && e.S_all() > 1;
 }
 
@@ -308,8 +316,7 @@ static hipError_t launch_gate_up(const DecArgs& a, int ksteps, int64_t n_blocks,
   return hipGetLastError();
 }
 
-hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
-                                 hipStream_t s, int stage) {
+static DecArgs make_dec_args(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y) {
   DecArgs a;
   a.x = static_cast<const bf16_t*>(x);
   a.w1 = static_cast<const bf16_t*>(e.w1);
@@ -318,6 +325,7 @@ hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char
   a.y = (e.S_all() == 1) ? static_cast<bf16_t*>(y) : reinterpret_cast<bf16_t*>(ws + L.y_slots);
   a.groups = e.groups;
   a.seg_off = reinterpret_cast<const int32_t*>(ws + L.seg_off);
+  a.work = nullptr;
   a.h_off = reinterpret_cast<const int64_t*>(ws + L.h_off);
   a.G = e.G;
   a.d = e.d;
@@ -325,24 +333,32 @@ hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
-  const bool two = T > 16;
+  return a;
+}
+
+// Down contraction + weighted sum over slots in one launch (callers check decode_fuses_combine first).
+hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s) {
+  const DecArgs a = make_dec_args(e, nullptr, T, ws, L, y);
+  const float* wbs = reinterpret_cast<const float*>(ws + L.w_by_slot);
+  bf16_t* yo = static_cast<bf16_t*>(y);
+  if (T > 16) hipLaunchKernelGGL((decode_down_combine_kernel<2>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
+  else hipLaunchKernelGGL((decode_down_combine_kernel<1>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
+  return hipGetLastError();
+}
+
+hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
+                                 hipStream_t s, int stage) {
+  DecArgs a = make_dec_args(e, x, T, ws, L, y);
   if (stage != 2) {
     a.work = reinterpret_cast<const int32_t*>(ws + L.work1);
     const int64_t nb = a.single ? e.max_width_pad / 16 : decode_unit_bound(e, T, 1);
-    hipError_t err = two ? launch_gate_up<2>(a, e.d / 256, nb, s) : launch_gate_up<1>(a, e.d / 256, nb, s);
+    hipError_t err = launch_gate_up<1>(a, e.d / 256, nb, s);
     if (err != hipSuccess || stage == 1) return err;
   }
-  if (decode_fuses_combine(e, T)) {
-    const float* wbs = reinterpret_cast<const float*>(ws + L.w_by_slot);
-    bf16_t* yo = static_cast<bf16_t*>(y);
-    if (two) hipLaunchKernelGGL((decode_down_combine_kernel<2>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
-    else hipLaunchKernelGGL((decode_down_combine_kernel<1>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
-    return hipGetLastError();
-  }
+  if (decode_fuses_combine(e, T)) return launch_decode_down_combine(e, T, ws, L, y, s);
   a.work = reinterpret_cast<const int32_t*>(ws + L.work2);
   const int64_t nb = a.single ? e.d / 16 : decode_unit_bound(e, T, 2);
-  if (two) hipLaunchKernelGGL((decode_down_kernel<2>), dim3((unsigned)nb), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((decode_down_kernel<1>), dim3((unsigned)nb), dim3(256), 0, s, a);
+  hipLaunchKernelGGL((decode_down_kernel<1>), dim3((unsigned)nb), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -523,7 +523,15 @@ int bf16_splitk(const Engine& e, int64_t T, int which) {
 // batch may split further than the largest one does.
 size_t bf16_splitk_bytes(const Engine& e, int64_t T) {
   (void)e;
-  return T > 32 ? SPLITK_MAX_BYTES : 0;
+  (void)T;
+  return SPLITK_MAX_BYTES;
+}
+
+// The split a launch may use: the chosen one, unless the slabs would not fit what the workspace reserved.
+static int splitk_that_fits(const Engine& e, int64_t T, int which, const WsLayout& L) {
+  const int ks = bf16_splitk(e, T, which);
+  const size_t per_part = (size_t)splitk_rows(e, T) * splitk_ldp(e, which) * sizeof(float);
+  return (ks > 1 && per_part * ks <= L.splitk_bytes) ? ks : 1;
 }
 
 // Finish of a K-split gate/up contraction: one workgroup per slot row adds the parts in order and applies
@@ -625,7 +633,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.n_blocks = (int)round_up64(gemm_work_bound(e, T, 1), 8);
   a.P = reinterpret_cast<float*>(ws + L.splitk);
   a.p_rows = splitk_rows(e, T);
-  a.k_split = bf16_splitk(e, T, 1);
+  a.k_split = splitk_that_fits(e, T, 1, L);
   a.ldp = splitk_ldp(e, 1);
   if (stage != 2) {
     hipError_t err = launch_cfg<1>(cfg_index(1, e, T), a, s);
@@ -655,7 +663,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
     const int64_t share = std::min<int64_t>(bound, (bound * c_max + 8 * c_min - 1) / (8 * c_min) + 2);
     a.n_blocks = (int)(remap && !a.single ? 8 * share : round_up64(bound, 8));
   }
-  a.k_split = bf16_splitk(e, T, 2);
+  a.k_split = splitk_that_fits(e, T, 2, L);
   a.ldp = splitk_ldp(e, 2);
   hipError_t err = launch_cfg<2>(cfg_index(2, e, T), a, s);
   if (err == hipSuccess && a.k_split > 1) {

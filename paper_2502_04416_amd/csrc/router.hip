@@ -359,28 +359,19 @@ __global__ __launch_bounds__(256) void router_gemm_kernel(const bf16_t* __restri
   }
 }
 
-// Sum the K-slice partials in slice order, then score, select and histogram a 64-token tile: the
-// 256 threads load and add the partials, then route the tile's 64 tokens in teams of four lanes.
-__global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io, const float* __restrict__ partial,
-                                                         int n_slices, int64_t T, int32_t* __restrict__ tile_counts,
-                                                         int G) {
-  extern __shared__ float pre[];                 // [TOK_TILE][n_rows + 1], then scores [TOK_TILE][MAX_SCORED + 1]
-  __shared__ int32_t hist[MAX_GROUPS];
-  const int tid = threadIdx.x;
-  const int n_rows = r.n_sw_rows + r.n_lin_rows;
-  const int ld = n_rows + 1;
-  float* sc = pre + TOK_TILE * ld;
-  constexpr int LDS_SC = MAX_SCORED + 1;
-  const int64_t t0 = (int64_t)blockIdx.x * TOK_TILE;
-  // n_rows is a multiple of 32: float4 loads, all slices of up to four vectors in flight together
+// Adds the K-slice partials [slice][T][n_rows] of tokens t0 .. t0+rows-1 in slice order into pre[row][ld]
+// (LDS; rows past T become zero).  n_rows is a multiple of 4: float4 loads, all slices of up to four vectors
+// per thread (sixteen loads) in flight together.  Called by all 256 threads of the workgroup.
+__device__ __forceinline__ void sum_partials(const float* __restrict__ partial, int n_slices, int64_t T, int64_t t0,
+                                             int rows, int n_rows, float* pre, int ld, int tid) {
   const int vec_per_row = n_rows >> 2;
-  const int n_vec = TOK_TILE * vec_per_row;
+  const int n_vec = rows * vec_per_row;
   for (int i0 = tid; i0 < n_vec; i0 += 4 * 256) {
     float4 v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int ks0 = 0; ks0 < n_slices; ks0 += 4) {
-      float4 ld4[4][4];                      // [slice][vector]: sixteen loads in flight, added in slice order
+      float4 ld4[4][4];                      // [slice][vector]
 #pragma unroll
       for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -408,6 +399,22 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
       }
     }
   }
+}
+
+// Sum the K-slice partials in slice order, then score, select and histogram a 64-token tile: the
+// 256 threads load and add the partials, then route the tile's 64 tokens in teams of four lanes.
+__global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io, const float* __restrict__ partial,
+                                                         int n_slices, int64_t T, int32_t* __restrict__ tile_counts,
+                                                         int G) {
+  extern __shared__ float pre[];                 // [TOK_TILE][n_rows + 1], then scores [TOK_TILE][MAX_SCORED + 1]
+  __shared__ int32_t hist[MAX_GROUPS];
+  const int tid = threadIdx.x;
+  const int n_rows = r.n_sw_rows + r.n_lin_rows;
+  const int ld = n_rows + 1;
+  float* sc = pre + TOK_TILE * ld;
+  constexpr int LDS_SC = MAX_SCORED + 1;
+  const int64_t t0 = (int64_t)blockIdx.x * TOK_TILE;
+  sum_partials(partial, n_slices, T, t0, TOK_TILE, n_rows, pre, ld, tid);
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
   const int n_tok = (T - t0 < TOK_TILE) ? (int)(T - t0) : TOK_TILE;
@@ -422,7 +429,7 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
 }
 
 // ---- decode front end ------------------------------------------------------------------------------
-// For batches of at most 16 tokens scoring is one launch and selection + permutation a second one.
+// For batches of at most one 64-token tile scoring is one launch and selection + permutation a second one.
 // (Fusing all three behind a device-wide arrival counter was tried: on this multi-die part a device-scope
 // release/acquire pair writes back and invalidates the whole L2, which costs far more than a launch.)
 //
@@ -483,8 +490,8 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
                                                           const float* __restrict__ partial, int n_slices, int T) {
   extern __shared__ float pre[];                 // [T][n_rows + 1], then scores [T][MAX_SCORED + 1]
   __shared__ int32_t hist[MAX_GROUPS];
-  __shared__ int32_t sel_g[16 * MAX_DYN];
-  __shared__ float sel_w[16 * MAX_DYN];
+  __shared__ int32_t sel_g[TOK_TILE * MAX_DYN];
+  __shared__ float sel_w[TOK_TILE * MAX_DYN];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int ld = n_rows + 1;
@@ -492,16 +499,7 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
   constexpr int LDS_SC = MAX_SCORED + 1;
   LaneWidths lw;
   if (wave == 0) lw = load_lane_widths(pl, lane);          // needed last, requested first
-  for (int i = tid; i < T * n_rows; i += 256) {
-    const int row = i / n_rows, col = i - row * n_rows;
-    float v[DEC_SLICES];
-#pragma unroll
-    for (int ks = 0; ks < DEC_SLICES; ++ks) v[ks] = ks < n_slices ? partial[(int64_t)ks * T * n_rows + i] : 0.0f;
-    float acc = 0.0f;
-#pragma unroll
-    for (int ks = 0; ks < DEC_SLICES; ++ks) acc += v[ks];
-    pre[row * ld + col] = acc;
-  }
+  sum_partials(partial, n_slices, T, 0, T, n_rows, pre, ld, tid);
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
   score_tile(r, io, pre, ld, sc, LDS_SC, T, 0, tid, 256);
@@ -509,7 +507,7 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
   io.sel_group = sel_g;
   io.sel_weight = sel_w;
   {
-    const int tok = tid / TEAM;                    // T <= 16 tokens x 4 lanes: the first wave
+    const int tok = tid / TEAM;                    // at most 64 tokens x 4 lanes
     if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM);
   }
   __syncthreads();
@@ -532,13 +530,46 @@ __global__ __launch_bounds__(64) void tile_count_kernel(const int32_t* __restric
 
 PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& L, int32_t* counts_out);
 
-// Up to 16 tokens (one MFMA token tile): there the two launches beat the general scorer + tile router +
-// placement by 3-4 us; from 17 tokens on the general path, whose scorer spreads over hundreds of
-// workgroups, is 3-6 us faster (measured at d = 4096, 13 routed experts).
-constexpr int FRONT_MAX_T = 16;
+// The MFMA scorer needs bf16 operands, K slices of 256 and whole 32-row blocks of router rows (at most five).
+static bool mfma_scorer_ok(const Engine& e) {
+  const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
+  return e.dtype == 1 && e.d % 256 == 0 && n_rows % 32 == 0 && n_rows / 32 <= 5;
+}
+
+// Pre-activation partials [slice][T][n_rows] of all router rows by router_gemm_kernel.
+static hipError_t launch_scorer_gemm(const Engine& e, const void* x, int64_t T, float* partial, hipStream_t s,
+                                     int& n_slices) {
+  const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
+  // K slices: enough workgroups to fill 256 CUs, at least 256 of K per slice, at most the partial buffer's 8
+  const int n_tt = (int)((T + RT_TOK - 1) / RT_TOK);
+  n_slices = (512 + n_tt - 1) / n_tt;
+  if (n_slices > 8) n_slices = 8;
+  while (n_slices > 1 && (e.d % (n_slices * 256) != 0)) --n_slices;
+  const int k_slice = e.d / n_slices;
+  dim3 grid(n_tt, n_slices), block(256);
+  const bf16_t* xx = static_cast<const bf16_t*>(x);
+  const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
+  switch (n_rows / 32) {
+    case 1: hipLaunchKernelGGL(router_gemm_kernel<1>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+    case 2: hipLaunchKernelGGL(router_gemm_kernel<2>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+    case 3: hipLaunchKernelGGL(router_gemm_kernel<3>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+    case 4: hipLaunchKernelGGL(router_gemm_kernel<4>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+    default: hipLaunchKernelGGL(router_gemm_kernel<5>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
+  }
+  return hipGetLastError();
+}
+
+// One tile of at most 64 tokens is scored in one launch and selected + placed by one workgroup in a second.
+// Up to 16 tokens (one MFMA token tile) the scorer is decode_score_kernel, which beats the general one by
+// 3-4 us there; from 17 tokens on it is the general scorer, whose work spreads over hundreds of workgroups
+// (measured at d = 4096, 13 routed experts).  The larger batches need the tile's pre-activations and scores
+// to fit the 64 KB of LDS a workgroup gets by default next to 14 KB of static arrays.
+constexpr int FRONT_SCORE_MAX_T = 16;
 bool decode_front_ok(const Engine& e, int64_t T) {
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
-  return e.S_dyn > 0 && T <= FRONT_MAX_T && decode_path_ok(e, T) && n_rows % 16 == 0;
+  if (e.S_dyn <= 0 || T < 1 || T > TOK_TILE) return false;
+  if (T <= FRONT_SCORE_MAX_T) return decode_path_ok(e, T) && n_rows % 16 == 0;
+  return mfma_scorer_ok(e) && sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1) <= 48 * 1024;
 }
 
 // Router scoring (one launch) and selection + permutation (one launch) of a decode batch.
@@ -558,23 +589,29 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   const PlaceArgs pl = make_place_args(e, T, ws, L, counts_out);
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
   float* pre_g = reinterpret_cast<float*>(ws + L.scores);
-  dim3 grid(n_rows / 16, DEC_SLICES), block(64);
-  const bf16_t* xx = static_cast<const bf16_t*>(x);
-  const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
-  const int ksteps = e.d / 256;                 // K steps of 32 per slice: d / (8 slices * 32)
   const int Ti = (int)T;
+  int n_slices = DEC_SLICES;
+  hipError_t err;
+  if (T <= FRONT_SCORE_MAX_T) {
+    dim3 grid(n_rows / 16, DEC_SLICES), block(64);
+    const bf16_t* xx = static_cast<const bf16_t*>(x);
+    const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
+    const int ksteps = e.d / 256;                 // K steps of 32 per slice: d / (8 slices * 32)
 #define CMOE_SCORE(NTT, KS) hipLaunchKernelGGL((decode_score_kernel<NTT, KS>), grid, block, 0, s, xx, ww, e.d, Ti, n_rows, pre_g)
-  switch (ksteps) {
-    case 16: CMOE_SCORE(1, 16); break;
-    case 8: CMOE_SCORE(1, 8); break;
-    case 4: CMOE_SCORE(1, 4); break;
-    default: CMOE_SCORE(1, 2); break;
-  }
+    switch (ksteps) {
+      case 16: CMOE_SCORE(1, 16); break;
+      case 8: CMOE_SCORE(1, 8); break;
+      case 4: CMOE_SCORE(1, 4); break;
+      default: CMOE_SCORE(1, 2); break;
+    }
 #undef CMOE_SCORE
-  hipError_t err = hipGetLastError();
+    err = hipGetLastError();
+  } else {
+    err = launch_scorer_gemm(e, x, T, pre_g, s, n_slices);
+  }
   if (err != hipSuccess) return err;
   const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
-  hipLaunchKernelGGL(route_place_kernel, dim3(1), dim3(256), smem, s, e.r, io, pl, pre_g, DEC_SLICES, Ti);
+  hipLaunchKernelGGL(route_place_kernel, dim3(1), dim3(256), smem, s, e.r, io, pl, pre_g, n_slices, Ti);
   return hipGetLastError();
 }
 
@@ -593,26 +630,10 @@ hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, co
   io.S_dyn = e.S_dyn;
   int32_t* tile_counts = reinterpret_cast<int32_t*>(ws + L.tile_counts);
   const int n_rows = e.r.n_sw_rows + e.r.n_lin_rows;
-  const bool mfma = e.dtype == 1 && e.d % 256 == 0 && n_rows % 32 == 0 && n_rows / 32 <= 5;
-  if (mfma) {
-    // K slices: enough workgroups to fill 256 CUs, at least 256 of K per slice, at most the partial buffer's 8
-    const int n_tt = (int)((T + RT_TOK - 1) / RT_TOK);
-    int n_slices = (512 + n_tt - 1) / n_tt;
-    if (n_slices > 8) n_slices = 8;
-    while (n_slices > 1 && (e.d % (n_slices * 256) != 0)) --n_slices;
-    const int k_slice = e.d / n_slices;
+  if (mfma_scorer_ok(e)) {
+    int n_slices = 1;
     float* partial = reinterpret_cast<float*>(ws + L.scores);
-    dim3 grid(n_tt, n_slices), block(256);
-    const bf16_t* xx = static_cast<const bf16_t*>(x);
-    const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
-    switch (n_rows / 32) {
-      case 1: hipLaunchKernelGGL(router_gemm_kernel<1>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
-      case 2: hipLaunchKernelGGL(router_gemm_kernel<2>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
-      case 3: hipLaunchKernelGGL(router_gemm_kernel<3>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
-      case 4: hipLaunchKernelGGL(router_gemm_kernel<4>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
-      default: hipLaunchKernelGGL(router_gemm_kernel<5>, grid, block, 0, s, xx, ww, e.d, T, k_slice, partial); break;
-    }
-    hipError_t err = hipGetLastError();
+    hipError_t err = launch_scorer_gemm(e, x, T, partial, s, n_slices);
     if (err != hipSuccess) return err;
     const size_t smem = sizeof(float) * (size_t)TOK_TILE * (n_rows + 1 + MAX_SCORED + 1);
     hipLaunchKernelGGL(route_tile_kernel, dim3(L.n_tok_tiles), dim3(256), smem, s, e.r, io, partial, n_slices, T,

@@ -243,6 +243,23 @@ def test_k_split_batches(binding, T):
     layer.close()
 
 
+@pytest.mark.parametrize("T", [1, 17, 32, 100])
+def test_small_batches_without_decode_kernels(binding, T):
+    """A model width the weight-streaming decode kernels are not built for (d = 1536: six K steps per
+    slice): batches of a few tokens then run the tiled contraction kernels, whose few tiles split K, so the
+    workspace must hold the partial sums at every batch size."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=1536, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    out = layer.forward(x)
+    _say("no-decode T=%d" % T, check_flat(cfg, weights, part, x, out))
+    _say("no-decode T=%d dense" % T, check_dense(cfg, weights, x, layer.dense_forward(x)))
+    assert np.array_equal(out["y"], layer.forward(x)["y"])
+    layer.close()
+
+
 def test_bias_update_loop_balances_the_load(binding):
     """Sec. 4.3: forward -> per-expert counts -> cmoe_update_bias, repeated on one batch.  The library's
     biases follow the oracle's step applied to the same counts, the most loaded expert's share falls,
