@@ -29,10 +29,12 @@ struct PlaceArgs {
   int decode;                  // 1: the work lists count decode units (16 neurons / 16 output columns per unit)
 };
 
-// All 64 callers are one wave: LDS traffic of a wave completes in order, so a workgroup-scope fence (which
-// waits for this wave's outstanding LDS operations) is enough to hand data between its lanes.
+// All 64 callers are one wave: the LDS operations of a wave are carried out in the order it issued them, so
+// waiting for its outstanding ones (and keeping the compiler from moving LDS accesses across this point) is
+// enough to hand data between its lanes.  Deliberately not a fence: a workgroup-scope fence also waits for
+// every global store the wave has in flight (a full memory round trip each time, 3.5 us per placement).
 __device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_wave_barrier();
 }
 
@@ -64,13 +66,16 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
   const int64_t t = (int64_t)tile * TOK_TILE + lane;
   const bool valid = t < p.T;
   // this token's routed entries, requested first: nothing below depends on them until the marking pass
+  // (S_dyn and G are the same for every lane: the unrolled loops below leave at the first unused entry
+  // through a scalar branch instead of running all MAX_DYN predicated bodies; one wave pays four cycles
+  // for every vector instruction, used or not)
   int my_g[MAX_DYN];
   float my_w[MAX_DYN];
 #pragma unroll
   for (int i = 0; i < MAX_DYN; ++i) {
-    const bool ok = valid && i < p.S_dyn;
-    my_g[i] = ok ? sel_g[t * p.S_dyn + i] : -1;
-    my_w[i] = ok ? sel_w[t * p.S_dyn + i] : 0.0f;
+    if (i >= p.S_dyn) break;
+    my_g[i] = valid ? sel_g[t * p.S_dyn + i] : -1;
+    my_w[i] = valid ? sel_w[t * p.S_dyn + i] : 0.0f;
   }
 #pragma unroll
   for (int k = 0; k < GPL; ++k) {
@@ -84,6 +89,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     const int g = lane + 64 * k;
     tot[k] = 0;
     prev[k] = 0;
+    if (64 * k >= p.G) continue;            // no lane has a group in this half
     if (g < p.G) {
       if (g < p.n_always) {
         tot[k] = (int)p.T;
@@ -110,8 +116,10 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
   }
   wave_lds_sync();                          // the cleared masks are visible to every lane
 #pragma unroll
-  for (int i = 0; i < MAX_DYN; ++i)
+  for (int i = 0; i < MAX_DYN; ++i) {
+    if (i >= p.S_dyn) break;
     if (my_g[i] >= 0) atomicOr(&present[my_g[i]][lane >> 5], 1u << (lane & 31));
+  }
   // exclusive prefix over groups of: slots, work items of the two contractions, hidden-buffer elements
   int run0 = 0, w1_0 = 0, w2_0 = 0;
   long long h0 = 0;
@@ -119,6 +127,10 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
 #pragma unroll
   for (int k = 0; k < GPL; ++k) {
     const int g = lane + 64 * k;
+    if (k > 0 && 64 * k >= p.G) {           // nothing to add: skip this half's four scans
+      n1[k] = 0; n2[k] = 0; w1x[k] = w1_0; w2x[k] = w2_0;
+      continue;
+    }
     const int cnt = tot[k], wp = lw.w[k];
     int a1, a2;
     if (p.decode) {
@@ -158,6 +170,8 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
       p.work2[p.G] = w2_0;
       p.h_off[p.G] = h0;
     }
+  }
+  if (tile == 0 && !p.decode) {            // (the decode kernels take their units in list order: no shares)
     // Where each XCD's share of a work list starts (entries G+1 .. G+9 of the list): contiguous ranges of
     // equal estimated cost, so that the tiles sharing operands stay in one L2 while the eight dies finish
     // together.  The gate/up tiles all have the full depth d; a down tile costs its group's width
@@ -173,6 +187,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
 #pragma unroll
     for (int k = 0; k < GPL; ++k) {
       c2[k] = cdiv(lw.w[k], 64) + TILE_FIXED_COST;
+      if (k > 0 && 64 * k >= p.G) { cx[k] = c0; continue; }
       const int cost = n2[k] * c2[k];
       const int ci = wave_incl_scan(cost, lane);
       cx[k] = c0 + ci - cost;
@@ -182,6 +197,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     for (int x = 1; x < N_XCD; ++x) {
 #pragma unroll
       for (int k = 0; k < GPL; ++k) {
+        if (k > 0 && 64 * k >= p.G) continue;
         // list 1: equal item counts; list 2: equal cost
         const int t1 = (int)((long long)x * w1_0 / N_XCD);
         if (n1[k] > 0 && w1x[k] <= t1 && t1 < w1x[k] + n1[k]) xs[0][x] = t1;
@@ -210,6 +226,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
   const uint32_t lt_hi = lane > 32 ? ((1u << (lane - 32)) - 1u) : 0u;
 #pragma unroll
   for (int i = 0; i < MAX_DYN; ++i) {
+    if (i >= p.S_dyn) break;
     const int g = my_g[i];
     if (g < 0) continue;
     const int slot = base[g] + __popc(present[g][0] & lt_lo) + __popc(present[g][1] & lt_hi);

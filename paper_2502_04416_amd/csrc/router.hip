@@ -123,13 +123,34 @@ struct TeamSel {
   int n;                   // entries written so far
 };
 
+// Gate parameters (Eq. 9) of the experts a team lane looks after, experts lo + q + 4u: requested in one go,
+// as early as the caller knows `lo`, so that one memory latency covers them all (a load of u_j for each
+// winner inside the selection rounds would add a dependent round trip per round).
+struct GateRegs { float u[TEAM_SLOTS], b[TEAM_SLOTS]; };
+__device__ __forceinline__ GateRegs load_gate_regs(const RouterDev& r, const RouteIO& io, int lo, int n, int q) {
+  GateRegs gr;
+#pragma unroll
+  for (int k = 0; k < TEAM_SLOTS; ++k) {
+    if (k * TEAM >= n) break;               // uniform: slots past the last expert are never read
+    const int j = q + TEAM * k;
+    const bool ok = r.use_gate && j < n;
+    gr.u[k] = (ok && io.gate_u) ? io.gate_u[lo + j] : 1.0f;
+    gr.b[k] = (ok && io.gate_b) ? io.gate_b[lo + j] : 0.0f;
+  }
+  return gr;
+}
+
 __device__ __forceinline__ void team_select_routed(const RouterDev& r, const RouteIO& io, const float* sc, int lo,
                                                    int n, float scale, int group_base, int64_t t, TeamSel& st,
-                                                   int32_t* topk_ptr, int32_t* hist, int q) {
+                                                   int32_t* topk_ptr, int32_t* hist, int q, const GateRegs& gr) {
+  // slots in use: the same for every lane, so each unrolled loop leaves at the first unused slot through a
+  // scalar branch (a wave pays for every predicated vector instruction, and n is often a quarter of the cap)
+  const int n_used = (n + TEAM - 1) / TEAM;
   float key[TEAM_SLOTS], sp[TEAM_SLOTS];
   float mx = -INFINITY;
 #pragma unroll
   for (int u = 0; u < TEAM_SLOTS; ++u) {
+    if (u >= n_used) break;
     const int j = q + TEAM * u;
     const float s = j < n ? (r.score_abs ? fabsf(sc[lo + j]) : sc[lo + j]) : -INFINITY;
     key[u] = s;
@@ -142,6 +163,7 @@ __device__ __forceinline__ void team_select_routed(const RouterDev& r, const Rou
     float sum = 0.0f;
 #pragma unroll
     for (int u = 0; u < TEAM_SLOTS; ++u) {
+      if (u >= n_used) break;
       sp[u] = (q + TEAM * u < n) ? expf(key[u] - mx) : 0.0f;
       sum += sp[u];
     }
@@ -149,38 +171,42 @@ __device__ __forceinline__ void team_select_routed(const RouterDev& r, const Rou
     sum += __shfl_xor(sum, 2, 64);
 #pragma unroll
     for (int u = 0; u < TEAM_SLOTS; ++u) {
+      if (u >= n_used) break;
       const int j = q + TEAM * u;
       sp[u] = sp[u] / sum;
-      key[u] = j < n ? sp[u] + (io.gate_b ? io.gate_b[lo + j] : 0.0f) : -INFINITY;
+      key[u] = j < n ? sp[u] + gr.b[u] : -INFINITY;
     }
   }
   uint32_t taken = 0u;
   for (int k = 0; k < r.top_k; ++k) {
-    float best = -INFINITY, best_sp = 0.0f;
+    float best = -INFINITY, best_sp = 0.0f, best_u = 1.0f;
     int bj = 0x7fffffff;
 #pragma unroll
     for (int u = 0; u < TEAM_SLOTS; ++u) {
+      if (u >= n_used) break;
       const int j = q + TEAM * u;
       const bool cand = j < n && ((taken >> u) & 1u) == 0u;
       if (cand && (bj == 0x7fffffff || key[u] > best)) {
         best = key[u];
         best_sp = sp[u];
+        best_u = gr.u[u];
         bj = j;
       }
     }
 #pragma unroll
     for (int o = 1; o < TEAM; o <<= 1) {
-      const float ob = __shfl_xor(best, o, 64), osp = __shfl_xor(best_sp, o, 64);
+      const float ob = __shfl_xor(best, o, 64), osp = __shfl_xor(best_sp, o, 64), ou = __shfl_xor(best_u, o, 64);
       const int oj = __shfl_xor(bj, o, 64);
       const bool take = oj != 0x7fffffff && (bj == 0x7fffffff || ob > best || (ob == best && oj < bj));
       best = take ? ob : best;
       best_sp = take ? osp : best_sp;
+      best_u = take ? ou : best_u;
       bj = take ? oj : bj;
     }
     if ((bj & (TEAM - 1)) == q) taken |= 1u << (bj / TEAM);
     if (q == 0) {
       float gate = 1.0f;
-      if (r.use_gate && io.gate_u) gate = 1.0f + best_sp * io.gate_u[lo + bj];
+      if (r.use_gate && io.gate_u) gate = 1.0f + best_sp * best_u;
       const int g = group_base + bj;
       io.sel_group[t * io.S_dyn + st.n] = g;
       io.sel_weight[t * io.S_dyn + st.n] = scale * gate;
@@ -193,12 +219,15 @@ __device__ __forceinline__ void team_select_routed(const RouterDev& r, const Rou
 
 // Selection for one token by one team: `sc` holds the token's n_scored scores (Eq. 8), `lin` its linear
 // outer logits (hierarchy only; every lane of the team evaluates the few outer logits itself).
+// `flat_gr`: gate parameters of a flat layer's experts, which the caller requested before it had the scores
+// (ignored for a hierarchy, whose expert range depends on the outer selection).
 __device__ __forceinline__ void route_select_team(const RouterDev& r, const RouteIO& io, const float* sc,
-                                                  const float* lin, int64_t t, int32_t* hist, int q) {
+                                                  const float* lin, int64_t t, int32_t* hist, int q,
+                                                  const GateRegs& flat_gr) {
   TeamSel st{0};
   if (r.outer_top_k == 0) {
     team_select_routed(r, io, sc, 0, r.n_scored, 1.0f, r.n_always, t, st,
-                       io.topk_out ? io.topk_out + t * r.top_k : nullptr, hist, q);
+                       io.topk_out ? io.topk_out + t * r.top_k : nullptr, hist, q, flat_gr);
     return;
   }
   int oe[MAX_OUTER_TOPK];
@@ -233,9 +262,11 @@ __device__ __forceinline__ void route_select_team(const RouterDev& r, const Rout
       }
       ++st.n;
     }
-    if (r.top_k > 0)
+    if (r.top_k > 0) {
+      const GateRegs gr = load_gate_regs(r, io, e * r.n_r_sub, r.n_r_sub, q);
       team_select_routed(r, io, sc, e * r.n_r_sub, r.n_r_sub, w_e, gbase + r.sub_has_shared, t, st,
-                         io.topk_out ? io.topk_out + (t * r.outer_top_k + i) * r.top_k : nullptr, hist, q);
+                         io.topk_out ? io.topk_out + (t * r.outer_top_k + i) * r.top_k : nullptr, hist, q, gr);
+    }
   }
 }
 
@@ -414,6 +445,8 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
   float* sc = pre + TOK_TILE * ld;
   constexpr int LDS_SC = MAX_SCORED + 1;
   const int64_t t0 = (int64_t)blockIdx.x * TOK_TILE;
+  GateRegs flat_gr;
+  if (r.outer_top_k == 0) flat_gr = load_gate_regs(r, io, 0, r.n_scored, tid % TEAM);   // needed last, requested first
   sum_partials(partial, n_slices, T, t0, TOK_TILE, n_rows, pre, ld, tid);
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
@@ -422,7 +455,7 @@ __global__ __launch_bounds__(256) void route_tile_kernel(RouterDev r, RouteIO io
   __syncthreads();
   {
     const int tok = tid / TEAM;                    // 256 threads = 64 tokens x 4 lanes
-    if (tok < n_tok) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, t0 + tok, hist, tid % TEAM);
+    if (tok < n_tok) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, t0 + tok, hist, tid % TEAM, flat_gr);
   }
   __syncthreads();
   for (int g = tid; g < G; g += 256) tile_counts[(int64_t)blockIdx.x * G + g] = hist[g];
@@ -499,6 +532,8 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
   constexpr int LDS_SC = MAX_SCORED + 1;
   LaneWidths lw;
   if (wave == 0) lw = load_lane_widths(pl, lane);          // needed last, requested first
+  GateRegs flat_gr;
+  if (r.outer_top_k == 0) flat_gr = load_gate_regs(r, io, 0, r.n_scored, tid % TEAM);
   sum_partials(partial, n_slices, T, 0, T, n_rows, pre, ld, tid);
   for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   __syncthreads();
@@ -508,7 +543,7 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
   io.sel_weight = sel_w;
   {
     const int tok = tid / TEAM;                    // at most 64 tokens x 4 lanes
-    if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM);
+    if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM, flat_gr);
   }
   __syncthreads();
   if (wave == 0) place_tile(pl, 0, hist, lane, sel_g, sel_w, lw);
