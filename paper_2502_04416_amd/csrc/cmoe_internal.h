@@ -132,7 +132,8 @@ bool decode_front_ok(const Engine& e, int64_t T);
 hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
                                int32_t* topk_out, int32_t* outer_out, float* scores_out, int32_t* counts_out,
                                hipStream_t s);
-// Decode batches (bf16, T <= 32): weight-streaming expert kernels, see decode.hip.
+// Decode batches (bf16, T <= 16; the fused down + combine kernel up to 32): weight-streaming expert kernels,
+// see decode.hip.
 bool decode_path_ok(const Engine& e, int64_t T);
 bool decode_fuses_combine(const Engine& e, int64_t T);   // the down kernel also does the weighted sum over slots
 hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
