@@ -32,6 +32,7 @@ struct GemmArgs {
   int single;                // 1: one always-on group holding all T tokens; no device schedule is read
   int n_blocks;              // grid size (multiple of 8) before the K split
   int xcd_remap;             // 1: consecutive work items run on the same XCD
+  int zero_pad;              // 1: tile rows past the end of a group read zeros instead of repeating its last row
   // K split: k_split > 1 workgroups share one tile, each multiplies a contiguous range of K tiles and
   // stores its fp32 partial sums to P [k_split][p_rows][ldp] (row = slot, column = column of the tile
   // grid); a finishing kernel adds the parts in order and applies the epilogue.  Used when a launch has
@@ -47,6 +48,12 @@ struct GemmArgs {
 // which global chunk a lane fetches is free, so the XOR swizzle is applied on the global side.  No
 // VGPRs are spent on staging, and STAGES-1 tiles are in flight while one is multiplied.
 __device__ __attribute__((aligned(16))) uint32_t g_zero_chunk[4] = {0, 0, 0, 0};
+// A row of zeros as long as any K this file meets in practice.  Tile rows past the end of a group (ragged
+// expert segments fill their last row tile to 50 % on average) read it instead of a real row: the result
+// rows are discarded either way, but an MFMA whose operand is all zeros draws less power than one on real
+// data, and on this part the clock under MFMA load is set by power.
+constexpr int ZERO_ROW_ELEMS = 32768;
+__device__ __attribute__((aligned(256))) bf16_t g_zero_row[ZERO_ROW_ELEMS];
 
 
 template <int N>
@@ -158,6 +165,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
   const int mt = sr * GM + rem % rows_in_sr;
   const int nt = rem / rows_in_sr;
 
+  // every offset a row source is read at stays below K_full rounded up to a whole K tile
+  const bool use_zero_row = p.zero_pad && K_full + BKT <= ZERO_ROW_ELEMS;
   // per-lane sources: transfer i of this wave covers tile rows rg*8 .. rg*8+7, rg = wave + i*NW; the lane
   // writes physical chunk lane%8 of row rg*8 + lane/8 and therefore fetches logical chunk (lane%8) ^ swz(row)
   const bf16_t* a_src[A_CH];
@@ -168,22 +177,26 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     const int row = (wave + i * NW) * RPI + lane / CPR;
     a_coff[i] = (((lane % CPR) ^ ((row >> SWZ_SHIFT) & (CPR - 1))) << 3);
     int r = mt * BM + row;
-    if (r >= cnt) r = cnt - 1;
+    const bool past = r >= cnt;
+    if (past) r = cnt - 1;
     if (MODE == 1) {
       const int64_t tok = p.slot2tok ? p.slot2tok[seg0 + r] : (seg0 + r);
       a_src[i] = p.A + tok * p.d + a_coff[i] + k_first;
     } else {
       a_src[i] = p.A + hoff + (int64_t)r * wp + a_coff[i] + k_first;
     }
+    if (past && use_zero_row) a_src[i] = g_zero_row + a_coff[i] + k_first;
   }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
     const int row = (wave + i * NW) * RPI + lane / CPR;
     b_coff[i] = (((lane % CPR) ^ ((row >> SWZ_SHIFT) & (CPR - 1))) << 3);
     int n = nt * BN + row;
-    if (n >= n_cols) n = n_cols - 1;
+    const bool past = n >= n_cols;
+    if (past) n = n_cols - 1;
     if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + b_coff[i] + k_first;
     else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + b_coff[i] + k_first;
+    if (past && use_zero_row) b_src[i] = g_zero_row + b_coff[i] + k_first;
   }
   const int KT = (K + BKT - 1) / BKT;
   const bool k_ragged = (K % BKT) != 0;
@@ -624,6 +637,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.xcd_remap = remap;
+  a.zero_pad = env_int("CMOE_ZERO_PAD", 1);
   // gate/up
   a.A = static_cast<const bf16_t*>(x);
   a.B = static_cast<const bf16_t*>(e.w1);
