@@ -111,7 +111,7 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
   L.w_by_slot = take(sizeof(float) * L.n_slots);
   L.scores = take(sizeof(float) * 8 * Tn * std::max(e.r.n_sw_rows + e.r.n_lin_rows, 1));   // router K-slice partials
   L.h = take(es * (size_t)Tn * (size_t)e.h_per_token);
-  L.y_slots = take(S_all == 1 ? 0 : es * (size_t)L.n_slots * e.d);
+  L.y_slots = take(e.direct_output() ? 0 : es * (size_t)L.n_slots * e.d);
   // Partial sums of a K-split contraction: reserved in full whenever the largest batch runs the tiled
   // contraction kernels (then smaller ones may too, and may split further), so that the size grows with T.
   L.splitk_bytes = (!use_simt_experts(e.dtype) && !decode_path_ok(e, Tn)) ? bf16_splitk_bytes(e, Tn) : 0;

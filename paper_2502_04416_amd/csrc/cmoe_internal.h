@@ -64,7 +64,7 @@ struct WsLayout {
   size_t w_by_slot;                  // [n_slots] float: the combine weight of each slot (decode batches)
   size_t scores;                     // [8][T][router rows] float: K-slice partial pre-activations of the router
   size_t h;                          // hidden activations, ragged: rows of group g are width_pad(g) wide
-  size_t y_slots;                    // [n_slots][d]; unused when S_all == 1 (written straight to y)
+  size_t y_slots;                    // [n_slots][d]; unused by a direct-output engine (written straight to y)
   size_t splitk;                     // fp32 partial sums of a K-split contraction (small batches only)
   size_t splitk_bytes;               // bytes reserved there (0: no contraction of this layout may split K)
   size_t total;
@@ -93,6 +93,10 @@ struct Engine {
   const float* gate_b = nullptr;   // [n_scored] or null
   const float* lin_off = nullptr;  // [n_lin] or null
   int S_all() const { return n_always + S_dyn; }
+  // One always-on group and nothing routed (the dense baseline): slot t is token t with weight 1, so the
+  // down contraction writes y itself.  A routed layer with one slot per token (top-1, no shared expert) does
+  // not qualify: its slots are permuted and carry a gate weight.
+  bool direct_output() const { return S_dyn == 0 && n_always == 1; }
 };
 
 size_t elem_size(int dtype);

@@ -322,7 +322,7 @@ static DecArgs make_dec_args(const Engine& e, const void* x, int64_t T, char* ws
   a.w1 = static_cast<const bf16_t*>(e.w1);
   a.w2 = static_cast<const bf16_t*>(e.w2);
   a.h = reinterpret_cast<bf16_t*>(ws + L.h);
-  a.y = (e.S_all() == 1) ? static_cast<bf16_t*>(y) : reinterpret_cast<bf16_t*>(ws + L.y_slots);
+  a.y = e.direct_output() ? static_cast<bf16_t*>(y) : reinterpret_cast<bf16_t*>(ws + L.y_slots);
   a.groups = e.groups;
   a.seg_off = reinterpret_cast<const int32_t*>(ws + L.seg_off);
   a.work = nullptr;

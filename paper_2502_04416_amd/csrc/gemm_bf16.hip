@@ -661,7 +661,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   // down
   a.A = reinterpret_cast<const bf16_t*>(ws + L.h);
   a.B = static_cast<const bf16_t*>(e.w2);
-  a.C = (e.S_all() == 1) ? static_cast<bf16_t*>(y) : reinterpret_cast<bf16_t*>(ws + L.y_slots);
+  a.C = e.direct_output() ? static_cast<bf16_t*>(y) : reinterpret_cast<bf16_t*>(ws + L.y_slots);
   a.work = reinterpret_cast<const int32_t*>(ws + L.work2);
   a.slot2tok = nullptr;
   {

@@ -149,7 +149,7 @@ static hipError_t run_simt(const Engine& e, const void* x, int64_t Tn, char* ws,
   }
   a.A = reinterpret_cast<const T*>(ws + L.h);
   a.B = static_cast<const T*>(e.w2);
-  a.C = (e.S_all() == 1) ? static_cast<T*>(y) : reinterpret_cast<T*>(ws + L.y_slots);
+  a.C = e.direct_output() ? static_cast<T*>(y) : reinterpret_cast<T*>(ws + L.y_slots);
   a.work = reinterpret_cast<const int32_t*>(ws + L.work2);
   a.slot2tok = nullptr;
   hipLaunchKernelGGL((grouped_gemm_simt<T, 2>), dim3((unsigned)gemm_work_bound(e, Tn, 2)), dim3(256), 0, s, a);

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_sl
 }
 
 hipError_t launch_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s) {
-  if (T == 0 || e.S_all() == 1) return hipSuccess;      // a single slot per token is written straight to y
+  if (T == 0 || e.direct_output()) return hipSuccess;   // the down contraction has written y itself
   if (decode_fuses_combine(e, T)) return hipSuccess;    // the decode down kernel has already summed the slots
   const int32_t* tok2slot = reinterpret_cast<const int32_t*>(ws + L.tok2slot);
   const float* slot_w = reinterpret_cast<const float*>(ws + L.slot_w);

@@ -120,6 +120,26 @@ def test_no_shared_expert(binding):
     layer.close()
 
 
+@pytest.mark.parametrize("base,T", [(0, 77), (1, 5), (1, 40), (1, 300)])
+def test_one_slot_per_token(binding, base, T):
+    """No shared expert and top-1 routing: every token has exactly one slot, but the slots are still a
+    permutation of the tokens and carry the gate weight of Eq. 9, so the output has to go through the
+    combine step (only the dense baseline may write y from the down contraction)."""
+    if base == 0:
+        cfg = synth.scaled(synth.CONFIGS[0], n_shared=0, top_k=1)
+    else:
+        cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_shared=0, top_k=1, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    u, b = synth.make_gate_params(cfg)
+    layer = _layer(binding, cfg, weights, part)
+    _say("top-1, N_s=0, %s T=%d" % (cfg.dtype, T), check_flat(cfg, weights, part, x, layer.forward(x)))
+    layer.set_gate_params(u, b)
+    _say("top-1, N_s=0, %s T=%d gate" % (cfg.dtype, T), check_flat(cfg, weights, part, x, layer.forward(x), u=u, b=b))
+    layer.close()
+
+
 def test_empty_batch_and_errors(binding, cfg0):
     import torch
     cfg, weights, src, part = cfg0
@@ -256,6 +276,42 @@ def test_small_batches_without_decode_kernels(binding, T):
     out = layer.forward(x)
     _say("no-decode T=%d" % T, check_flat(cfg, weights, part, x, out))
     _say("no-decode T=%d dense" % T, check_dense(cfg, weights, x, layer.dense_forward(x)))
+    assert np.array_equal(out["y"], layer.forward(x)["y"])
+    layer.close()
+
+
+def _random_shapes(n, seed):
+    """Seeded layer shapes and batch sizes inside the documented limits: model widths with and without the
+    decode kernels (d / 256 in {2, 4} or not) and with a ragged last K tile (d = 200), expert counts up to 64,
+    expert widths that miss the 32-neuron padding, batch sizes on both sides of every kernel switch."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        d = int(rng.choice([200, 256, 320, 512, 768, 1024]))
+        N = int(rng.choice([4, 8, 12, 16, 24, 32, 64]))
+        m = int(rng.choice([24, 40, 64, 100, 172]))
+        N_s = int(rng.integers(0, min(N - 1, 4) + 1))
+        N_k = int(rng.integers(1, min(N - N_s, 8) + 1))
+        T = int(rng.choice([1, 3, 16, 17, 31, 33, 64, 65, 100, 257, 600]))
+        out.append((i, d, N, m, N_s, N_k, T, bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("i,d,N,m,N_s,N_k,T,gate", _random_shapes(16, 20250211))
+def test_random_bf16_shapes(binding, i, d, N, m, N_s, N_k, T, gate):
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=d, d_ff=N * m, n_experts=N, n_shared=N_s, top_k=N_k, n_centres=16)
+    weights = synth.make_weights(cfg, seed=900 + i)
+    part = synth.trivial_partition(cfg, seed=i)
+    x = synth.make_token_source(cfg).eval_batch(i, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    u = b = None
+    if gate:
+        u, b = synth.make_gate_params(cfg, seed=7000 + i)
+        layer.set_gate_params(u, b)
+    out = layer.forward(x)
+    _say("random %d: d=%d N=%d m=%d S%dA%d T=%d gate=%s" % (i, d, N, m, N_s, N_k, T, gate),
+         check_flat(cfg, weights, part, x, out, u=u, b=b))
+    check_dense(cfg, weights, x, layer.dense_forward(x))
     assert np.array_equal(out["y"], layer.forward(x)["y"])
     layer.close()
 
