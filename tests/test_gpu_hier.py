@@ -83,16 +83,47 @@ def test_hier_small(binding):
 
 @pytest.mark.parametrize("T", [1, 7, 20, 32, 33, 64, 65])
 def test_hier_decode_batches(binding, T):
-    """Small batches take the fused decode kernels (one launch scores, selects and permutes; the down
-    kernel also combines); 33 tokens is the first size back on the tiled path."""
+    """Small batches: the weight-streaming kernels up to 16 tokens, the one-tile routing front end up to 64,
+    the fused down + combine kernel up to 32; 65 tokens is the first size on the general path."""
     cfg = synth.scaled(synth.CONFIGS[4], d_model=512, d_ff=1408, n_experts=8, n_shared=2, top_k=2, n_outer=4,
                        outer_top_k=2, n_centres=16)
     hier, experts, w_router, offsets = _make(binding, cfg)
     x = synth.make_token_source(cfg).eval_batch(0, n=T)
-    for rep_i in range(2):                      # twice: the arrival counters must come back to zero
+    for rep_i in range(2):                      # twice: nothing may depend on what the last call left behind
         out = hier.forward(x)
         rep = _check(cfg, experts, w_router, offsets, x, out, hier.dense_forward(x), np.arange(T))
     print("\n[parity] hier decode T=%d: %s" % (T, rep), flush=True)
+    hier.close()
+
+
+def _random_hier_shapes(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        d = int(rng.choice([256, 512, 768]))
+        n_outer = int(rng.choice([2, 3, 4, 8]))
+        otk = int(rng.integers(1, min(n_outer, 3) + 1))
+        N = int(rng.choice([4, 8]))
+        N_s = int(rng.integers(0, 3))
+        N_k = int(rng.integers(1, min(N - N_s, 3) + 1))
+        m = int(rng.choice([64, 100, 176]))
+        T = int(rng.choice([1, 7, 33, 100, 300]))
+        out.append((i, d, n_outer, otk, N, N_s, N_k, m, T))
+    return out
+
+
+@pytest.mark.parametrize("i,d,n_outer,otk,N,N_s,N_k,m,T", _random_hier_shapes(10, 20250212))
+def test_hier_random_shapes(binding, i, d, n_outer, otk, N, N_s, N_k, m, T):
+    """Seeded hierarchy shapes inside the documented limits, including a single outer expert per token and
+    sub-layers without a shared expert."""
+    cfg = synth.scaled(synth.CONFIGS[4], d_model=d, d_ff=N * m, n_experts=N, n_shared=N_s, top_k=N_k, n_outer=n_outer,
+                       outer_top_k=otk, n_centres=8)
+    hier, experts, w_router, offsets = _make(binding, cfg)
+    x = synth.make_token_source(cfg).eval_batch(i, n=T)
+    out = hier.forward(x)
+    rep = _check(cfg, experts, w_router, offsets, x, out, hier.dense_forward(x), np.arange(T))
+    print("\n[parity] hier random %d: d=%d outer %d/%d sub S%dA%dE%d m=%d T=%d: %s" % (i, d, otk, n_outer, N_s, N_k, N, m, T, rep), flush=True)
+    assert np.array_equal(out["y"], hier.forward(x)["y"])
     hier.close()
 
 
