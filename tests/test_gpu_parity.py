@@ -316,6 +316,39 @@ def test_random_bf16_shapes(binding, i, d, N, m, N_s, N_k, T, gate):
     layer.close()
 
 
+def _random_fp32_shapes(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        d = int(rng.choice([64, 100, 256, 333]))
+        N = int(rng.choice([4, 8, 16]))
+        m = int(rng.choice([8, 24, 50]))
+        N_s = int(rng.integers(0, 3))
+        N_k = int(rng.integers(1, min(N - N_s, 4) + 1))
+        T = int(rng.choice([1, 5, 64, 65, 200]))
+        out.append((i, d, N, m, N_s, N_k, T, bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("i,d,N,m,N_s,N_k,T,gate", _random_fp32_shapes(8, 20250213))
+def test_random_fp32_shapes(binding, i, d, N, m, N_s, N_k, T, gate):
+    """The plain-FMA path on seeded shapes, including model widths that are not a multiple of any tile."""
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=d, d_ff=N * m, n_experts=N, n_shared=N_s, top_k=N_k, n_centres=8)
+    weights = synth.make_weights(cfg, seed=950 + i)
+    part = synth.trivial_partition(cfg, seed=i)
+    x = synth.make_token_source(cfg).eval_batch(i, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    u = b = None
+    if gate:
+        u, b = synth.make_gate_params(cfg, seed=7100 + i)
+        layer.set_gate_params(u, b)
+    out = layer.forward(x)
+    _say("random fp32 %d: d=%d N=%d m=%d S%dA%d T=%d gate=%s" % (i, d, N, m, N_s, N_k, T, gate),
+         check_flat(cfg, weights, part, x, out, u=u, b=b))
+    check_dense(cfg, weights, x, layer.dense_forward(x))
+    layer.close()
+
+
 def test_bias_update_loop_balances_the_load(binding):
     """Sec. 4.3: forward -> per-expert counts -> cmoe_update_bias, repeated on one batch.  The library's
     biases follow the oracle's step applied to the same counts, the most loaded expert's share falls,
