@@ -47,7 +47,80 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="the paper's expert configurations SxAyEz at 75 %% active and the sparsity ladder with 16 "
                          "experts, on the config's dense layer (speedup vs dense at two batch sizes)")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="the layer against its baseline over batch sizes from 1 token up (arbitrary partition; several "
+                         "device copies of the layer and token sets are cycled so that weights come from HBM)")
     return ap.parse_args()
+
+
+BATCH_SWEEP = [1, 4, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
+
+
+def bench_batches(args, cfg, np, torch, binding, synth):
+    """Forward time of the restructured layer and of its baseline (dense FFN, or the un-restructured MoE layer
+    for the hierarchical config) as a function of the batch size."""
+    dev = torch.device("cuda:0")
+    t_setup = time.time()
+    src = synth.make_token_source(cfg)
+    n_sets = 8 if cfg.n_outer else 4
+    if cfg.n_outer:
+        w_router, offsets = synth.make_outer_router(cfg)
+        subs = []
+        for e in range(cfg.n_outer):
+            wg, wu, wd = synth.make_outer_expert_weights(cfg, e)
+            part = synth.trivial_partition(cfg, seed=e)
+            subs.append(binding.Layer.from_partition(cfg, wg, wu, wd, part["neuron_order"], part["rep_neuron"], upload=False))
+        layers = [binding.Hierarchy(subs, cfg.outer_top_k, w_router, offsets)]       # 2.8 GB: beyond the Infinity Cache
+    else:
+        weights = synth.make_weights(cfg)
+        part = synth.trivial_partition(cfg)
+        layers = [binding.Layer.from_partition(cfg, *weights, part["neuron_order"], part["rep_neuron"]) for _ in range(n_sets)]
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    rows = []
+    for T in ([args.batch] if args.batch else BATCH_SWEEP):
+        xs = [torch.from_numpy(src.draw(100 + i, T)).to(dev, torch.bfloat16) for i in range(n_sets)]
+        y = torch.empty_like(xs[0])
+        st = {"i": 0}
+
+        def moe():
+            i = st["i"] % n_sets
+            st["i"] += 1
+            if cfg.n_outer:
+                layers[0].forward_device(xs[i], y)
+            else:
+                layers[i].forward_device(xs[i], y, None, None, None)
+
+        def base():
+            i = st["i"] % n_sets
+            st["i"] += 1
+            (layers[0] if cfg.n_outer else layers[i]).dense_forward_device(xs[i], y)
+
+        a = timed(moe, args.steps, args.warmup)
+        b = timed(base, args.steps, args.warmup)
+        layers[0].forward_timed(xs[0], y, False)
+        stage = layers[0].forward_timed(xs[0], y, False)
+        rows.append({"T": T, "ms_per_step": a, "baseline_ms_per_step": b, "speedup_vs_baseline": b / a,
+                     "tokens_per_s": T / (a * 1e-3),
+                     "stage_ms_with_event_overhead": dict(zip(("router", "permute", "gate_up", "down", "combine"), map(float, stage)))})
+    head = rows[-1]
+    print(json.dumps({
+        "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "batch sizes on cfg%d %s; headline fields are T=%d" % (cfg.cfg, cfg.name, head["T"]),
+                   "partition": "arbitrary", "baseline": "un-restructured MoE layer" if cfg.n_outer else "dense FFN"},
+        "batch_sweep": rows, "setup_s": time.time() - t_setup}))
 
 
 def bench_hier(args, cfg, np, torch, binding, synth):
@@ -189,6 +262,9 @@ def main():
         print("bench.py: no HIP device visible", file=sys.stderr)
         sys.exit(2)
     cfg = synth.CONFIGS[args.config]
+    if args.batch_sweep:
+        bench_batches(args, cfg, np, torch, binding, synth)
+        return
     if cfg.n_outer:
         bench_hier(args, cfg, np, torch, binding, synth)
         return
