@@ -171,7 +171,62 @@ void RoundedDense::from_fp32(int dtype_, int d_, int d_ff_, const float* w_gate,
   });
 }
 
+void init_packed_set(PackedSet& ps, int dtype, int d) {
+  ps.dtype = dtype;
+  ps.d = d;
+  ps.tiled = dtype == CMOE_BF16;
+  ps.ld = ps.tiled ? TILE_K * tiles_along_k(d) : w1_row_stride(d);
+}
+
+// Tiled variant of pack_group: same rows, same zero padding, 16 x 32 tiles.
+static void pack_group_tiled(PackedSet& ps, const RoundedDense& rd, const int32_t* neurons, int width) {
+  const size_t es = elem_size(ps.dtype);
+  const int d = ps.d;
+  const int wp = round_up(width, WPAD);
+  const int kt1 = ps.ld / TILE_K;                     // tiles along K of W1
+  const int kt2 = wp / TILE_K;                        // tiles along K (= neurons) of this group's W2
+  const int d16 = round_up(d, TILE_ROWS);
+  GroupDev gd;
+  gd.width_pad = wp;
+  gd.w1_row0 = (int32_t)ps.w1_rows;
+  gd.w2_off = ps.w2_elems;
+  ps.groups.push_back(gd);
+  ps.width.push_back(width);
+  const int64_t row0 = ps.w1_rows;                    // a multiple of 2 * IL, hence of the tile height
+  ps.w1.resize((size_t)(row0 + 2 * wp) * ps.ld * es, 0);
+  const size_t w2_base = ps.w2.size();
+  ps.w2.resize(w2_base + (size_t)d16 * wp * es, 0);
+  ps.w1_rows += 2 * wp;
+  ps.w2_elems += (int64_t)d16 * wp;
+  auto put_row = [&](int64_t row, const uint8_t* src) {
+    for (int k0 = 0; k0 < d; k0 += TILE_K) {
+      const int n = std::min(TILE_K, d - k0);
+      std::memcpy(ps.w1.data() + (size_t)tiled_offset(row, k0, kt1) * es, src + (size_t)k0 * es, (size_t)n * es);
+    }
+  };
+  parallel_for(wp / IL, [&](int64_t blk) {
+    for (int c = 0; c < IL; ++c) {
+      const int n = (int)blk * IL + c;
+      if (n >= width) continue;
+      put_row(row0 + blk * 2 * IL + c, rd.gate_row(neurons[n]));
+      put_row(row0 + blk * 2 * IL + IL + c, rd.up_row(neurons[n]));
+    }
+  });
+  parallel_for((d + 63) / 64, [&](int64_t cb) {
+    const int c0 = (int)cb * 64, c1 = std::min(d, c0 + 64);
+    for (int n = 0; n < width; ++n) {
+      const uint8_t* src = rd.down_row(neurons[n]);
+      for (int c = c0; c < c1; ++c)
+        std::memcpy(ps.w2.data() + w2_base + (size_t)tiled_offset(c, n, kt2) * es, src + (size_t)c * es, es);
+    }
+  });
+}
+
 void pack_group(PackedSet& ps, const RoundedDense& rd, const int32_t* neurons, int width) {
+  if (ps.tiled) {
+    pack_group_tiled(ps, rd, neurons, width);
+    return;
+  }
   const size_t es = elem_size(ps.dtype);
   const int d = ps.d;
   const int wp = round_up(width, WPAD);
@@ -280,6 +335,7 @@ static void fill_flat_engines(cmoe_layer* L) {
   e.dtype = c.dtype;
   e.d = c.d_model;
   e.ldw1 = L->moe.ld;
+  e.w_tiled = L->moe.tiled ? 1 : 0;
   e.G = (int)L->moe.groups.size();
   e.n_always = c.n_shared > 0 ? 1 : 0;
   e.S_dyn = c.top_k;
@@ -308,6 +364,7 @@ static void fill_flat_engines(cmoe_layer* L) {
   dn.dtype = c.dtype;
   dn.d = c.d_model;
   dn.ldw1 = L->dense.ld;
+  dn.w_tiled = L->dense.tiled ? 1 : 0;
   dn.G = 1;
   dn.n_always = 1;
   dn.S_dyn = 0;
@@ -368,15 +425,11 @@ static int build_common(const cmoe_config* cfg, const float* w_gate, const float
       }
     }
     // expert groups: one shared group of N_s*m neurons (if any), then the routed experts
-    L->moe.dtype = cfg->dtype;
-    L->moe.d = d;
-    L->moe.ld = w1_row_stride(d);
+    init_packed_set(L->moe, cfg->dtype, d);
     if (cfg->n_shared > 0) pack_group(L->moe, rd, L->neuron_order.data(), cfg->n_shared * m);
     for (int j = 0; j < n_r; ++j) pack_group(L->moe, rd, L->neuron_order.data() + (size_t)(cfg->n_shared + j) * m, m);
     // dense baseline: every neuron in its original order, one group, padded once
-    L->dense.dtype = cfg->dtype;
-    L->dense.d = d;
-    L->dense.ld = w1_row_stride(d);
+    init_packed_set(L->dense, cfg->dtype, d);
     std::vector<int32_t> ident(d_ff);
     for (int i = 0; i < d_ff; ++i) ident[i] = i;
     pack_group(L->dense, rd, ident.data(), d_ff);
@@ -721,6 +774,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     m.dtype = c.dtype;
     m.d = d;
     m.ldw1 = experts[0]->moe.ld;
+    m.w_tiled = experts[0]->moe.tiled ? 1 : 0;
     const int gpo = has_shared + n_r;
     m.G = n_outer * gpo;
     m.n_always = 0;
@@ -752,6 +806,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     dn.dtype = c.dtype;
     dn.d = d;
     dn.ldw1 = experts[0]->dense.ld;
+    dn.w_tiled = experts[0]->dense.tiled ? 1 : 0;
     dn.G = n_outer;
     dn.n_always = 0;
     dn.S_dyn = outer_top_k;

@@ -26,11 +26,28 @@ __host__ __device__ static inline int round_up(int v, int m) { return (v + m - 1
 static inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 __host__ __device__ static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
+// ---- weight layout of the bf16 kernels ------------------------------------------------------------
+// W1 and W2 are stored in tiles of 16 rows x 32 K elements (1 KB of consecutive memory), the tiles of a
+// 16-row block one after the other along K.  A tile is exactly one A operand of v_mfma_f32_16x16x32_bf16, so
+// a load instruction of the weight-streaming decode kernels covers 1 KB of consecutive bytes and a wave's
+// K slice is one contiguous run; with row-major rows the same instruction would touch half of 16 different
+// 128-byte lines (measured on a load-only skeleton: 3.6 against 5.2 TB/s).  The prefill kernels' 1 KB DMA
+// transfers (8 rows x 64 K) are two 512-byte pieces of neighbouring tiles.  K is padded to a multiple of 32
+// with zeros, rows to a multiple of 16.  fp32 layers keep row-major weights.
+constexpr int TILE_ROWS = 16;
+constexpr int TILE_K = 32;
+constexpr int TILE_ELEMS = TILE_ROWS * TILE_K;
+__host__ __device__ static inline int tiles_along_k(int K) { return (K + TILE_K - 1) / TILE_K; }
+// Element offset of (row, k) in a tiled matrix whose rows are kt32 tiles long.
+__host__ __device__ static inline int64_t tiled_offset(int64_t row, int k, int kt32) {
+  return ((row / TILE_ROWS) * kt32 + k / TILE_K) * TILE_ELEMS + (row % TILE_ROWS) * TILE_K + (k % TILE_K);
+}
+
 // One expert group as the device kernels see it.
 struct GroupDev {
   int32_t width_pad;    // neurons incl. zero padding (multiple of WPAD)
   int32_t w1_row0;      // first packed (interleaved gate/up) row of the group in W1
-  int64_t w2_off;       // element offset of the group's down matrix [d][width_pad] in W2
+  int64_t w2_off;       // element offset of the group's down matrix [d][width_pad] in W2 (tiled: d padded to 16 rows)
 };
 
 // What the router kernel scores and selects.  Rows of the router matrix Wr [n_sw_rows + n_lin_rows][d]:
@@ -81,7 +98,8 @@ struct Engine {
   int S_dyn = 0;             // routed slots per token
   int64_t h_per_token = 0;   // upper bound of hidden elements per token (sum of its groups' width_pad)
   int max_width_pad = 0;
-  int ldw1 = 0;              // row stride (elements) of W1: d plus a pad that breaks the power-of-two stride
+  int ldw1 = 0;              // elements per row of W1 (row-major: the row stride; tiled: 32 * tiles along K)
+  int w_tiled = 0;           // 1: W1 and W2 are tiled 16 x 32 (bf16 layers)
   int width_pad_host[MAX_GROUPS] = {0};   // host copy of the groups' padded widths
   RouterDev r{};
   // device pointers (inside the caller's weight buffer)

@@ -31,7 +31,8 @@ struct DecArgs {
   const int64_t* h_off;
   const int32_t* slot2tok;
   int G, d;
-  int ldw;                  // row stride of w1
+  int ldw;                  // elements per row of w1
+  int tiled;                // 1: w1 and w2 are tiled 16 x 32: the weights of one operand are 1 KB of consecutive memory
   int64_t T;
   int single;
 };
@@ -83,8 +84,10 @@ __global__ __launch_bounds__(512) void decode_gate_up_kernel(DecArgs p) {
   // weight rows of this lane: packed row = (n / IL) * 2 * IL + n % IL (+ IL for the up row)
   const int n = neuron0 + r16;
   const int64_t grow = (int64_t)p.groups[g].w1_row0 + (n / IL) * 2 * IL + (n % IL);
-  const bf16_t* wg = p.w1 + grow * p.ldw + kbase;
-  const bf16_t* wu = wg + (int64_t)IL * p.ldw;
+  // (grow is a multiple of 16 plus lane%16, kbase a multiple of 32 plus (lane/16)*8: one tile per K step)
+  const bf16_t* wg = p.w1 + (p.tiled ? tiled_offset(grow, kbase, p.ldw / TILE_K) : grow * p.ldw + kbase);
+  const bf16_t* wu = wg + (p.tiled ? (int64_t)(IL / TILE_ROWS) * (p.ldw / TILE_K) * TILE_ELEMS : (int64_t)IL * p.ldw);
+  const int kadv = p.tiled ? TILE_ELEMS : 32;                 // elements from one K step's operand to the next
   // tokens (B operand), kept for the whole unit
   bf16x8_t bx[NTT][KSTEPS];
 #pragma unroll
@@ -104,8 +107,8 @@ __global__ __launch_bounds__(512) void decode_gate_up_kernel(DecArgs p) {
     for (int i = 0; i < 4; ++i) { accg[tt][i] = 0.0f; accu[tt][i] = 0.0f; }
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks) {
-    const bf16x8_t ag = ld_frag(wg + ks * 32);
-    const bf16x8_t au = ld_frag(wu + ks * 32);
+    const bf16x8_t ag = ld_frag(wg + ks * kadv);
+    const bf16x8_t au = ld_frag(wu + ks * kadv);
 #pragma unroll
     for (int tt = 0; tt < NTT; ++tt) {
       accg[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, bx[tt][ks], accg[tt], 0, 0, 0);
@@ -143,7 +146,9 @@ __global__ __launch_bounds__(256) void decode_down_kernel(DecArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, kq = lane >> 4;
   const int c0 = local * 16;
-  const bf16_t* wrow = p.w2 + p.groups[g].w2_off + (int64_t)(c0 + r16) * wp + kq * 8;
+  const bf16_t* wrow = p.w2 + p.groups[g].w2_off +
+                       (p.tiled ? tiled_offset(c0 + r16, kq * 8, wp / TILE_K) : (int64_t)(c0 + r16) * wp + kq * 8);
+  const int kadv = p.tiled ? TILE_ELEMS : 32;                 // elements from one K step's operand to the next
   const bf16_t* hrow[NTT];
   bool hok[NTT];
 #pragma unroll
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(256) void decode_down_kernel(DecArgs p) {
     bf16x8_t a[4], b[NTT][4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      a[u] = ld_frag(wrow + (ks + 4 * u) * 32);
+      a[u] = ld_frag(wrow + (ks + 4 * u) * kadv);
 #pragma unroll
       for (int tt = 0; tt < NTT; ++tt) b[tt][u] = hok[tt] ? ld_frag(hrow[tt] + (ks + 4 * u) * 32) : zero_frag();
     }
@@ -174,7 +179,7 @@ __global__ __launch_bounds__(256) void decode_down_kernel(DecArgs p) {
       for (int tt = 0; tt < NTT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[tt][u], acc[tt], 0, 0, 0);
   }
   for (; ks < n_steps; ks += 4) {
-    const bf16x8_t a = ld_frag(wrow + ks * 32);
+    const bf16x8_t a = ld_frag(wrow + ks * kadv);
 #pragma unroll
     for (int tt = 0; tt < NTT; ++tt) {
       const bf16x8_t b = hok[tt] ? ld_frag(hrow[tt] + ks * 32) : zero_frag();
@@ -234,13 +239,16 @@ __global__ __launch_bounds__(DC_WAVES * 64) void decode_down_combine_kernel(DecA
     const int seg0 = p.seg_off[g], cnt = p.seg_off[g + 1] - seg0;
     const int wp = p.groups[g].width_pad;
     const int ns = min(DC_CH, wp / 32 - ks0);
-    const bf16_t* wrow = p.w2 + p.groups[g].w2_off + (int64_t)(c0 + r16) * wp + kq * 8 + ks0 * 32;
+    const int kadv = p.tiled ? TILE_ELEMS : 32;
+    const bf16_t* wrow = p.w2 + p.groups[g].w2_off +
+                         (p.tiled ? tiled_offset(c0 + r16, ks0 * 32 + kq * 8, wp / TILE_K)
+                                  : (int64_t)(c0 + r16) * wp + kq * 8 + ks0 * 32);
     const bf16_t* hbase = p.h + p.h_off[g] + kq * 8 + ks0 * 32;
     bf16x8_t a[DC_CH], b[NTT][DC_CH];
     int tok[NTT];
     float wt[NTT];
 #pragma unroll
-    for (int s = 0; s < DC_CH; ++s) a[s] = s < ns ? ld_frag(wrow + s * 32) : zero_frag();
+    for (int s = 0; s < DC_CH; ++s) a[s] = s < ns ? ld_frag(wrow + s * kadv) : zero_frag();
 #pragma unroll
     for (int tt = 0; tt < NTT; ++tt) {
       const int col = tt * 16 + r16;
@@ -330,6 +338,7 @@ static DecArgs make_dec_args(const Engine& e, const void* x, int64_t T, char* ws
   a.G = e.G;
   a.d = e.d;
   a.ldw = e.ldw1;
+  a.tiled = e.w_tiled;
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);

@@ -27,7 +27,8 @@ struct GemmArgs {
   const int32_t* slot2tok;   // MODE 1 gather; null = identity
   int G;
   int d;
-  int ldb;                   // row stride of B in MODE 1 (packed gate/up rows)
+  int ldb;                   // elements per row of B in MODE 1 (packed gate/up rows)
+  int b_tiled;               // 1: the weight matrices are tiled 16 x 32 (see cmoe_internal.h)
   int64_t T;
   int single;                // 1: one always-on group holding all T tokens; no device schedule is read
   int n_blocks;              // grid size (multiple of 8) before the K split
@@ -194,10 +195,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     int n = nt * BN + row;
     const bool past = n >= n_cols;
     if (past) n = n_cols - 1;
-    if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + b_coff[i] + k_first;
-    else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + b_coff[i] + k_first;
-    if (past && use_zero_row) b_src[i] = g_zero_row + b_coff[i] + k_first;
+    if (p.b_tiled) {
+      // the lane's chunk of K tile kt lies 64 / 32 = 2 tiles (BKT / TILE_K) further for every kt
+      const int64_t rowg = (MODE == 1) ? (int64_t)p.groups[g].w1_row0 + n : n;
+      const int64_t base = (MODE == 1) ? 0 : p.groups[g].w2_off;
+      const int kt32 = (MODE == 1) ? p.ldb / TILE_K : wp / TILE_K;
+      b_src[i] = p.B + base + tiled_offset(rowg, k_first + b_coff[i], kt32);
+    } else {
+      if (MODE == 1) b_src[i] = p.B + ((int64_t)p.groups[g].w1_row0 + n) * p.ldb + b_coff[i] + k_first;
+      else b_src[i] = p.B + p.groups[g].w2_off + (int64_t)n * wp + b_coff[i] + k_first;
+      if (past && use_zero_row) b_src[i] = g_zero_row + b_coff[i] + k_first;
+    }
   }
+  const int b_adv = p.b_tiled ? (BKT / TILE_K) * TILE_ELEMS : BKT;     // elements between a lane's chunks of two K tiles
   const int KT = (K + BKT - 1) / BKT;
   const bool k_ragged = (K % BKT) != 0;
   auto a_slot = [&](int kt) -> bf16_t* { return HR ? smem + ((2 * kt) % 5) * HALF : smem + (kt % (HR ? 1 : STAGES)) * STAGE_ELEMS; };
@@ -213,7 +223,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs 
     dma16(src, a_slot(kt) + (wave + i * NW) * RPI * BKT);
   };
   auto issue_b = [&](int kt, int i, bool maybe_last) {
-    const void* src = b_src[i] + kt * BKT;
+    const void* src = b_src[i] + kt * b_adv;
     if (maybe_last && k_ragged && kt == KT - 1 && kt * BKT + b_coff[i] >= K) src = g_zero_chunk;
     dma16(src, b_slot(kt) + (wave + i * NW) * RPI * BKT);
   };
@@ -634,6 +644,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.G = e.G;
   a.d = e.d;
   a.ldb = e.ldw1;
+  a.b_tiled = e.w_tiled;
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.xcd_remap = remap;

@@ -21,6 +21,7 @@ struct SimtArgs {
   int G;
   int d;
   int ldb;
+  int b_tiled;               // 1: B is tiled 16 x 32 (bf16 layers run here only when forced to)
   int64_t T_tokens;
   int single;
 };
@@ -71,6 +72,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_simt(SimtArgs<T> p) {
   if (bn >= n_cols) bn = n_cols - 1;
   const T* b_src = (MODE == 1) ? p.B + ((int64_t)p.groups[g].w1_row0 + bn) * p.ldb
                                : p.B + p.groups[g].w2_off + (int64_t)bn * wp;
+  // tiled weights: element (row, k) through the layout function instead of b_src + k
+  const int64_t b_rowg = (MODE == 1) ? (int64_t)p.groups[g].w1_row0 + bn : bn;
+  const T* b_base = (MODE == 1) ? p.B : p.B + p.groups[g].w2_off;
+  const int b_kt32 = (MODE == 1) ? p.ldb / TILE_K : wp / TILE_K;
   // columns owned by this thread inside the 64-wide tile
   int cols[4];
   if (MODE == 1) { cols[0] = 2 * tx; cols[1] = 2 * tx + 1; cols[2] = IL + 2 * tx; cols[3] = IL + 2 * tx + 1; }
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_simt(SimtArgs<T> p) {
     for (int j = 0; j < 4; ++j) {
       const int k = k0 + lk + j;
       As[lk + j][lrow] = (k < K) ? Elem<T>::ld(a_src + k) : 0.0f;
-      Bs[lk + j][lrow] = (k < K) ? Elem<T>::ld(b_src + k) : 0.0f;
+      Bs[lk + j][lrow] = (k < K) ? Elem<T>::ld(p.b_tiled ? b_base + tiled_offset(b_rowg, k, b_kt32) : b_src + k) : 0.0f;
     }
     __syncthreads();
 #pragma unroll
@@ -135,6 +140,7 @@ static hipError_t run_simt(const Engine& e, const void* x, int64_t Tn, char* ws,
   a.G = e.G;
   a.d = e.d;
   a.ldb = e.ldw1;
+  a.b_tiled = e.w_tiled;
   a.T_tokens = Tn;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.A = static_cast<const T*>(x);

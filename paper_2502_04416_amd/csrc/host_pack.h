@@ -32,11 +32,12 @@ void parallel_for(int64_t n, const std::function<void(int64_t)>& fn, int max_thr
 struct PackedSet {
   int dtype = 1;
   int d = 0;
-  int ld = 0;                       // row stride of w1 in elements (w1_row_stride(d))
+  int ld = 0;                       // elements per row of w1 (row-major: w1_row_stride(d); tiled: 32 * tiles along K)
+  bool tiled = false;               // 16 x 32 tiles (bf16) instead of row-major rows (fp32)
   std::vector<GroupDev> groups;     // offsets relative to this set's own W1 / W2
   std::vector<int> width;           // real neuron count per group
-  std::vector<uint8_t> w1;          // [rows][ld] interleaved gate/up rows
-  std::vector<uint8_t> w2;          // per group [d][width_pad]
+  std::vector<uint8_t> w1;          // [rows][ld] interleaved gate/up rows (tiled: tiles of all 16-row blocks)
+  std::vector<uint8_t> w2;          // per group [d][width_pad] (tiled: d padded to a multiple of 16 rows)
   int64_t w1_rows = 0;
   int64_t w2_elems = 0;
 };
@@ -54,6 +55,8 @@ struct RoundedDense {
 
 // Append one group (the listed dense neuron ids, padded with zero neurons to a multiple of WPAD).
 void pack_group(PackedSet& ps, const RoundedDense& rd, const int32_t* neurons, int width);
+// Layout of a set for the layer's dtype and width (call before the first pack_group).
+void init_packed_set(PackedSet& ps, int dtype, int d);
 
 // Router rows for `n` representative neurons in SwiGLU blocks of 2*IL rows; appended to `out`
 // ([rows][d] in the layer dtype); scored expert index = first_index + j decides the block and row.
