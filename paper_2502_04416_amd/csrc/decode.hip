@@ -88,6 +88,13 @@ __global__ __launch_bounds__(512) void decode_gate_up_kernel(DecArgs p) {
   const bf16_t* wg = p.w1 + (p.tiled ? tiled_offset(grow, kbase, p.ldw / TILE_K) : grow * p.ldw + kbase);
   const bf16_t* wu = wg + (p.tiled ? (int64_t)(IL / TILE_ROWS) * (p.ldw / TILE_K) * TILE_ELEMS : (int64_t)IL * p.ldw);
   const int kadv = p.tiled ? TILE_ELEMS : 32;                 // elements from one K step's operand to the next
+  // The gate rows of the unit are requested before anything else (the stream from HBM is what the kernel
+  // waits for; left to itself the compiler keeps half a dozen weight loads in flight per wave), the up rows
+  // as the loop goes.  Requesting those up front as well costs a third workgroup per CU and gains nothing.
+  bf16x8_t ag[KSTEPS];
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) ag[ks] = ld_frag(wg + ks * kadv);
+  __builtin_amdgcn_sched_barrier(0);
   // tokens (B operand), kept for the whole unit
   bf16x8_t bx[NTT][KSTEPS];
 #pragma unroll
@@ -107,11 +114,10 @@ __global__ __launch_bounds__(512) void decode_gate_up_kernel(DecArgs p) {
     for (int i = 0; i < 4; ++i) { accg[tt][i] = 0.0f; accu[tt][i] = 0.0f; }
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks) {
-    const bf16x8_t ag = ld_frag(wg + ks * kadv);
     const bf16x8_t au = ld_frag(wu + ks * kadv);
 #pragma unroll
     for (int tt = 0; tt < NTT; ++tt) {
-      accg[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, bx[tt][ks], accg[tt], 0, 0, 0);
+      accg[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag[ks], bx[tt][ks], accg[tt], 0, 0, 0);
       accu[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(au, bx[tt][ks], accu[tt], 0, 0, 0);
     }
   }
