@@ -118,8 +118,8 @@ struct Engine {
 };
 
 size_t elem_size(int dtype);
-// Row stride of the packed gate/up matrix for model width d.  Rows that are a power of two apart all map
-// to the same L2 channel; the pad spreads the rows of a tile over the channels.
+// Row stride of a row-major (fp32) packed gate/up matrix for model width d: d plus the optional pad of the
+// CMOE_LDPAD tuning variable (rows a power of two apart all map to the same L2 channel).
 int w1_row_stride(int d);
 
 // Record the calling thread's error message (what cmoe_last_error returns) and hand `code` back.
