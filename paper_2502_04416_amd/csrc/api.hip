@@ -638,7 +638,7 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   if (T == 0) return CMOE_OK;
   if (!x || !y || !ws) return fail(CMOE_EINVAL, "x, y or workspace is null");
   if (T * (int64_t)e.S_all() > (int64_t)0x7fffffff / 2) return fail(CMOE_EINVAL, "batch too large for 32-bit slot indices");
-  const WsLayout L = ws_layout(e, T);
+  WsLayout L = ws_layout(e, T);
   if (ws_bytes < L.total) return fail(CMOE_EINVAL, "workspace too small: %zu bytes given, %zu needed", ws_bytes, L.total);
   if (((uintptr_t)ws & 255) != 0) return fail(CMOE_EINVAL, "workspace must be 256-byte aligned");
   char* w = static_cast<char*>(ws);
@@ -647,6 +647,7 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   auto mark = [&](int i) { if (ev) (void)hipEventRecord(ev[i], s); };
   // decode batches: scoring is one kernel, selection + permutation a second one
   const bool front = !single && !use_simt_experts(e.dtype) && decode_front_ok(e, T);
+  L.skip_always = (front && decode_front_runs_shared(e, T)) ? 1 : 0;
   mark(0);
   if (!single) {
     err = front ? launch_decode_front(e, x, T, w, L, topk, outer, scores, counts, s)

@@ -87,6 +87,8 @@ struct WsLayout {
   size_t total;
   int64_t n_slots;
   int n_tok_tiles;
+  int skip_always;                   // 1: the gate/up work list leaves out the always-on group (the routing front end
+                                     // runs its units itself, next to selection and placement)
 };
 
 // A grouped SwiGLU problem on the device: router (optional) -> permute -> experts -> combine.
@@ -157,6 +159,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
 // Decode batches (bf16, T <= 16; the fused down + combine kernel up to 32): weight-streaming expert kernels,
 // see decode.hip.
 bool decode_path_ok(const Engine& e, int64_t T);
+bool decode_front_runs_shared(const Engine& e, int64_t T);   // the front end's second launch also runs group 0's gate/up
 bool decode_fuses_combine(const Engine& e, int64_t T);   // the down kernel also does the weighted sum over slots
 hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
 hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,

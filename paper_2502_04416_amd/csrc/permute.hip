@@ -47,6 +47,7 @@ PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& 
   p.bn2 = gemm_tile(e, T, 4);
   p.d = e.d;
   p.decode = (!use_simt_experts(e.dtype) && decode_path_ok(e, T)) ? 1 : 0;
+  p.skip_always = L.skip_always;
   return p;
 }
 

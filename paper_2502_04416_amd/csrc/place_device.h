@@ -27,6 +27,7 @@ struct PlaceArgs {
   int G, n_always, S_dyn, n_tiles;
   int bm1, bn1, bm2, bn2, d;   // tile sizes of the grouped GEMMs (bn1 in packed gate/up rows)
   int decode;                  // 1: the work lists count decode units (16 neurons / 16 output columns per unit)
+  int skip_always;             // 1: no gate/up work items for the always-on groups (another launch ran them)
 };
 
 // All 64 callers are one wave: the LDS operations of a wave are carried out in the order it issued them, so
@@ -141,6 +142,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
       a2 = cdiv(cnt, p.bm2) * cdiv(p.d, p.bn2);
     }
     if (g >= p.G) { a1 = 0; a2 = 0; }
+    if (p.skip_always && g < p.n_always) a1 = 0;
     const long long ah = (long long)cnt * wp;
     const int run_i = wave_incl_scan(cnt, lane), w1_i = wave_incl_scan(a1, lane), w2_i = wave_incl_scan(a2, lane);
     const long long h_i = wave_incl_scan(ah, lane);

@@ -4,7 +4,9 @@
 //   router_gemm_kernel  bf16 MFMA partial products over (32-token tile, K slice) workgroups, followed by
 //                       route_tile_kernel, which sums the slices in order, selects, and emits each
 //                       64-token tile's per-group histogram (prefill batches)
+#include <cstdlib>
 #include "cmoe_internal.h"
+#include "decode_device.h"
 #include "device_utils.h"
 #include "place_device.h"
 
@@ -519,13 +521,15 @@ __global__ __launch_bounds__(64) void decode_score_kernel(const bf16_t* __restri
 // the 256 threads add the K-slice partials of the pre-activations in slice order and route the tokens in
 // teams of four lanes, then wave 0 places the tile.  Histogram and routed entries are handed over in LDS (the
 // workspace copies of the entries are not written: nothing after this kernel reads them).
-__global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
-                                                          const float* __restrict__ partial, int n_slices, int T) {
-  extern __shared__ float pre[];                 // [T][n_rows + 1], then scores [T][MAX_SCORED + 1]
+// The body works with the first 256 threads of the workgroup; every thread of it must call (barriers).
+// `pre`: dynamic shared memory, [T][n_rows + 1] pre-activations, then scores [T][MAX_SCORED + 1].
+__device__ __forceinline__ void route_place_body(const RouterDev& r, RouteIO io, const PlaceArgs& pl,
+                                                 const float* __restrict__ partial, int n_slices, int T, float* pre) {
   __shared__ int32_t hist[MAX_GROUPS];
   __shared__ int32_t sel_g[TOK_TILE * MAX_DYN];
   __shared__ float sel_w[TOK_TILE * MAX_DYN];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool worker = tid < 256;
   const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int ld = n_rows + 1;
   float* sc = pre + T * ld;
@@ -533,20 +537,46 @@ __global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO i
   LaneWidths lw;
   if (wave == 0) lw = load_lane_widths(pl, lane);          // needed last, requested first
   GateRegs flat_gr;
-  if (r.outer_top_k == 0) flat_gr = load_gate_regs(r, io, 0, r.n_scored, tid % TEAM);
-  sum_partials(partial, n_slices, T, 0, T, n_rows, pre, ld, tid);
-  for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
+  if (worker) {
+    if (r.outer_top_k == 0) flat_gr = load_gate_regs(r, io, 0, r.n_scored, tid % TEAM);
+    sum_partials(partial, n_slices, T, 0, T, n_rows, pre, ld, tid);
+    for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
+  }
   __syncthreads();
-  score_tile(r, io, pre, ld, sc, LDS_SC, T, 0, tid, 256);
+  if (worker) score_tile(r, io, pre, ld, sc, LDS_SC, T, 0, tid, 256);
   __syncthreads();
   io.sel_group = sel_g;
   io.sel_weight = sel_w;
-  {
+  if (worker) {
     const int tok = tid / TEAM;                    // at most 64 tokens x 4 lanes
     if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM, flat_gr);
   }
   __syncthreads();
   if (wave == 0) place_tile(pl, 0, hist, lane, sel_g, sel_w, lw);
+}
+
+__global__ __launch_bounds__(256) void route_place_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
+                                                          const float* __restrict__ partial, int n_slices, int T) {
+  extern __shared__ float pre[];
+  route_place_body(r, io, pl, partial, n_slices, T, pre);
+}
+
+// The same launch with company: workgroup 0 selects and places, the others run the gate/up units of the
+// always-on (shared-expert) group, which need nothing from the router.  Selection and placement are one
+// workgroup's chain of dependent steps, 8 us long at one token; the shared expert's share of the gate/up
+// stream (half of the bytes at one token) is read meanwhile instead of afterwards, with no hand-off between
+// workgroups and no second stream.  The gate/up work list then leaves that group out.
+template <int KSTEPS>
+__global__ __launch_bounds__(512) void route_place_shared_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
+                                                                 const float* __restrict__ partial, int n_slices, int T,
+                                                                 DecArgs da) {
+  extern __shared__ float pre[];
+  __shared__ DecGateUpRed<1> red;
+  if (blockIdx.x == 0) {
+    route_place_body(r, io, pl, partial, n_slices, T, pre);
+    return;
+  }
+  decode_gate_up_unit<1, KSTEPS>(da, 0, (int)blockIdx.x - 1, 0, T, da.groups[0].width_pad, 0, red);
 }
 
 // Per-tile histogram of the routed entries (used when the scoring kernel did not produce one).
@@ -646,8 +676,27 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   }
   if (err != hipSuccess) return err;
   const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
+  if (L.skip_always) {
+    // (the caller set this from decode_front_runs_shared: one always-on group, decode kernels, T <= 16)
+    DecArgs da = make_dec_args(e, x, T, ws, L, nullptr);
+    da.slot2tok = nullptr;                        // group 0's slots are the tokens in order; the map is not written yet
+    da.work = nullptr;
+    const dim3 grid(1 + e.width_pad_host[0] / 16), block(512);
+    switch (e.d / 256) {
+      case 16: hipLaunchKernelGGL(route_place_shared_kernel<16>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da); break;
+      case 8: hipLaunchKernelGGL(route_place_shared_kernel<8>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da); break;
+      case 4: hipLaunchKernelGGL(route_place_shared_kernel<4>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da); break;
+      default: hipLaunchKernelGGL(route_place_shared_kernel<2>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da); break;
+    }
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(route_place_kernel, dim3(1), dim3(256), smem, s, e.r, io, pl, pre_g, n_slices, Ti);
   return hipGetLastError();
+}
+
+bool decode_front_runs_shared(const Engine& e, int64_t T) {
+  static const bool off = [] { const char* v = getenv("CMOE_FRONT_SHARED"); return v && v[0] == '0'; }();
+  return !off && T <= FRONT_SCORE_MAX_T && e.n_always == 1 && decode_front_ok(e, T) && decode_path_ok(e, T);
 }
 
 hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
