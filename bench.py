@@ -56,6 +56,15 @@ def parse():
 BATCH_SWEEP = [1, 4, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096]
 
 
+def shared_in_front(cfg, T):
+    """Does the library run the shared expert's gate/up units inside the selection/placement launch (so that
+    the gate/up launch streams the routed experts only)?  Mirrors the library's rule: bf16 flat layer with
+    shared experts, at most 16 tokens, a model width the decode kernels are built for."""
+    return (cfg.dtype == "bf16" and cfg.n_shared > 0 and not cfg.n_outer and 1 <= T <= 16
+            and cfg.d_model % 256 == 0 and cfg.d_model // 256 in (2, 4, 8, 16)
+            and os.environ.get("CMOE_FRONT_SHARED", "1")[:1] != "0")
+
+
 def bench_batches(args, cfg, np, torch, binding, synth):
     """Forward time of the restructured layer and of its baseline (dense FFN, or the un-restructured MoE layer
     for the hierarchical config) as a function of the batch size."""
@@ -370,7 +379,7 @@ def main():
                     "traffic": None}
     else:
         gu_ms = net(float(st_moe[2]))
-        b = es * 2.0 * d * m * (cfg.n_shared + union)
+        b = es * 2.0 * d * m * (union + (0 if shared_in_front(cfg, T) else cfg.n_shared))
         roofline = {"kernel": "decode_gate_up_kernel", "bound": "hbm", "achieved": b / (gu_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "traffic": None}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
@@ -458,12 +467,13 @@ def main():
             std_ /= 2 * len(copies)
             u_avg = touched / len(copies)
             bytes_moe = es * (3.0 * d * m * (cfg.n_shared + u_avg) + 2.0 * d * cfg.n_routed)
-            bytes_gu = es * 2.0 * d * m * (cfg.n_shared + u_avg)
+            # bytes the gate/up launch itself streams (the shared group's units may run in the launch before it)
+            bytes_gu = es * 2.0 * d * m * (u_avg + (0 if shared_in_front(cfg, Td) else cfg.n_shared))
             bytes_dense = es * 3.0 * d * cfg.d_ff
             dec.append({
                 "T": Td, "ms_per_step": ms_m, "tokens_per_s": Td / (ms_m * 1e-3), "dense_ms_per_step": ms_dn,
                 "speedup_vs_dense": ms_dn / ms_m, "experts_touched_avg": u_avg,
-                "weight_bytes_touched": bytes_moe,
+                "weight_bytes_touched": bytes_moe, "shared_group_in_front_launch": shared_in_front(cfg, Td),
                 "hbm_frac_whole_path": bytes_moe / (ms_m * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "dense_hbm_frac": bytes_dense / (ms_dn * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "stage_ms": dict(zip(binding.STAGES, [float(v) for v in st])),
