@@ -80,7 +80,20 @@ __global__ __launch_bounds__(256) void decode_down_kernel(DecArgs p) {
     for (int i = 0; i < 4; ++i) acc[tt][i] = 0.0f;
   const int n_steps = wp / 32;
   int ks = wave;
-  // four K steps of this wave at a time: their loads are independent and all in flight together
+  // eight K steps of this wave at a time: their loads are independent and all in flight together
+  for (; ks + 28 < n_steps; ks += 32) {
+    bf16x8_t a[8], b[NTT][8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      a[u] = ld_frag(wrow + (ks + 4 * u) * kadv);
+#pragma unroll
+      for (int tt = 0; tt < NTT; ++tt) b[tt][u] = hok[tt] ? ld_frag(hrow[tt] + (ks + 4 * u) * 32) : zero_frag();
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int tt = 0; tt < NTT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[tt][u], acc[tt], 0, 0, 0);
+  }
   for (; ks + 12 < n_steps; ks += 16) {
     bf16x8_t a[4], b[NTT][4];
 #pragma unroll
