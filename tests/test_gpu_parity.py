@@ -349,6 +349,44 @@ def test_random_fp32_shapes(binding, i, d, N, m, N_s, N_k, T, gate):
     layer.close()
 
 
+@pytest.mark.parametrize("T", [1, 16, 40, 300])
+def test_forward_is_capturable_in_a_graph(binding, T):
+    """A forward enqueues kernels only (no allocation, no synchronisation, no memset), so it can be recorded
+    into a HIP graph; every replay, with eager forwards and synchronisations in between, reproduces the
+    eager result bit for bit."""
+    import torch
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    layer = _layer(binding, cfg, weights, part)
+    src = synth.make_token_source(cfg)
+    x = torch.from_numpy(src.eval_batch(0, n=T)).to("cuda", torch.bfloat16)
+    x2 = torch.from_numpy(src.eval_batch(1, n=T)).to("cuda", torch.bfloat16)
+    y = torch.empty_like(x)
+    y2 = torch.empty_like(x)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture (first-launch set-up)
+        layer.forward_device(x, y, None, None, None)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    ref = y.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer.forward_device(x, y, None, None, None)
+    for _ in range(4):
+        y.zero_()
+        layer.forward_device(x2, y2, None, None, None)   # eager work on the same layer and workspace in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref)
+    out = layer.forward(x.float().cpu().numpy())
+    assert np.array_equal(out["y"], ref.float().cpu().numpy())
+    del graph
+    layer.close()
+
+
 def test_bias_update_loop_balances_the_load(binding):
     """Sec. 4.3: forward -> per-expert counts -> cmoe_update_bias, repeated on one batch.  The library's
     biases follow the oracle's step applied to the same counts, the most loaded expert's share falls,
