@@ -449,11 +449,16 @@ static int env_int(const char* name, int dflt) {
 // shape at every batch size from 33 to 8192 tokens or one within a few per cent of it.
 static int gate_up_cfg(const Engine& e, int64_t T) {
   struct Cand { int cfg, bm, bn, slots; double t; };
-  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}, {7, 64, 128, 1, 0.30}};
   const bool single = e.G == 1 && e.n_always == 1;
+  // (64x128: a second, nearly empty round of the grouped problem costs a whole round, 224-256 tokens on 16
+  // experts, while the single-group problem's second round is a third full and still the better choice)
+  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}, {7, 64, 128, 1, single ? 0.30 : 0.34}};
   int best = 0;
   double best_t = 1e30;
   for (const Cand& c : cands) {
+    // a 256-row tile for groups that average less than a quarter of it streams its weights at the pace of a
+    // full tile (measured at 224-256 tokens on 16 experts: 61 us against 52 us with 128x128)
+    if (!single && c.bm >= 256 && T * e.S_dyn * 4 < (int64_t)std::min<int64_t>(e.G - e.n_always, T * e.S_dyn) * c.bm) continue;
     int64_t tiles = 0;
     for (int g = 0; g < e.n_always; ++g) tiles += ((T + c.bm - 1) / c.bm) * cdiv(2 * e.width_pad_host[g], c.bn);
     if (!single && e.G > e.n_always) {
@@ -464,7 +469,9 @@ static int gate_up_cfg(const Engine& e, int64_t T) {
     }
     // the routed groups' partial tiles are an estimate: average over the estimate and 8 % more
     const int64_t slots = 256 * c.slots, hi = single ? tiles : tiles + (tiles * 2 + 24) / 25;
-    const double t = 0.5 * c.t * (double)((tiles + slots - 1) / slots + (hi + slots - 1) / slots);
+    double t = 0.5 * c.t * (double)((tiles + slots - 1) / slots + (hi + slots - 1) / slots);
+    // the skinny tile runs one workgroup per CU and its rounds are long: count the pessimistic estimate only
+    if (c.cfg == 7 && !single) t = c.t * (double)((hi + slots - 1) / slots);
     if (t < best_t) {
       best_t = t;
       best = c.cfg;
