@@ -450,9 +450,7 @@ static int env_int(const char* name, int dflt) {
 static int gate_up_cfg(const Engine& e, int64_t T) {
   struct Cand { int cfg, bm, bn, slots; double t; };
   const bool single = e.G == 1 && e.n_always == 1;
-  // (64x128: a second, nearly empty round of the grouped problem costs a whole round, 224-256 tokens on 16
-  // experts, while the single-group problem's second round is a third full and still the better choice)
-  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}, {7, 64, 128, 1, single ? 0.30 : 0.34}};
+  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}, {7, 64, 128, 1, 0.30}};
   int best = 0;
   double best_t = 1e30;
   for (const Cand& c : cands) {
@@ -470,8 +468,9 @@ static int gate_up_cfg(const Engine& e, int64_t T) {
     // the routed groups' partial tiles are an estimate: average over the estimate and 8 % more
     const int64_t slots = 256 * c.slots, hi = single ? tiles : tiles + (tiles * 2 + 24) / 25;
     double t = 0.5 * c.t * (double)((tiles + slots - 1) / slots + (hi + slots - 1) / slots);
-    // the skinny tile runs one workgroup per CU and its rounds are long: count the pessimistic estimate only
-    if (c.cfg == 7 && !single) t = c.t * (double)((hi + slots - 1) / slots);
+    // the skinny tile runs one workgroup per CU and its rounds are long: when the estimate is within 8 % of
+    // spilling into a second, nearly empty round, count that round in full
+    if (c.cfg == 7 && !single && tiles <= slots && hi > slots) t = 2.3 * c.t;      // (above one round of 128x128)
     if (t < best_t) {
       best_t = t;
       best = c.cfg;
