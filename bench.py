@@ -422,6 +422,13 @@ def main():
         "streaming_read_reference_GBs": read_ref_gbs,
         "mfma_probe": mfma_probe,
     }
+    # what a kernel that only reads achieves on this device with 1 KB of consecutive bytes per load
+    # instruction (2 GiB, beyond the last-level cache): the practical ceiling of the decode streams
+    try:
+        out["hbm_probe_GBs"] = binding.cmoe_probe_hbm(2 << 30, 5)
+    except binding.CmoeError as e:
+        print("bench.py: cmoe_probe_hbm failed (%s)" % e, file=sys.stderr)
+        out["hbm_probe_GBs"] = None
 
     # ---- decode batches: cycle over several device copies of the layer so weights come from HBM ----
     if not args.no_decode and cfg.dtype == "bf16":
@@ -486,6 +493,10 @@ def main():
                                    "achieved": es * 2.0 * d * cfg.d_ff / (net(std_[2]) * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                                    "unit": "GB/s", "frac": es * 2.0 * d * cfg.d_ff / (net(std_[2]) * 1e-3) / 1e9 / HBM_PEAK_GBS},
             })
+        if out.get("hbm_probe_GBs"):
+            for e in dec:
+                e["roofline"]["frac_of_streaming_read"] = e["roofline"]["achieved"] / out["hbm_probe_GBs"]
+                e["dense_roofline"]["frac_of_streaming_read"] = e["dense_roofline"]["achieved"] / out["hbm_probe_GBs"]
         out["decode"] = dec
         out["decode_layer_copies"] = len(copies)
 

@@ -210,6 +210,15 @@ void cmoe_hier_destroy(cmoe_hier* h);
  * memory, runs on the null stream and synchronises; not part of the forward path. */
 int cmoe_probe_mfma(int random_operands, int iters, double* tflops, double* shader_mhz);
 
+/* Measurement aid for the roofline of the weight-streaming decode kernels (the per-neuron form of the FFN,
+ * Eq. 1, on the selected experts of Eq. 4): the rate at which the current device reads `bytes` of device
+ * memory (rounded down to a multiple of 256 KB; choose more than the 256 MB last-level cache) when every
+ * load instruction covers 1 KB of consecutive bytes and nothing else is done with the data.  Best of
+ * `reps` launches after one warm-up, event-timed (the 4-5 us an event pair costs are inside), in GB/s to
+ * *gbytes_per_s (host).  Allocates, zero-fills and frees the buffer, runs on the null stream and
+ * synchronises; not part of the forward path. */
+int cmoe_probe_hbm(size_t bytes, int reps, double* gbytes_per_s);
+
 const char* cmoe_last_error(void);   /* thread-local, never NULL */
 const char* cmoe_version(void);
 

@@ -38,7 +38,7 @@ EXPORTS = [
     "cmoe_destroy", "cmoe_hier_create", "cmoe_hier_packed_bytes", "cmoe_hier_workspace_bytes",
     "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
-    "cmoe_balanced_assignment", "cmoe_probe_mfma", "cmoe_get_gate_params", "cmoe_update_bias",
+    "cmoe_balanced_assignment", "cmoe_probe_mfma", "cmoe_probe_hbm", "cmoe_get_gate_params", "cmoe_update_bias",
     "cmoe_build_gpu", "cmoe_profile_activations",
 ]
 
@@ -89,6 +89,7 @@ def load():
     lib.cmoe_hier_destroy.argtypes = [vp]
     lib.cmoe_hier_destroy.restype = None
     lib.cmoe_probe_mfma.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.cmoe_probe_hbm.argtypes = [C.c_size_t, C.c_int, C.POINTER(C.c_double)]
     lib.cmoe_last_error.restype = C.c_char_p
     lib.cmoe_version.restype = C.c_char_p
     _lib = lib
@@ -173,6 +174,13 @@ def cmoe_probe_mfma(random_operands: bool, iters: int):
     tf, mhz = C.c_double(), C.c_double()
     _check(load().cmoe_probe_mfma(int(random_operands), int(iters), C.byref(tf), C.byref(mhz)), "cmoe_probe_mfma")
     return tf.value, mhz.value
+
+
+def cmoe_probe_hbm(n_bytes: int, reps: int = 5) -> float:
+    """GB/s of a plain streaming read of n_bytes of device memory (measurement aid)."""
+    g = C.c_double()
+    _check(load().cmoe_probe_hbm(int(n_bytes), int(reps), C.byref(g)), "cmoe_probe_hbm")
+    return g.value
 
 
 def cmoe_export_partition(layer: int, d_ff: int, n_routed: int) -> Dict[str, np.ndarray]:

@@ -48,7 +48,57 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(const uint4* __restrict
   }
 }
 
+// Streaming read: every workgroup of eight waves reads its own 256 KB of consecutive memory, each load
+// instruction 1 KB of consecutive bytes, all 32 loads of a lane in flight: the access pattern the weight
+// layout gives the decode kernels, with nothing else to do.
+constexpr int HBM_PROBE_BLOCK_BYTES = 512 * 32 * 16;
+__global__ __launch_bounds__(512) void hbm_probe_kernel(const uint4* __restrict__ src, float* sink) {
+  const uint4* p = src + (size_t)blockIdx.x * (HBM_PROBE_BLOCK_BYTES / 16) + (threadIdx.x >> 6) * (32 * 64) + (threadIdx.x & 63);
+  uint32_t acc = 0;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const uint4 v = p[i * 64];
+    acc ^= v.x ^ v.w;
+  }
+  if (acc == 0x12345678u) sink[0] = 1.0f;        // never true for the zero-filled buffer; keeps the loads alive
+}
+
 }  // namespace cmoe
+
+extern "C" int cmoe_probe_hbm(size_t bytes, int reps, double* gbytes_per_s) {
+  using namespace cmoe;
+  if (!gbytes_per_s || reps < 1 || reps > 1000 || bytes < HBM_PROBE_BLOCK_BYTES || bytes > ((size_t)64 << 30))
+    return fail(CMOE_EINVAL, "cmoe_probe_hbm: need 256 KB <= bytes <= 64 GiB, 1 <= reps <= 1000, a result pointer");
+  const size_t n_blocks = bytes / HBM_PROBE_BLOCK_BYTES;
+  if (n_blocks > 0x7fffffffu) return fail(CMOE_EINVAL, "cmoe_probe_hbm: too many workgroups");
+  const size_t used = n_blocks * HBM_PROBE_BLOCK_BYTES;
+  char* buf = nullptr;
+  if (hipMalloc(&buf, used + 256) != hipSuccess) return fail(CMOE_ENOMEM, "cmoe_probe_hbm: device allocation failed");
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = CMOE_OK;
+  float best = 0.0f;
+  auto ok = [&](hipError_t e) { if (e != hipSuccess && rc == CMOE_OK) rc = fail(CMOE_EHIP, "cmoe_probe_hbm: %s", hipGetErrorString(e)); return e == hipSuccess; };
+  if (ok(hipMemset(buf, 0, used + 256)) && ok(hipEventCreate(&e0)) && ok(hipEventCreate(&e1))) {
+    const uint4* src = reinterpret_cast<const uint4*>(buf);
+    float* sink = reinterpret_cast<float*>(buf + used);
+    for (int rep = 0; rep <= reps && rc == CMOE_OK; ++rep) {     // the first launch is a warm-up
+      float ms = 0.0f;
+      ok(hipEventRecord(e0, nullptr));
+      hipLaunchKernelGGL(hbm_probe_kernel, dim3((unsigned)n_blocks), dim3(512), 0, nullptr, src, sink);
+      ok(hipGetLastError());
+      ok(hipEventRecord(e1, nullptr));
+      ok(hipEventSynchronize(e1));
+      ok(hipEventElapsedTime(&ms, e0, e1));
+      if (rep > 0 && (best == 0.0f || ms < best)) best = ms;
+    }
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(buf);
+  if (rc != CMOE_OK) return rc;
+  *gbytes_per_s = (double)used / (best * 1e-3) / 1e9;
+  return CMOE_OK;
+}
 
 extern "C" int cmoe_probe_mfma(int random_operands, int iters, double* tflops, double* shader_mhz) {
   using namespace cmoe;

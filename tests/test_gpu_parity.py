@@ -466,3 +466,15 @@ def test_mfma_probe_reports_a_plausible_rate(binding):
     assert 100.0 < tf1 <= tf0 * 1.05 < 2700.0
     with pytest.raises(binding.CmoeError):
         binding.cmoe_probe_mfma(True, 0)
+
+
+def test_hbm_probe_reports_a_plausible_rate(binding):
+    """The streaming-read probe reports a rate between what a single HBM stack delivers and the published
+    peak of the part, and rejects sizes it cannot run."""
+    g = binding.cmoe_probe_hbm(1 << 30, 3)
+    _say("hbm probe", {"GBs": g})
+    assert 1000.0 < g < 8000.0
+    with pytest.raises(binding.CmoeError):
+        binding.cmoe_probe_hbm(1024, 3)
+    with pytest.raises(binding.CmoeError):
+        binding.cmoe_probe_hbm(1 << 30, 0)
