@@ -76,8 +76,15 @@ __device__ __forceinline__ int lds_off_t(int row, int c) {
   return row * 32 + ((c ^ ((row >> 2) & 3)) << 3);
 }
 
+// Waves per SIMD the register allocation has to leave room for: two when two four-wave workgroups fit a CU's
+// 160 KB of LDS (the compiler otherwise spends up to 512 registers on a wave that is alone on its SIMD).
+constexpr int min_waves_per_simd(int bm, int bn, int bkt, int stages, int nw) {
+  return (stages >= 2 && nw == 4 && bm * bn >= 256 * 128 && stages * (bm + bn) * bkt * 2 <= 80 * 1024) ? 2 : 1;
+}
+
 template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE>
-__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_bf16_dma(GemmArgs p) {
+__global__ __launch_bounds__(WGM* WGN * 64)
+__attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* WGN)))) void grouped_gemm_bf16_dma(GemmArgs p) {
   constexpr int NW = WGM * WGN;
   constexpr int TM = BM / WGM, TN = BN / WGN, MI = TM / 32, NI = TN / 32;
   constexpr int CPR = BKT / 8;                                  // 16-byte chunks per tile row
@@ -428,6 +435,9 @@ static const TileCfg kCfgs[] = {
                                //    CU keeps 72 KB of loads in flight, two thirds of them weights (such a launch
                                //    is bound by HBM latency x bytes in flight, not by MFMA work).  Measured against
                                //    32x128 (2 waves; 3 and 7 stages), 32x256 and 64x128 with 3 and 6 stages.
+    {128, 256, 2, 2, 3, 32},   // 8: four waves of 64x128, three K tiles of 32: 72 KB of LDS and at most 256 registers,
+                               //    so two workgroups share a CU and one's epilogue overlaps the other's K loop
+                               //    (the short-K down contraction; 256x128 in the same arrangement was slower)
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -485,17 +495,39 @@ static int cfg_index(int which, const Engine& e, int64_t T) {
   int dflt = 0;
   if (which == 1) dflt = gate_up_cfg(e, T);
   if (which == 2) {
-    // the largest tile that still gives every CU one: 256x256, else 256x128, else 128x128 (measured on
-    // T = 2048..8192: a half-empty chip costs more than the smaller tile's lower arithmetic intensity)
-    const int64_t tiles_256 = ((T * e.S_all() + 255) / 256) * ((e.d + 255) / 256);
-    // 256x256: four waves when the contraction is deep (dense FFN: K = d_h), eight when it is an expert's
-    // width (a few K steps per tile: the eight-wave tile gets through prologue and epilogue faster)
-    const int big = e.max_width_pad >= 2048 ? 6 : 0;
-    dflt = tiles_256 >= 256 ? big : (2 * tiles_256 >= 256 ? 4 : 3);
-    // Many small groups: every touched group has at least one row tile, so the 128x128 list can exceed the
-    // 512 workgroups the chip holds at once while the 256x256 list still fits its 256 (16 experts at 160-256
-    // tokens: 544 against 256 tiles; measured 32-38 us against 29-32 us).
-    if (dflt == 3 && est_tiles(e, T, 2, 128, 128) > 512 && est_tiles(e, T, 2, 256, 256) <= 256) dflt = 0;
+    const bool single = e.G == 1 && e.n_always == 1;
+    int k_min = 1 << 30;
+    for (int g = 0; g < e.G; ++g) k_min = std::min(k_min, e.width_pad_host[g]);
+    if (!single && k_min < 2048) {
+      // Short K (an expert's width, up to a few tens of K steps per tile; a wider merged shared group next to
+      // such experts does not change the picture): rounds x time per round, rounds = ceil(tiles /
+      // workgroup slots on the chip).  Measured on 8 to 64 experts of 352 to 1792 neurons, 128 to 8192 tokens:
+      // a round of 256 tiles of 256x256 (eight waves, one workgroup per CU) and a round of 512 tiles of 128x256
+      // (two per CU) take the same time, a round of 512 tiles of 128x128 two thirds of it.  The 128-row tiles
+      // waste less of a ragged segment, and two workgroups on a CU overlap one's epilogue with the other's
+      // K loop; a single round of the two-per-CU shape costs 1.4 (both workgroups of a CU start together).
+      const int64_t n0 = est_tiles(e, T, 2, 256, 256), n9 = est_tiles(e, T, 2, 128, 256), n3 = est_tiles(e, T, 2, 128, 128);
+      const int64_t r0 = (n0 + 255) / 256, r9 = (n9 + 511) / 512, r3 = (n3 + 511) / 512;
+      const double t0 = (double)r0, t9 = (double)r9 + (r9 == 1 ? 0.4 : 0.0), t3 = 0.66 * (double)r3;
+      dflt = (t3 < t9 && t3 < t0) ? 3 : (t9 <= t0 ? 8 : 0);
+    } else {
+      // Deep K (dense FFN, un-restructured experts): 256x256 tiles with four waves when every CU gets one;
+      // below that 256x128, whose round takes 0.56 of the time, unless it would need a second round; 128x128
+      // (two workgroups per CU) for batches of a few hundred tokens.
+      const int64_t tiles_256 = ((T * e.S_all() + 255) / 256) * ((e.d + 255) / 256), tiles_4 = 2 * tiles_256;
+      const int big = e.max_width_pad >= 2048 ? 6 : 0;
+      const double t_big = (double)((tiles_256 + 255) / 256), t_4 = 0.56 * (double)((tiles_4 + 255) / 256);
+      dflt = (2 * tiles_256 < 256) ? 3 : (t_big <= t_4 ? big : 4);
+      if (dflt == 3 && est_tiles(e, T, 2, 128, 128) > 512 && tiles_256 <= 256) dflt = 0;
+      // Batches of hundreds of tokens split K (see bf16_splitk); there 128x256 tiles with two workgroups per
+      // CU stream the weights faster than 128x128 ones over part of the range (measured: dense FFN at 512 to
+      // 1024 tokens 69-114 us against 83-142 us; eight experts of 14336 neurons up to 256 tokens 145-166 us
+      // against 195-202 us; slower outside these ranges).
+      if (dflt == 3) {
+        const int64_t n8 = est_tiles(e, T, 2, 128, 256);
+        if (single ? (n8 > 48 && n8 <= 160) : n8 <= 128) dflt = 8;
+      }
+    }
   }
   int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", dflt);
   if (c < 0 || c >= kNumCfgs) c = dflt;
@@ -546,10 +578,10 @@ int bf16_splitk(const Engine& e, int64_t T, int which) {
   const int kt = cdiv(k_min, c.bk);
   const size_t per_part = (size_t)splitk_rows(e, T) * splitk_ldp(e, which) * sizeof(float);
   int ks = 1;
-  // Split only while the launch stays well inside one round of workgroups (two 128x128 tiles fit a CU, one of
+  // Split only while the launch stays well inside one round of workgroups (two tiles of 128 rows fit a CU, one of
   // the larger shapes): measured at 64..512 tokens, splitting a launch that already has a tile for most
   // CUs costs more (partial sums, a second launch) than the shorter K loop saves.
-  const int64_t slots = (c.bm == 128 && c.bn == 128) ? 2 : 1;
+  const int64_t slots = c.bm == 128 ? 2 : 1;
   while (ks < 8 && tiles * ks * 2 <= 192 * slots && kt / (ks * 2) >= 4 && per_part * ks * 2 <= SPLITK_MAX_BYTES) ks *= 2;
   return ks;
 }
@@ -642,6 +674,7 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
     case 4: return launch_dma<256, 128, 64, 3, 4, 2, MODE>(a, s);
     case 6: return launch_dma<256, 256, 64, 0, 2, 2, MODE>(a, s);
     case 7: return launch_dma<64, 128, 64, 4, 2, 2, MODE>(a, s);
+    case 8: return launch_dma<128, 256, 32, 3, 2, 2, MODE>(a, s);
     default: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
   }
 }
