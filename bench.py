@@ -332,6 +332,21 @@ def main():
     torch.cuda.synchronize()
     cnt = counts.cpu().numpy()
 
+    # ---- spread of single forwards: 100 of them, each between its own pair of events on the launch stream
+    # (the library enqueues on torch's current stream; a pair of events around nothing reads 4-5 us here, which
+    # these figures contain and the headline, timed by the host clock around all steps, does not) ----
+    def spread(fn, n=100):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for e0, e1 in ev:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        us = np.sort(np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in ev]))
+        return {"n": n, "median": float(us[n // 2]), "p10": float(us[n // 10]), "p90": float(us[(9 * n) // 10])}
+    forward_us = spread(lambda: layer.forward_device(x, y, topk, None, counts))
+    dense_forward_us = None if args.no_dense else spread(lambda: layer.dense_forward_device(x, y))
+
     # ---- per-stage times from HIP events recorded inside the library on the launch stream ----
     def stages(dense, n):
         acc = np.zeros(5)
@@ -412,6 +427,7 @@ def main():
         "speedup_vs_dense": ms_dense / ms_moe,
         "whole_path_tflops": flops_total / (ms_moe * 1e-3) / 1e12,
         "dense_tflops": flops_dense / (ms_dense * 1e-3) / 1e12,
+        "forward_us_by_events": forward_us, "dense_forward_us_by_events": dense_forward_us,
         "stage_ms": dict(zip(binding.STAGES, [float(v) for v in st_moe])),
         "dense_stage_ms": dict(zip(binding.STAGES, [float(v) for v in st_dense])),
         "expert_counts": cnt.tolist(), "experts_touched": union,
