@@ -280,6 +280,26 @@ def test_small_batches_without_decode_kernels(binding, T):
     layer.close()
 
 
+@pytest.mark.parametrize("which", ["CMOE_GEMM1_CFG", "CMOE_GEMM2_CFG"])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_tile_shape(binding, monkeypatch, which, shape):
+    """Each tile shape of the bf16 contraction kernels forced on the gate/up or the down contraction (the
+    library reads the tuning variables at every call) of a layer whose segments end inside tiles: d = 328 (a
+    ragged last K tile at either tile depth), experts of 100 neurons, 333 tokens."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=328, d_ff=1200, n_experts=12, n_shared=2, top_k=3, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=333)
+    layer = _layer(binding, cfg, weights, part)
+    ref = layer.forward(x)
+    monkeypatch.setenv(which, str(shape))
+    out = layer.forward(x)
+    _say("%s=%d" % (which, shape), check_flat(cfg, weights, part, x, out))
+    _say("%s=%d dense" % (which, shape), check_dense(cfg, weights, x, layer.dense_forward(x)))
+    assert np.array_equal(out["topk"], ref["topk"])
+    layer.close()
+
+
 def _random_shapes(n, seed):
     """Seeded layer shapes and batch sizes inside the documented limits: model widths with and without the
     decode kernels (d / 256 in {2, 4} or not) and with a ragged last K tile (d = 200), expert counts up to 64,
