@@ -438,6 +438,9 @@ static const TileCfg kCfgs[] = {
     {128, 256, 2, 2, 3, 32},   // 8: four waves of 64x128, three K tiles of 32: 72 KB of LDS and at most 256 registers,
                                //    so two workgroups share a CU and one's epilogue overlaps the other's K loop
                                //    (the short-K down contraction; 256x128 in the same arrangement was slower)
+    {224, 256, 1, 4, 0, 64},   // 9: four waves of 224x64 (all rows, a quarter of the columns each): 7/8 of the
+                               //    MFMA work of 6 per tile, for segments that fill 256-row tiles poorly
+    {192, 256, 1, 4, 0, 64},   // 10: four waves of 192x64
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
@@ -455,18 +458,23 @@ static int env_int(const char* name, int dflt) {
 // LLaMA-shaped layers (K = d for every shape, so the ratios carry over), in units of the eight-wave
 // 256x256 tile: 256x256 with four waves 0.95 (one workgroup per CU), 256x128 0.58 (one per CU), 128x128
 // 0.66 (two per CU), 64x128 0.30 (one per CU; it only wins while the launch is one or two rounds, i.e. up to
-// 128 tokens for the dense FFN and about 200 for the 16-expert layer).  The model picks the measured best
-// shape at every batch size from 33 to 8192 tokens or one within a few per cent of it.
+// 128 tokens for the dense FFN and about 200 for the 16-expert layer).  224x256 and 192x256 tiles (four waves
+// side by side, each over all rows of the tile: a quarter more LDS reads per MFMA than 128x128 per wave) take
+// 0.875 and 0.81: when ragged segments fill 256-row tiles poorly, a lower tile with the same number of rounds
+// does less padded work (16 experts at 4096 tokens: 820 rows are four tiles either way, 204 -> 187 us).
+// The model picks the measured best shape at every batch size from 33 to 8192 tokens or one within a few
+// per cent of it.
 static int gate_up_cfg(const Engine& e, int64_t T) {
   struct Cand { int cfg, bm, bn, slots; double t; };
   const bool single = e.G == 1 && e.n_always == 1;
-  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}, {7, 64, 128, 1, 0.30}};
+  const Cand cands[] = {{3, 128, 128, 2, 0.66}, {4, 256, 128, 1, 0.58}, {6, 256, 256, 1, 0.95}, {7, 64, 128, 1, 0.30},
+                        {9, 224, 256, 1, 0.875}, {10, 192, 256, 1, 0.81}};
   int best = 0;
   double best_t = 1e30;
   for (const Cand& c : cands) {
     // a 256-row tile for groups that average less than a quarter of it streams its weights at the pace of a
     // full tile (measured at 224-256 tokens on 16 experts: 61 us against 52 us with 128x128)
-    if (!single && c.bm >= 256 && T * e.S_dyn * 4 < (int64_t)std::min<int64_t>(e.G - e.n_always, T * e.S_dyn) * c.bm) continue;
+    if (!single && c.bm >= 192 && T * e.S_dyn * 4 < (int64_t)std::min<int64_t>(e.G - e.n_always, T * e.S_dyn) * c.bm) continue;
     int64_t tiles = 0;
     for (int g = 0; g < e.n_always; ++g) tiles += ((T + c.bm - 1) / c.bm) * cdiv(2 * e.width_pad_host[g], c.bn);
     if (!single && e.G > e.n_always) {
@@ -675,6 +683,8 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
     case 6: return launch_dma<256, 256, 64, 0, 2, 2, MODE>(a, s);
     case 7: return launch_dma<64, 128, 64, 4, 2, 2, MODE>(a, s);
     case 8: return launch_dma<128, 256, 32, 3, 2, 2, MODE>(a, s);
+    case 9: return launch_dma<224, 256, 64, 0, 1, 4, MODE>(a, s);
+    case 10: return launch_dma<192, 256, 64, 0, 1, 4, MODE>(a, s);
     default: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
   }
 }

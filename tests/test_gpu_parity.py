@@ -281,7 +281,7 @@ def test_small_batches_without_decode_kernels(binding, T):
 
 
 @pytest.mark.parametrize("which", ["CMOE_GEMM1_CFG", "CMOE_GEMM2_CFG"])
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_every_tile_shape(binding, monkeypatch, which, shape):
     """Each tile shape of the bf16 contraction kernels forced on the gate/up or the down contraction (the
     library reads the tuning variables at every call) of a layer whose segments end inside tiles: d = 328 (a
