@@ -27,6 +27,32 @@ FP32_VALU_PEAK_TF = 157.3
 MEASURED_GATE_UP_TRAFFIC_BYTES = 310.6e6
 
 
+RAMP_MS = 40.0
+
+
+def timed(fn, steps, warmup):
+    """Milliseconds per call of `fn` over exactly `steps` calls bracketed by synchronize, after `warmup` untimed
+    calls.  Before the warm-up the same call runs for RAMP_MS of wall time: a device that has been idle (a
+    fresh process, host-side construction, a CPU timing leg) starts at a low clock and takes tens of
+    milliseconds of load to reach the clock it then holds; ten warm-up steps of 0.25 ms are over before that
+    (measured on config 1, T = 2048: 0.250 ms per step after 10 warm-up steps, 0.219-0.223 ms after 100 or more,
+    and 0.220 ms by per-forward events either way)."""
+    import torch
+    t_ramp = time.perf_counter()
+    while (time.perf_counter() - t_ramp) * 1e3 < RAMP_MS:
+        for _ in range(8):
+            fn()
+        torch.cuda.synchronize()
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,16 +111,6 @@ def bench_batches(args, cfg, np, torch, binding, synth):
         part = synth.trivial_partition(cfg)
         layers = [binding.Layer.from_partition(cfg, *weights, part["neuron_order"], part["rep_neuron"]) for _ in range(n_sets)]
 
-    def timed(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
-
     rows = []
     for T in ([args.batch] if args.batch else BATCH_SWEEP):
         xs = [torch.from_numpy(src.draw(100 + i, T)).to(dev, torch.bfloat16) for i in range(n_sets)]
@@ -124,7 +140,7 @@ def bench_batches(args, cfg, np, torch, binding, synth):
     head = rows[-1]
     print(json.dumps({
         "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
-        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "batch sizes on cfg%d %s; headline fields are T=%d" % (cfg.cfg, cfg.name, head["T"]),
@@ -147,16 +163,6 @@ def bench_hier(args, cfg, np, torch, binding, synth):
     T = args.batch if args.batch else max(cfg.eval_batches)
     x = torch.from_numpy(synth.make_token_source(cfg).eval_batch(0, n=T)).to(dev, torch.bfloat16)
     y = torch.empty_like(x)
-
-    def timed(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
 
     ms_moe = timed(lambda: hier.forward_device(x, y), args.steps, args.warmup)
     ms_dense = timed(lambda: hier.dense_forward_device(x, y), args.steps, args.warmup)
@@ -183,7 +189,7 @@ def bench_hier(args, cfg, np, torch, binding, synth):
     roofline["frac_of_sustained_mfma"] = roofline["achieved"] / tf1
     out = {
         "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
-        "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": ms_moe, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "cfg%d %s: %d outer experts (top-%d) of d=%d d_ff=%d, each %d sub-experts of %d neurons, "
@@ -219,16 +225,6 @@ def bench_sweep(args, base, np, torch, binding, synth):
     batches = [args.batch] if args.batch else [2048, 8192]
     xs = {T: torch.from_numpy(src.eval_batch(0, n=T)).to(dev, torch.bfloat16) for T in batches}
 
-    def timed(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
-
     rows = []
     dense_ms = {}
     for name, n, n_s, n_k in SWEEP_SHAPES:
@@ -247,7 +243,7 @@ def bench_sweep(args, base, np, torch, binding, synth):
     head = rows[0]
     out = {
         "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
-        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": base.dtype, "data": "synthetic",
         "config": {"workload": "sweep of expert configurations on cfg%d %s (d=%d d_ff=%d); headline fields are %s at T=%d"
@@ -306,16 +302,6 @@ def main():
     y = torch.empty_like(x)
     topk = torch.empty((T, cfg.top_k), dtype=torch.int32, device=dev)
     counts = torch.empty((cfg.n_routed,), dtype=torch.int32, device=dev)
-
-    def timed(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / steps
 
     if args.copy_probe:
         # a copy of known size: 2^30 bytes read + 2^30 bytes written; scales FETCH_SIZE / WRITE_SIZE readings
@@ -417,7 +403,7 @@ def main():
 
     out = {
         "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
-        "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": ms_moe, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "cfg%d %s: d=%d d_ff=%d, %d experts of %d neurons, %d shared + top-%d of %d routed, T=%d tokens"
