@@ -480,6 +480,7 @@ def test_cfg3_full(binding):
 
 def test_mfma_probe_reports_a_plausible_rate(binding):
     """The measurement aid runs, and all-zero operands are never slower than random ones."""
+    binding.cmoe_probe_mfma(True, 16384)            # brings an idle device up to its sustained clock first
     tf0, mhz0 = binding.cmoe_probe_mfma(False, 2048)
     tf1, mhz1 = binding.cmoe_probe_mfma(True, 2048)
     _say("mfma probe", {"zero_TFLOPs": tf0, "zero_MHz": mhz0, "random_TFLOPs": tf1, "random_MHz": mhz1})
