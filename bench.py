@@ -257,7 +257,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "--gpus %d is not supported. DESIGN.md says how the path would shard." % args.gpus, file=sys.stderr)
+              "--gpus %d is not supported (the design notes say how the path would shard)." % args.gpus, file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
