@@ -468,6 +468,12 @@ def test_cfg1_mid_batches(binding):
     _full(binding, 1, None, n_sample=32, sizes=[33, 64, 65, 300, 1000, 3072])
 
 
+def test_cfg1_very_large_batch(binding):
+    """32768 tokens (131072 slots, 1 GB of per-slot outputs): many rounds of every tile shape, 64-bit offsets
+    into the hidden and slot buffers; routing of every token and sampled outputs against the oracle."""
+    _full(binding, 1, None, n_sample=96, sizes=[32768])
+
+
 @pytest.mark.parametrize("n,n_s,n_k", [(8, 1, 5), (16, 3, 9), (16, 6, 6)])
 def test_paper_expert_configurations(binding, n, n_s, n_k):
     """SxAyEz splits of the paper's configuration study (75 % of the neurons active) on the full-size layer."""
