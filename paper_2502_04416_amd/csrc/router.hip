@@ -543,10 +543,19 @@ __device__ __forceinline__ void route_place_body(const RouterDev& r, RouteIO io,
     for (int i = tid; i < MAX_GROUPS; i += 256) hist[i] = 0;
   }
   __syncthreads();
-  if (worker) score_tile(r, io, pre, ld, sc, LDS_SC, T, 0, tid, 256);
-  __syncthreads();
   io.sel_group = sel_g;
   io.sel_weight = sel_w;
+  if (T == 1) {
+    // one token: wave 0 scores and selects it with one lane per expert (no team split, no barriers in between)
+    if (wave == 0) {
+      route_token(r, io, pre, 0, hist);
+      wave_lds_sync();
+      place_tile(pl, 0, hist, lane, sel_g, sel_w, lw);
+    }
+    return;
+  }
+  if (worker) score_tile(r, io, pre, ld, sc, LDS_SC, T, 0, tid, 256);
+  __syncthreads();
   if (worker) {
     const int tok = tid / TEAM;                    // at most 64 tokens x 4 lanes
     if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM, flat_gr);
