@@ -472,8 +472,9 @@ static int gate_up_cfg(const Engine& e, int64_t T) {
   int best = 0;
   double best_t = 1e30;
   for (const Cand& c : cands) {
-    // a 256-row tile for groups that average less than a quarter of it streams its weights at the pace of a
-    // full tile (measured at 224-256 tokens on 16 experts: 61 us against 52 us with 128x128)
+    // a tile of 192 rows or more for groups that average less than a quarter of it streams its weights at the
+    // pace of a full tile (measured with 256 rows at 224-256 tokens on 16 experts: 61 us against 52 us with
+    // 128x128)
     if (!single && c.bm >= 192 && T * e.S_dyn * 4 < (int64_t)std::min<int64_t>(e.G - e.n_always, T * e.S_dyn) * c.bm) continue;
     int64_t tiles = 0;
     for (int g = 0; g < e.n_always; ++g) tiles += ((T + c.bm - 1) / c.bm) * cdiv(2 * e.width_pad_host[g], c.bn);
