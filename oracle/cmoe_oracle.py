@@ -25,9 +25,11 @@ notes of the repository):
 
 Parity unpinned by the paper (no printed example fixes them): the signed-score
 reading, the iteration count, the centroid used for the representative neuron,
-per-expert calibration in the hierarchical build.  `build` and
-`hier_forward`'s outer gate therefore carry "parity unpinned" for those choices;
-everything else is pinned by tests/test_oracle_*.py.
+per-expert calibration in the hierarchical build (`hier_build`).  `build`,
+`hier_build` and `hier_forward`'s outer gate therefore carry "parity unpinned"
+for those choices: the code that implements each reading is pinned (hand-worked
+examples, exhaustive search, loops written out in the tests), the choice of
+reading is not.  Everything else is pinned by tests/test_oracle_pins.py.
 """
 from __future__ import annotations
 
@@ -192,6 +194,7 @@ def build(w_gate, w_up, calib_x, n_experts: int, n_shared: int, k_act: int = 10,
       mu           [d_h]  activation rates
       label        [N_r*m] cluster of each remaining neuron (remaining in ascending id)
       cost         float  objective of the last assignment
+      label_history, cost_history   the same for every round that ran, in order
     """
     d_h = w_gate.shape[1]
     assert d_h % n_experts == 0
@@ -207,10 +210,13 @@ def build(w_gate, w_up, calib_x, n_experts: int, n_shared: int, k_act: int = 10,
     feat = a[:, remaining].T.astype(F64)                        # [N_r*m, q]
     centroids = init_centroids(a, mu, remaining, n_routed)
     label, cost, prev_label = None, np.nan, None
+    label_history, cost_history = [], []
     for _ in range(max(1, kmeans_iters)):
         dist = distance_matrix(feat, centroids, squared=squared_dist)
         label = balanced_assignment(dist, m)
         cost = assignment_cost(dist, label)
+        label_history.append(label)
+        cost_history.append(cost)
         centroids = update_centroids(feat, label, centroids)
         if prev_label is not None and np.array_equal(prev_label, label):
             break
@@ -226,6 +232,8 @@ def build(w_gate, w_up, calib_x, n_experts: int, n_shared: int, k_act: int = 10,
         "label": label,
         "cost": cost,
         "remaining": remaining,
+        "label_history": label_history,
+        "cost_history": cost_history,
     }
 
 
@@ -311,11 +319,11 @@ def moe_forward(x, w_gate, w_up, w_down, neuron_order, rep_neuron, n_experts: in
 
 
 def moe_forward_one_token(x_row, w_gate, w_up, w_down, neuron_order, rep_neuron, n_experts, n_shared,
-                          top_k, u=None, b=None, sel_override=None) -> Dict[str, np.ndarray]:
+                          top_k, u=None, b=None, sel_override=None, abs_score: bool = False) -> Dict[str, np.ndarray]:
     """The same computation for a single token (used to sample outputs of large batches)."""
     so = None if sel_override is None else np.asarray(sel_override).reshape(1, -1)
     out = moe_forward(np.asarray(x_row)[None, :], w_gate, w_up, w_down, neuron_order, rep_neuron,
-                      n_experts, n_shared, top_k, u=u, b=b, sel_override=so)
+                      n_experts, n_shared, top_k, u=u, b=b, abs_score=abs_score, sel_override=so)
     return {k: v[0] for k, v in out.items()}
 
 
@@ -348,7 +356,8 @@ def outer_route(x, w_router, offsets, outer_top_k: int) -> Tuple[np.ndarray, np.
 
 
 def hier_forward(x, w_router, offsets, outer_top_k: int, experts: Sequence[dict], n_sub: int,
-                 n_shared: int, top_k: int, outer_sel_override=None, sub_sel_override=None) -> Dict[str, np.ndarray]:
+                 n_shared: int, top_k: int, outer_sel_override=None, sub_sel_override=None,
+                 abs_score: bool = False) -> Dict[str, np.ndarray]:
     """Existing MoE layer whose every expert E_e has been restructured into
     E^s_e + sum_j g'_{e,j} E^r_{e,j}  (Sec. 4.4, Eq. 10):
         y = sum_{e in outer top-k} w_e * F_MoE^{(e)}(x).
@@ -372,12 +381,35 @@ def hier_forward(x, w_router, offsets, outer_top_k: int, experts: Sequence[dict]
         so = None if sub_sel_override is None else np.asarray(sub_sel_override)[rows, slot]
         out = moe_forward(x[rows], ex["w_gate"], ex["w_up"], ex["w_down"], ex["neuron_order"],
                           ex["rep_neuron"], n_sub, n_shared, top_k, u=ex.get("u"), b=ex.get("b"),
-                          sel_override=so)
+                          abs_score=abs_score, sel_override=so)
         y[rows] += o_w[rows, slot][:, None] * out["y"]
         sub_sel[rows, slot] = out["sel"]
         sub_gap[rows, slot] = out["gap"]
     return {"y": y, "outer_sel": o_sel, "outer_weight": o_w, "outer_gap": o_gap,
             "sub_sel": sub_sel, "sub_gap": sub_gap}
+
+
+def hier_build(expert_weights: Sequence[Tuple[np.ndarray, np.ndarray]], w_router, offsets, outer_top_k: int,
+               calib_x, n_sub: int, n_shared: int, k_act: int = 10, kmeans_iters: int = 1,
+               squared_dist: bool = False, min_tokens: int = 64) -> Dict[str, list]:
+    """Restructuring of every expert of an existing MoE layer (Sec. 4.4): stages (A)-(C) of Sec. 4 are
+    applied to each expert E_e on its own.  The paper does not say which calibration tokens profile
+    which expert; the reading taken here (parity unpinned): expert e is profiled on the calibration
+    tokens whose outer top-k contains e, in their original order, and on the whole calibration set when
+    fewer than max(min_tokens, K_a) tokens reach it.
+    expert_weights[e] = (w_gate_e, w_up_e).  Returns per expert: parts (the dict of `build`),
+    tokens (indices of the calibration tokens used), routed (how many tokens the outer router sent)."""
+    calib_x = np.asarray(calib_x, dtype=F64)
+    o_sel, _, _ = outer_route(calib_x, w_router, offsets, outer_top_k)
+    parts, tokens, routed = [], [], []
+    for e, (wg, wu) in enumerate(expert_weights):
+        rows = np.nonzero((o_sel == e).any(axis=1))[0]
+        routed.append(int(rows.size))
+        if rows.size < max(min_tokens, k_act):
+            rows = np.arange(calib_x.shape[0])
+        tokens.append(rows)
+        parts.append(build(wg, wu, calib_x[rows], n_sub, n_shared, k_act, kmeans_iters, squared_dist))
+    return {"parts": parts, "tokens": tokens, "routed": routed}
 
 
 def moe_layer_dense_experts(x, w_router, offsets, outer_top_k: int, experts: Sequence[dict]) -> np.ndarray:

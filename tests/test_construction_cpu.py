@@ -75,7 +75,8 @@ def _check_build(cfg, weights, calib, kmeans_iters=1, dist_mode=0):
     e = binding.cmoe_export_partition(h, cfg.d_ff, cfg.n_routed)
     binding.cmoe_destroy(h)
     wg, wu, _ = weights
-    p = O.build(wg, wu, calib, cfg.n_experts, cfg.n_shared, cfg.k_act, kmeans_iters=1, squared_dist=bool(dist_mode))
+    p = O.build(wg, wu, calib, cfg.n_experts, cfg.n_shared, cfg.k_act, kmeans_iters=kmeans_iters,
+                squared_dist=bool(dist_mode))
     m, n_s, n_r = cfg.m, cfg.n_shared, cfg.n_routed
     order = e["neuron_order"]
     # rates, shared experts: unique, must match exactly (ties to the lowest index on both sides)
@@ -83,7 +84,8 @@ def _check_build(cfg, weights, calib, kmeans_iters=1, dist_mode=0):
     assert np.array_equal(order[: n_s * m], p["neuron_order"][: n_s * m])
     # partition
     assert sorted(order.tolist()) == list(range(cfg.d_ff))
-    # cost of the first assignment is unique even where the assignment is not
+    # the cost of the first assignment is unique even where the assignment is not; later rounds start from
+    # centroids that depend on which optimal assignment was taken (see test_build_rounds_chain)
     if kmeans_iters == 1:
         assert e["cost"] == pytest.approx(p["cost"], rel=1e-9)
     # representative neurons: valid under the library's own final clusters (Eq. 7)
@@ -129,10 +131,55 @@ def test_build_first_assignment_is_optimal_for_the_oracles_distances():
 @pytest.mark.parametrize("dtype,iters,dist_mode", [("bf16", 1, 0), ("bf16", 3, 1), ("fp32", 2, 0)])
 def test_build_reduced_configs(dtype, iters, dist_mode):
     cfg = synth.scaled(synth.CONFIGS[1], d_model=128, d_ff=768, n_experts=12, n_shared=2, top_k=3, dtype=dtype,
-                       n_centres=8, n_calib=300, k_act=6)
+                       n_centres=8, n_calib=100, k_act=20)
     weights = synth.make_weights(cfg)
     calib = synth.make_token_source(cfg).calibration()
-    _check_build(cfg, weights, calib, kmeans_iters=iters, dist_mode=dist_mode)
+    e, _ = _check_build(cfg, weights, calib, kmeans_iters=iters, dist_mode=dist_mode)
+    assert e["cost"] > 1.0                              # the routed neurons' feature vectors are not all zero
+
+
+@pytest.mark.parametrize("dtype,dist_mode", [("bf16", 1), ("fp32", 0)])
+def test_build_rounds_chain(dtype, dist_mode):
+    """Several K-means rounds (App. A.3: assignment, cluster update, repeated).  Optimal assignments are not
+    unique, so the library's round k cannot be compared with the oracle's round k label by label.  What is
+    unique: a build with k rounds starts from the result of the build with k - 1 rounds (the library is
+    deterministic), so the labels of k - 1 rounds give the centroids of round k (means of their members,
+    computed here by the oracle's update), the oracle's distance matrix against those centroids prices the
+    labels of k rounds, and that price must equal both the cost the library reports and the optimum of that
+    matrix (the oracle's replicated-column assignment).  A library that skipped the update, updated from
+    other labels, or stopped early without reason fails the cost equality."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=128, d_ff=768, n_experts=12, n_shared=2, top_k=3, dtype=dtype,
+                       n_centres=8, n_calib=100, k_act=20)
+    wg, wu, wd = synth.make_weights(cfg)
+    calib = synth.make_token_source(cfg).calibration()
+    m, n_s, n_r = cfg.m, cfg.n_shared, cfg.n_routed
+    a = O.atopk_matrix(O.hidden_states(calib, wg, wu), cfg.k_act)
+    mu = O.activation_rates(a)
+    shared = O.select_shared(mu, n_s * m)
+    remaining = np.setdiff1d(np.arange(cfg.d_ff), shared)
+    feat = a[:, remaining].T.astype(float)
+    pos = {int(nid): k for k, nid in enumerate(remaining)}
+    cent = O.init_centroids(a, mu, remaining, n_r)
+    prev_label, moved, stopped = None, 0, False
+    for k in range(1, 8):
+        h = binding.cmoe_build(binding.make_config(cfg, k, dist_mode), wg, wu, wd, calib)
+        e = binding.cmoe_export_partition(h, cfg.d_ff, n_r)
+        binding.cmoe_destroy(h)
+        assert np.array_equal(np.sort(e["neuron_order"][: n_s * m]), np.sort(shared))
+        label = np.empty(len(remaining), dtype=np.int64)
+        for j in range(n_r):
+            for nid in e["neuron_order"][(n_s + j) * m:(n_s + j + 1) * m]:
+                label[pos[int(nid)]] = j
+        dist = O.distance_matrix(feat, cent, squared=bool(dist_mode))
+        assert O.assignment_cost(dist, label) == pytest.approx(e["cost"], rel=1e-9)
+        assert e["cost"] == pytest.approx(O.assignment_cost(dist, O.balanced_assignment(dist, m)), rel=1e-9)
+        if prev_label is not None and np.array_equal(prev_label, label):
+            stopped = True                          # the library stops when a round moves nothing
+            break
+        moved += prev_label is not None
+        prev_label = label
+        cent = O.update_centroids(feat, label, cent)
+    assert moved >= 1 and stopped                   # later rounds did change the assignment, then it settled
 
 
 def test_build_argument_errors():

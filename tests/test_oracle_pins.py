@@ -270,6 +270,117 @@ def test_build_assignment_optimal_by_exchange_certificate():
     assert np.diag(w).min() >= -1e-9
 
 
+def test_init_centroids_hand_example():
+    """App. A.3 'Centroid Initialization' worked by hand.  Six neurons over four calibration tokens:
+        column      0        1        2        3        4        5
+        A[:, i]  (1,1,1,1) (1,0,1,0) (0,1,0,0) (1,1,0,1) (0,1,0,1) (0,0,0,0)
+        mu          1       0.5      0.25     0.75      0.5       0
+    Neuron 0 is the shared one, so the candidates are 1..5; with two routed experts the initial centroids
+    are the feature vectors of neuron 3 (rate 0.75) and then of neuron 1: it ties with neuron 4 at 0.5 and
+    the lower index wins.  A choice of the lowest rates would give neurons 5 and 2, one that forgot to
+    exclude the shared neuron would start with neuron 0, one that returned rows of A instead of columns
+    would have the wrong shape."""
+    a = np.array([[1, 1, 0, 1, 0, 0],
+                  [1, 0, 1, 1, 1, 0],
+                  [1, 1, 0, 0, 0, 0],
+                  [1, 0, 0, 1, 1, 0]], dtype=bool)
+    mu = O.activation_rates(a)
+    assert mu.tolist() == [1.0, 0.5, 0.25, 0.75, 0.5, 0.0]
+    cent = O.init_centroids(a, mu, np.array([1, 2, 3, 4, 5]), 2)
+    assert cent.shape == (2, 4)
+    assert cent.tolist() == [[1.0, 1.0, 0.0, 1.0], [1.0, 0.0, 1.0, 0.0]]
+    # a remaining set given in another order must not change which neurons are picked on a tie
+    cent = O.init_centroids(a, mu, np.array([1, 2, 3, 4, 5]), 3)
+    assert cent.tolist() == [[1.0, 1.0, 0.0, 1.0], [1.0, 0.0, 1.0, 0.0], [0.0, 1.0, 0.0, 1.0]]
+
+
+def _loops_hidden(x, wg, wu):
+    q, d = x.shape
+    h = np.zeros((q, wg.shape[1]))
+    for t in range(q):
+        for i in range(wg.shape[1]):
+            a = sum(x[t, k] * wg[k, i] for k in range(d))
+            b = sum(x[t, k] * wu[k, i] for k in range(d))
+            h[t, i] = a / (1.0 + math.exp(-a)) * b
+    return h
+
+
+def _bruteforce_optimum(dist, n_r, m):
+    """Minimum of sum_i dist[i][label_i] over all labellings with exactly m rows per cluster."""
+    n = len(dist)
+    best = math.inf
+    for lab in itertools.product(range(n_r), repeat=n):
+        if any(lab.count(j) != m for j in range(n_r)):
+            continue
+        best = min(best, sum(dist[i][lab[i]] for i in range(n)))
+    return best
+
+
+@pytest.mark.parametrize("seed,squared", [(25, False), (29, False), (40, True)])
+def test_build_rounds_against_a_loop_written_out_here(seed, squared):
+    """The whole of stages (A)-(C) with several K-means rounds (App. A.2-A.3, Eq. 7) on a layer small enough
+    for exhaustive search: 12 neurons, 4 experts of 3 (1 shared), 16 calibration tokens, K_a = 3.
+    Everything is recomputed here with explicit loops and sorts.  Optimal assignments are not unique, so
+    every round is checked through what is: given the oracle's own labels of the round before, the centroids
+    are the means of those members (the initial ones: the three remaining neurons of highest rate), the
+    distance matrix follows, and the oracle's cost of this round must equal the exhaustive optimum of that
+    matrix and be attained by the oracle's balanced labelling.  The seeds were chosen so that the second
+    round changes the assignment (a loop that never updated its centroids, or updated them from the wrong
+    labels, prices differently) and so that seed 25 has a rate tie at the initial-centroid boundary."""
+    r = _rng(seed)
+    d, d_h, q, n_experts, n_shared, k_act = 5, 12, 16, 4, 1, 3
+    m, n_r = d_h // n_experts, n_experts - n_shared
+    wg, wu = r.standard_normal((d, d_h)), r.standard_normal((d, d_h))
+    x = r.standard_normal((q, d))
+    p = O.build(wg, wu, x, n_experts, n_shared, k_act, kmeans_iters=4, squared_dist=squared)
+    # (A) profiling
+    h = _loops_hidden(x, wg, wu)
+    a = np.zeros((q, d_h), dtype=int)
+    for t in range(q):
+        for i in sorted(range(d_h), key=lambda i: (-abs(h[t, i]), i))[:k_act]:
+            a[t, i] = 1
+    mu = [sum(a[t, i] for t in range(q)) / q for i in range(d_h)]
+    assert np.allclose(p["mu"], mu, rtol=0, atol=1e-15)
+    ranked = sorted(range(d_h), key=lambda i: (-mu[i], i))
+    shared = ranked[: n_shared * m]
+    assert p["neuron_order"][: n_shared * m].tolist() == shared
+    remaining = sorted(set(range(d_h)) - set(shared))
+    assert p["remaining"].tolist() == remaining
+    n = len(remaining)
+    # (B) rounds
+    hist = p["label_history"]
+    assert len(hist) == len(p["cost_history"]) >= 3
+    assert not np.array_equal(hist[0], hist[1])                  # the second round matters for these seeds
+    assert np.array_equal(hist[-1], hist[-2])                    # ... and the loop stopped because nothing moved
+    assert all(not np.array_equal(hist[k], hist[k - 1]) for k in range(1, len(hist) - 1))
+    cent = [[float(a[t, i]) for t in range(q)] for i in sorted(remaining, key=lambda i: (-mu[i], i))[:n_r]]
+    for k, label in enumerate(hist):
+        assert np.bincount(label, minlength=n_r).tolist() == [m] * n_r
+        dist = [[sum((a[t, i] - cent[j][t]) ** 2 for t in range(q)) for j in range(n_r)] for i in remaining]
+        if not squared:
+            dist = [[math.sqrt(v) for v in row] for row in dist]
+        mine = sum(dist[i][label[i]] for i in range(n))
+        assert p["cost_history"][k] == pytest.approx(mine, rel=1e-12)
+        assert mine == pytest.approx(_bruteforce_optimum(dist, n_r, m), rel=1e-12)
+        cent = [[sum(a[t, remaining[i]] for i in range(n) if label[i] == j) / m for t in range(q)] for j in range(n_r)]
+    assert p["cost"] == p["cost_history"][-1] and np.array_equal(p["label"], hist[-1])
+    # (C) representative neurons against the means of the final members, ties to the lowest neuron id
+    for j in range(n_r):
+        members = [remaining[i] for i in range(n) if hist[-1][i] == j]
+        assert p["neuron_order"][(n_shared + j) * m:(n_shared + j + 1) * m].tolist() == members
+        dd = [math.sqrt(sum((a[t, i] - cent[j][t]) ** 2 for t in range(q))) for i in members]
+        assert p["rep_neuron"][j] == members[dd.index(min(dd))]
+
+
+def test_build_single_round_is_the_first_round_of_several():
+    r = _rng(25)
+    wg, wu, x = r.standard_normal((5, 12)), r.standard_normal((5, 12)), r.standard_normal((16, 5))
+    one = O.build(wg, wu, x, 4, 1, 3, kmeans_iters=1)
+    many = O.build(wg, wu, x, 4, 1, 3, kmeans_iters=4)
+    assert len(one["label_history"]) == 1
+    assert one["cost"] == many["cost_history"][0] and np.array_equal(one["label"], many["label_history"][0])
+
+
 # ------------------------------------------------------------------ Eq. 4/5/8/9: forward
 
 def test_top_k_matches_sort_and_tie_rule():
@@ -329,6 +440,42 @@ def test_error_identity(top_k):
                     a_ = x[t] @ wg[:, i]
                     missing += (a_ / (1 + math.exp(-a_))) * (x[t] @ wu[:, i]) * wd[i]
         assert np.allclose(out["y"][t] - dense[t], -missing, rtol=1e-11, atol=1e-11)
+
+
+def test_abs_score_ranks_experts_by_magnitude():
+    """The optional key |s| (the router ranks experts by the size of the representative neuron's hidden
+    state, Sec. 4.2 Eq. 6-8): selection = a stable descending sort of |h_{R_j}| taken from the dense hidden
+    state, scores stay signed, and the same option reaches the one-token and the hierarchical forwards.
+    The layer is drawn so that the two keys disagree on most tokens."""
+    n_experts, n_shared, top_k = 8, 2, 2
+    wg, wu, wd = _tiny_layer(31, d=8, d_h=24)
+    x = _rng(32).standard_normal((40, 8))
+    order, reps = _random_partition(33, 24, n_experts, n_shared)
+    h = O.hidden_states(x, wg, wu)
+    signed = O.moe_forward(x, wg, wu, wd, order, reps, n_experts, n_shared, top_k)
+    mag = O.moe_forward(x, wg, wu, wd, order, reps, n_experts, n_shared, top_k, abs_score=True)
+    assert np.array_equal(mag["scores"], signed["scores"])
+    differ = 0
+    for t in range(40):
+        want = sorted(range(6), key=lambda j: (-abs(h[t, reps[j]]), j))[:top_k]
+        assert mag["sel"][t].tolist() == want
+        differ += want != signed["sel"][t].tolist()
+        one = O.moe_forward_one_token(x[t], wg, wu, wd, order, reps, n_experts, n_shared, top_k, abs_score=True)
+        assert one["sel"].tolist() == want and np.allclose(one["y"], mag["y"][t], rtol=1e-13, atol=1e-13)
+    assert differ >= 10
+    # with u, b set the key is Softmax(|s|) + b
+    u, b = _rng(34).uniform(-0.5, 0.5, 6), _rng(35).standard_normal(6) * 0.05
+    g = O.moe_forward(x, wg, wu, wd, order, reps, n_experts, n_shared, top_k, u=u, b=b, abs_score=True)
+    for t in range(40):
+        e = np.exp(np.abs(h[t, reps]) - np.abs(h[t, reps]).max())
+        sp = e / e.sum()
+        want = sorted(range(6), key=lambda j: (-(sp[j] + b[j]), j))[:top_k]
+        assert g["sel"][t].tolist() == want
+        assert np.allclose(g["gate"][t], 1.0 + sp[want] * u[want], rtol=1e-12)
+    # hierarchy: one outer expert holding this layer, outer weight 1
+    ex = [{"w_gate": wg, "w_up": wu, "w_down": wd, "neuron_order": order, "rep_neuron": reps}]
+    hz = O.hier_forward(x, np.ones((8, 1)), np.zeros(1), 1, ex, n_experts, n_shared, top_k, abs_score=True)
+    assert np.array_equal(hz["sub_sel"][:, 0, :], mag["sel"]) and np.allclose(hz["y"], mag["y"], rtol=1e-12, atol=1e-12)
 
 
 def test_gate_neutral_at_initialisation():
@@ -445,6 +592,41 @@ def test_hierarchical_per_token_bruteforce():
                                                 ex["neuron_order"], ex["rep_neuron"], 6, 2, 2)["y"]
         assert out["outer_sel"][t].tolist() == top
         assert np.allclose(out["y"][t], y, rtol=1e-12, atol=1e-12)
+
+
+def test_hier_build_routes_the_calibration_tokens_by_hand():
+    """Restructuring an existing MoE layer expert by expert (Sec. 4.4): with W_router = the first three
+    unit vectors, token t's logits are its first three coordinates, so which experts profile which
+    calibration tokens can be read off the tokens.  Expert e is built on the tokens whose outer top-2
+    contains e (in order); an expert that receives fewer than the minimum is built on the whole set."""
+    d, d_h, n_sub, n_shared, k_act = 6, 8, 4, 1, 2
+    r = _rng(50)
+    q = 12
+    x = r.standard_normal((q, d))
+    # coordinates 0..2 decide the outer routing: tokens 0-5 prefer (0, 1), 6-9 prefer (0, 2), 10-11 prefer (1, 2)
+    x[:, :3] = 0.0
+    x[0:6, 0], x[0:6, 1] = 5.0, 4.0
+    x[6:10, 0], x[6:10, 2] = 4.0, 5.0
+    x[10:12, 1], x[10:12, 2] = 5.0, 4.0
+    w_router = np.zeros((d, 3))
+    w_router[0, 0] = w_router[1, 1] = w_router[2, 2] = 1.0
+    weights = [(r.standard_normal((d, d_h)), r.standard_normal((d, d_h))) for _ in range(3)]
+    hb = O.hier_build(weights, w_router, np.zeros(3), 2, x, n_sub, n_shared, k_act, min_tokens=7)
+    assert hb["routed"] == [10, 8, 6]
+    assert hb["tokens"][0].tolist() == list(range(10))
+    assert hb["tokens"][1].tolist() == [0, 1, 2, 3, 4, 5, 10, 11]
+    assert hb["tokens"][2].tolist() == list(range(12))          # 6 < 7: falls back to the whole set
+    for e in range(3):
+        rows = hb["tokens"][e]
+        h = _loops_hidden(x[rows], *weights[e])
+        a = np.zeros(h.shape, dtype=int)
+        for t in range(h.shape[0]):
+            for i in sorted(range(d_h), key=lambda i: (-abs(h[t, i]), i))[:k_act]:
+                a[t, i] = 1
+        assert np.allclose(hb["parts"][e]["mu"], a.sum(axis=0) / len(rows), rtol=0, atol=1e-15)
+    # offsets move the routing: a large offset on expert 2 puts it into every token's top-2
+    hb2 = O.hier_build(weights, w_router, np.array([0.0, 0.0, 10.0]), 2, x, n_sub, n_shared, k_act, min_tokens=7)
+    assert hb2["routed"] == [10, 2, 12]
 
 
 def test_moe_layer_dense_experts_hand_weights():
