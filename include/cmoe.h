@@ -116,7 +116,10 @@ int cmoe_export_partition(const cmoe_layer* layer, int32_t* neuron_order, int32_
 
 /* Gate parameters of Eq. 9: u [N_r] (NULL = zeros), b [N_r] (NULL = zeros), host fp32.
  * With both zero the gate is the binary gate of Eq. 4 and no softmax is evaluated.
- * May be called before or after cmoe_upload; takes effect at the next forward. */
+ * May be called before or after cmoe_upload; takes effect at the next forward.  On an uploaded layer
+ * the call waits for the whole device (hipDeviceSynchronize) before it overwrites the device copy, so a
+ * forward still in flight on any stream keeps the old values; it must not overlap a forward being
+ * enqueued from another host thread. */
 int cmoe_set_gate_params(cmoe_layer* layer, const float* u, const float* b);
 
 /* Copies the current gate parameters to host arrays u [N_r], b [N_r] (either may be NULL). */
@@ -130,8 +133,15 @@ int cmoe_get_gate_params(const cmoe_layer* layer, float* u, float* b);
  * not for layers inside a hierarchy).  CMOE_EINVAL on a negative count or a negative gamma. */
 int cmoe_update_bias(cmoe_layer* layer, const int32_t* counts, float gamma);
 
+/* The dense baseline F(x) of Eq. 3 needs a second, single-group copy of the layer's weights.  It is
+ * kept by default (the speedup of the restructured layer is measured against it); enabled = 0 before
+ * cmoe_upload / cmoe_hier_create releases the host copy and leaves it out of cmoe_packed_bytes and of the
+ * upload: cmoe_dense_forward then returns CMOE_ESTATE.  It cannot be enabled again (CMOE_ESTATE). */
+int cmoe_set_baseline(cmoe_layer* layer, int enabled);
+
 /* Bytes of device memory cmoe_upload needs for the packed weights (expert-sliced copy for the
- * MoE forward, an unpadded copy for the dense baseline, and the router columns). */
+ * MoE forward, the router columns and, unless cmoe_set_baseline switched it off, an unpadded copy
+ * for the dense baseline). */
 size_t cmoe_packed_bytes(const cmoe_layer* layer);
 
 /* Bytes of device workspace a forward call with up to max_tokens tokens needs. */
@@ -179,6 +189,27 @@ void cmoe_destroy(cmoe_layer* layer);
  * w_router: host fp32 [d, n_outer]; logit_offset: host fp32 [n_outer] or NULL. */
 int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_top_k,
                      const float* w_router, const float* logit_offset, cmoe_hier** out);
+
+/* The same from the un-restructured MoE layer (Sec. 4.4): w_gate / w_up / w_down are arrays of n_outer host
+ * pointers to the experts' dense matrices ([d, d_h], [d, d_h], [d_h, d] each, fp32), calib_x [q, d] one
+ * calibration set for the whole layer.  The calibration tokens are routed by the outer router on the host
+ * (double precision on the dtype-rounded operands, top-`outer_top_k`, ties to the lowest id); outer expert e
+ * is then restructured as by cmoe_build (cmoe_build_gpu when on_gpu != 0) on the tokens whose selection
+ * contains e, in their original order, or on the whole set when fewer than max(min_tokens, K_a) tokens reach
+ * it (min_tokens <= 0 means 64).  The paper does not say which tokens profile which expert; this is the
+ * reading taken.  with_baseline = 0 leaves out the un-restructured copy (cmoe_hier_dense_forward then
+ * returns CMOE_ESTATE).  The hierarchy owns the experts it built: cmoe_hier_destroy frees them. */
+int cmoe_hier_build(const cmoe_config* cfg, int32_t n_outer, int32_t outer_top_k, const float* const* w_gate,
+                    const float* const* w_up, const float* const* w_down, const float* w_router,
+                    const float* logit_offset, const float* calib_x, int64_t q, int32_t min_tokens, int on_gpu,
+                    int with_baseline, cmoe_hier** out);
+
+/* Outer expert e of a hierarchy as a borrowed handle (valid until cmoe_hier_destroy; use it with
+ * cmoe_export_partition / cmoe_get_gate_params only), NULL if e is out of range.  calib_routed / calib_used
+ * (either may be NULL) receive how many calibration tokens the outer router sent to the expert and how
+ * many it was profiled on in cmoe_hier_build (-1 for a hierarchy made by cmoe_hier_create). */
+const cmoe_layer* cmoe_hier_expert(const cmoe_hier* h, int32_t e, int64_t* calib_routed, int64_t* calib_used);
+
 size_t cmoe_hier_packed_bytes(const cmoe_hier* h);
 size_t cmoe_hier_workspace_bytes(const cmoe_hier* h, int64_t max_tokens);
 int cmoe_hier_upload(cmoe_hier* h, void* dev_weights, void* hip_stream);
@@ -218,6 +249,14 @@ int cmoe_probe_mfma(int random_operands, int iters, double* tflops, double* shad
  * *gbytes_per_s (host).  Allocates, zero-fills and frees the buffer, runs on the null stream and
  * synchronises; not part of the forward path. */
 int cmoe_probe_hbm(size_t bytes, int reps, double* gbytes_per_s);
+
+/* Tuning switch `name` (the names of the environment variables the library reads once at first use:
+ * CMOE_GEMM1_CFG, CMOE_GEMM2_CFG, CMOE_XCD_REMAP, CMOE_SPLITK, CMOE_ZERO_PAD, CMOE_DECODE_FUSE,
+ * CMOE_FRONT_SHARED, CMOE_FORCE_SIMT, CMOE_LDPAD, CMOE_HOST_THREADS, CMOE_SKIP_ROWS, CMOE_DECODE_SPLIT,
+ * CMOE_WS_DOWN) takes `value` from the next call on; -1 restores the per-batch choice of the tile-shape
+ * switches.  For A/B measurements and tests inside one process; every default is the measured best.  Not
+ * synchronised against forwards being enqueued from other host threads.  CMOE_EINVAL on an unknown name. */
+int cmoe_set_tuning(const char* name, int value);
 
 const char* cmoe_last_error(void);   /* thread-local, never NULL */
 const char* cmoe_version(void);

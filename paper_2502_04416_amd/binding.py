@@ -39,7 +39,8 @@ EXPORTS = [
     "cmoe_hier_upload", "cmoe_hier_forward", "cmoe_hier_dense_forward", "cmoe_hier_destroy",
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
     "cmoe_balanced_assignment", "cmoe_probe_mfma", "cmoe_probe_hbm", "cmoe_get_gate_params", "cmoe_update_bias",
-    "cmoe_build_gpu", "cmoe_profile_activations",
+    "cmoe_build_gpu", "cmoe_profile_activations", "cmoe_set_baseline", "cmoe_hier_build", "cmoe_hier_expert",
+    "cmoe_set_tuning",
 ]
 
 
@@ -90,6 +91,13 @@ def load():
     lib.cmoe_hier_destroy.restype = None
     lib.cmoe_probe_mfma.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.cmoe_probe_hbm.argtypes = [C.c_size_t, C.c_int, C.POINTER(C.c_double)]
+    lib.cmoe_set_baseline.argtypes = [vp, C.c_int]
+    fpp = C.POINTER(f32p)
+    lib.cmoe_hier_build.argtypes = [cfgp, C.c_int32, C.c_int32, fpp, fpp, fpp, f32p, f32p, f32p, i64, C.c_int32, C.c_int,
+                                    C.c_int, C.POINTER(vp)]
+    lib.cmoe_hier_expert.argtypes = [vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.cmoe_hier_expert.restype = vp
+    lib.cmoe_set_tuning.argtypes = [C.c_char_p, C.c_int]
     lib.cmoe_last_error.restype = C.c_char_p
     lib.cmoe_version.restype = C.c_char_p
     _lib = lib
@@ -263,6 +271,37 @@ def cmoe_hier_create(layers: Sequence[int], outer_top_k: int, w_router, logit_of
     return h.value
 
 
+def cmoe_hier_build(cfg: cmoe_config, outer_top_k: int, w_gate: Sequence, w_up: Sequence, w_down: Sequence, w_router,
+                    logit_offset, calib_x, min_tokens: int = 64, on_gpu: bool = False, with_baseline: bool = True) -> int:
+    n = len(w_gate)
+    wg, wu, wd = [_f32(a) for a in w_gate], [_f32(a) for a in w_up], [_f32(a) for a in w_down]
+    fpp = C.POINTER(C.c_float) * n
+    wr, cx = _f32(w_router), _f32(calib_x)
+    off = None if logit_offset is None else _f32(logit_offset)
+    h = C.c_void_p()
+    _check(load().cmoe_hier_build(C.byref(cfg), n, outer_top_k, fpp(*[_fp(a) for a in wg]), fpp(*[_fp(a) for a in wu]),
+                                  fpp(*[_fp(a) for a in wd]), _fp(wr), _fp(off), _fp(cx), cx.shape[0], int(min_tokens),
+                                  int(on_gpu), int(with_baseline), C.byref(h)), "cmoe_hier_build")
+    return h.value
+
+
+def cmoe_hier_expert(h: int, e: int):
+    """(borrowed layer handle, calibration tokens routed to the expert, calibration tokens it was built on)."""
+    routed, used = C.c_int64(), C.c_int64()
+    layer = load().cmoe_hier_expert(h, e, C.byref(routed), C.byref(used))
+    if not layer:
+        raise CmoeError("cmoe_hier_expert failed: %s" % load().cmoe_last_error().decode())
+    return layer, routed.value, used.value
+
+
+def cmoe_set_baseline(layer: int, enabled: bool) -> None:
+    _check(load().cmoe_set_baseline(layer, int(enabled)), "cmoe_set_baseline")
+
+
+def cmoe_set_tuning(name: str, value: int) -> None:
+    _check(load().cmoe_set_tuning(name.encode(), int(value)), "cmoe_set_tuning")
+
+
 def cmoe_hier_packed_bytes(h: int) -> int:
     return load().cmoe_hier_packed_bytes(h)
 
@@ -339,9 +378,12 @@ class Layer(_DeviceMixin):
         self._ws_tokens = -1
 
     @classmethod
-    def from_partition(cls, cfg, w_gate, w_up, w_down, neuron_order, rep_neuron, score_mode: int = 0, upload=True):
+    def from_partition(cls, cfg, w_gate, w_up, w_down, neuron_order, rep_neuron, score_mode: int = 0, upload=True,
+                       baseline=True):
         h = cmoe_build_from_partition(make_config(cfg, score_mode=score_mode), w_gate, w_up, w_down, neuron_order, rep_neuron)
         self = cls(h, cfg)
+        if not baseline:
+            cmoe_set_baseline(h, False)
         if upload:
             self.upload()
         return self
@@ -439,17 +481,32 @@ class Layer(_DeviceMixin):
 class Hierarchy(_DeviceMixin):
     """An MoE layer whose experts were each restructured (Sec. 4.4)."""
 
-    def __init__(self, layers: Sequence[Layer], outer_top_k: int, w_router, logit_offset):
+    def __init__(self, layers: Sequence[Layer], outer_top_k: int, w_router, logit_offset, handle=None, cfg=None):
         self.layers = list(layers)
-        self.cfg = layers[0].cfg
+        self.cfg = layers[0].cfg if cfg is None else cfg
         self.bf16 = self.cfg.dtype == "bf16"
         self.outer_top_k = outer_top_k
-        self.h = cmoe_hier_create([l.h for l in layers], outer_top_k, w_router, logit_offset)
+        self.h = handle if handle is not None else cmoe_hier_create([l.h for l in layers], outer_top_k, w_router, logit_offset)
         torch = _torch()
         self._weights = self._alloc(cmoe_hier_packed_bytes(self.h))
         cmoe_hier_upload(self.h, self._weights.data_ptr(), _stream_ptr(torch))
         self._ws = None
         self._ws_tokens = -1
+
+    @classmethod
+    def build(cls, cfg, outer_top_k: int, w_gate, w_up, w_down, w_router, logit_offset, calib_x, kmeans_iters=1,
+              dist_mode=0, score_mode=0, min_tokens=64, on_gpu=False, with_baseline=True):
+        """cmoe_hier_build: the library routes the calibration tokens and restructures every outer expert."""
+        h = cmoe_hier_build(make_config(cfg, kmeans_iters, dist_mode, score_mode), outer_top_k, w_gate, w_up, w_down,
+                            w_router, logit_offset, calib_x, min_tokens, on_gpu, with_baseline)
+        return cls([], outer_top_k, None, None, handle=h, cfg=cfg)
+
+    def expert_partition(self, e: int):
+        """Partition of outer expert e plus the calibration-token counts of cmoe_hier_build."""
+        layer, routed, used = cmoe_hier_expert(self.h, e)
+        part = cmoe_export_partition(layer, self.cfg.d_ff, self.cfg.n_routed)
+        part["calib_routed"], part["calib_used"] = routed, used
+        return part
 
     def _ws_bytes(self, T):
         return cmoe_hier_workspace_bytes(self.h, T)

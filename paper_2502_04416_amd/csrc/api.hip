@@ -1,10 +1,12 @@
 // C ABI of libcmoe (see include/cmoe.h): handles, argument checks, weight packing and upload, and the
 // forward calls, which only enqueue kernels on the caller's stream.
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
 #include <memory>
 #include <new>
 #include <string>
@@ -37,14 +39,35 @@ size_t elem_size(int dtype) { return dtype == CMOE_BF16 ? 2 : 4; }
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+struct TuningField { const char* name; int Tuning::*field; };
+static const TuningField kTuningFields[] = {
+    {"CMOE_GEMM1_CFG", &Tuning::gemm1_cfg},     {"CMOE_GEMM2_CFG", &Tuning::gemm2_cfg},
+    {"CMOE_XCD_REMAP", &Tuning::xcd_remap},     {"CMOE_SPLITK", &Tuning::splitk},
+    {"CMOE_ZERO_PAD", &Tuning::zero_pad},       {"CMOE_DECODE_FUSE", &Tuning::decode_fuse},
+    {"CMOE_FRONT_SHARED", &Tuning::front_shared}, {"CMOE_FORCE_SIMT", &Tuning::force_simt},
+    {"CMOE_LDPAD", &Tuning::ldpad},             {"CMOE_HOST_THREADS", &Tuning::host_threads},
+    {"CMOE_SKIP_ROWS", &Tuning::skip_rows},     {"CMOE_DECODE_SPLIT", &Tuning::decode_split},
+    {"CMOE_WS_DOWN", &Tuning::ws_down},
+};
+
+Tuning& tuning() {
+  static Tuning t = [] {
+    Tuning v;
+    for (const TuningField& f : kTuningFields)
+      if (const char* e = std::getenv(f.name)) v.*(f.field) = std::atoi(e);
+    return v;
+  }();
+  return t;
+}
+
 int w1_row_stride(int d) {
-  static const int pad = std::getenv("CMOE_LDPAD") ? std::atoi(std::getenv("CMOE_LDPAD")) : 0;
+  const int pad = tuning().ldpad;
   return d + ((pad > 0 && pad % 8 == 0) ? pad : 0);
 }
 
 void parallel_for(int64_t n, const std::function<void(int64_t)>& fn, int max_threads) {
   int nt = max_threads > 0 ? max_threads : (int)std::thread::hardware_concurrency();
-  if (const char* env = std::getenv("CMOE_HOST_THREADS")) nt = std::atoi(env);
+  if (tuning().host_threads > 0) nt = tuning().host_threads;
   if (nt > 16) nt = 16;
   if (nt < 1) nt = 1;
   if ((int64_t)nt > n) nt = (int)std::max<int64_t>(n, 1);
@@ -52,19 +75,39 @@ void parallel_for(int64_t n, const std::function<void(int64_t)>& fn, int max_thr
     for (int64_t i = 0; i < n; ++i) fn(i);
     return;
   }
+  // An exception inside a worker (an allocation that fails) is carried over to the calling thread; one
+  // thrown while the threads are being created (std::system_error) leaves after the ones that exist joined.
   std::vector<std::thread> th;
-  for (int w = 0; w < nt; ++w)
-    th.emplace_back([=, &fn]() {
+  std::vector<std::exception_ptr> err(nt);
+  std::exception_ptr spawn_err;
+  try {
+    th.reserve(nt);
+    for (int w = 0; w < nt; ++w)
+      th.emplace_back([=, &fn, &err]() {
+        try {
+          const int64_t lo = n * w / nt, hi = n * (w + 1) / nt;
+          for (int64_t i = lo; i < hi; ++i) fn(i);
+        } catch (...) {
+          err[w] = std::current_exception();
+        }
+      });
+  } catch (...) {
+    spawn_err = std::current_exception();
+  }
+  const size_t started = th.size();
+  for (auto& t : th) t.join();
+  if (spawn_err) {
+    // the chunks of the threads that never started still have to run
+    for (int w = (int)started; w < nt; ++w) {
       const int64_t lo = n * w / nt, hi = n * (w + 1) / nt;
       for (int64_t i = lo; i < hi; ++i) fn(i);
-    });
-  for (auto& t : th) t.join();
+    }
+  }
+  for (auto& e : err)
+    if (e) std::rethrow_exception(e);
 }
 
-bool use_simt_experts(int dtype) {
-  static const int force = std::getenv("CMOE_FORCE_SIMT") ? std::atoi(std::getenv("CMOE_FORCE_SIMT")) : 0;
-  return dtype != CMOE_BF16 || force != 0;
-}
+bool use_simt_experts(int dtype) { return dtype != CMOE_BF16 || tuning().force_simt != 0; }
 
 int gemm_tile(const Engine& e, int64_t T, int which) {
   return use_simt_experts(e.dtype) ? simt_gemm_tile(which) : bf16_gemm_tile(which, e, T);
@@ -296,6 +339,8 @@ struct cmoe_layer {
   bool has_u = false, has_b = false;
   bool uploaded = false;
   bool in_hier = false;
+  bool baseline = true;                        // the dense single-group copy is packed and uploaded too
+  int64_t calib_routed = -1, calib_used = -1;  // cmoe_hier_build: calibration tokens routed to / used for this expert
   Engine e_moe, e_dense;
   float* d_u = nullptr;
   float* d_b = nullptr;
@@ -309,8 +354,19 @@ struct cmoe_hier {
   std::vector<uint8_t> lin_rows;               // [IL][d] outer router, rows = outer experts
   std::vector<float> lin_off;
   bool uploaded = false;
+  bool owns_experts = false;                   // built by cmoe_hier_build: destroyed with the hierarchy
+  bool baseline = true;
   Engine e_moe, e_dense;
 };
+
+// Every entry point that can reach an allocation or a thread runs its body between these two: nothing
+// may propagate through the C boundary.
+#define CMOE_TRY try {
+#define CMOE_CATCH                                                                             \
+  }                                                                                            \
+  catch (const std::bad_alloc&) { return fail(CMOE_ENOMEM, "out of host memory"); }            \
+  catch (const std::exception& ex) { return fail(CMOE_EINVAL, "internal error: %s", ex.what()); } \
+  catch (...) { return fail(CMOE_EINVAL, "internal error"); }
 
 static int check_config(const cmoe_config* c) {
   if (!c) return fail(CMOE_EINVAL, "config is null");
@@ -405,6 +461,9 @@ static int build_common(const cmoe_config* cfg, const float* w_gate, const float
       L->rep_neuron.assign(rep_in, rep_in + n_r);
     } else {
       if (!calib_x || q < 1) return fail(CMOE_EINVAL, "calibration set is null or empty");
+      if (q > (int64_t)0x7fffffff / std::max(cfg->k_act, 1)) return fail(CMOE_EINVAL, "calibration set too large");
+      for (int64_t i = 0; i < q * d; ++i)
+        if (!std::isfinite(calib_x[i])) return fail(CMOE_EINVAL, "calibration token %lld has a non-finite entry", (long long)(i / d));
       if (cfg->k_act < 1 || cfg->k_act > d_ff) return fail(CMOE_EINVAL, "need 1 <= k_act <= d_ff");
       if (cfg->kmeans_iters < 1) return fail(CMOE_EINVAL, "kmeans_iters must be >= 1");
       if (cfg->dist_mode != 0 && cfg->dist_mode != 1) return fail(CMOE_EINVAL, "dist_mode must be 0 or 1");
@@ -447,6 +506,10 @@ static int build_common(const cmoe_config* cfg, const float* w_gate, const float
     fill_flat_engines(L.get());
   } catch (const std::bad_alloc&) {
     return fail(CMOE_ENOMEM, "out of host memory while packing");
+  } catch (const std::exception& ex) {
+    return fail(CMOE_EINVAL, "internal error: %s", ex.what());
+  } catch (...) {
+    return fail(CMOE_EINVAL, "internal error");
   }
   *out = L.release();
   return CMOE_OK;
@@ -473,6 +536,8 @@ int cmoe_profile_activations(const cmoe_config* cfg, const float* w_gate, const 
   if (!w_gate || !w_up || !calib_x || !active_out) return fail(CMOE_EINVAL, "null argument");
   if (q < 1) return fail(CMOE_EINVAL, "calibration set is empty");
   if (cfg->k_act < 1 || cfg->k_act > cfg->d_ff) return fail(CMOE_EINVAL, "need 1 <= k_act <= d_ff");
+  for (int64_t i = 0; i < q * cfg->d_model; ++i)
+    if (!std::isfinite(calib_x[i])) return fail(CMOE_EINVAL, "calibration token %lld has a non-finite entry", (long long)(i / cfg->d_model));
   try {
     RoundedDense rd;
     rd.from_fp32(cfg->dtype, cfg->d_model, cfg->d_ff, w_gate, w_up, w_up);   // the down matrix plays no part here
@@ -486,6 +551,10 @@ int cmoe_profile_activations(const cmoe_config* cfg, const float* w_gate, const 
     }
   } catch (const std::bad_alloc&) {
     return fail(CMOE_ENOMEM, "out of host memory");
+  } catch (const std::exception& ex) {
+    return fail(CMOE_EINVAL, "internal error: %s", ex.what());
+  } catch (...) {
+    return fail(CMOE_EINVAL, "internal error");
   }
   return CMOE_OK;
 }
@@ -500,6 +569,10 @@ int cmoe_balanced_assignment(const double* dist, int32_t n, int32_t n_r, int32_t
       return fail(CMOE_EINVAL, "%s", msg.c_str());
   } catch (const std::bad_alloc&) {
     return fail(CMOE_ENOMEM, "out of host memory");
+  } catch (const std::exception& ex) {
+    return fail(CMOE_EINVAL, "internal error: %s", ex.what());
+  } catch (...) {
+    return fail(CMOE_EINVAL, "internal error");
   }
   return CMOE_OK;
 }
@@ -530,7 +603,9 @@ int cmoe_set_gate_params(cmoe_layer* L, const float* u, const float* b) {
   }
   L->e_moe.r.use_gate = (L->has_u || L->has_b) ? 1 : 0;
   if (L->uploaded) {
-    hipError_t e = hipMemcpy(L->d_u, L->u.data(), sizeof(float) * L->n_r, hipMemcpyHostToDevice);
+    // a forward still in flight on some stream may be reading the old values: wait for the device first
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(L->d_u, L->u.data(), sizeof(float) * L->n_r, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(L->d_b, L->b.data(), sizeof(float) * L->n_r, hipMemcpyHostToDevice);
     if (e != hipSuccess) return fail_hip(e, "copying gate parameters");
   }
@@ -555,6 +630,7 @@ int cmoe_update_bias(cmoe_layer* L, const int32_t* counts, float gamma) {
     total += counts[j];
   }
   if (total == 0) return CMOE_OK;
+  CMOE_TRY
   std::vector<float> b(L->b.begin(), L->b.begin() + L->n_r);
   for (int j = 0; j < L->n_r; ++j) {
     const int64_t c = (int64_t)counts[j] * L->n_r;       // p_j > 1/N_r  <=>  counts_j * N_r > total
@@ -563,6 +639,7 @@ int cmoe_update_bias(cmoe_layer* L, const int32_t* counts, float gamma) {
   }
   std::vector<float> u(L->u.begin(), L->u.begin() + L->n_r);
   return cmoe_set_gate_params(L, L->has_u ? u.data() : nullptr, b.data());
+  CMOE_CATCH
 }
 
 // device buffer of a flat layer: [moe W1][moe W2][dense W1][dense W2][router][moe groups][dense groups][u][b]
@@ -573,11 +650,11 @@ static FlatOffsets flat_offsets(const cmoe_layer* L) {
   auto take = [&](size_t bytes) { size_t r = off; off = align256(off + bytes); return r; };
   o.w1 = take(L->moe.w1.size());
   o.w2 = take(L->moe.w2.size());
-  o.dw1 = take(L->dense.w1.size());
-  o.dw2 = take(L->dense.w2.size());
+  o.dw1 = take(L->baseline ? L->dense.w1.size() : 0);
+  o.dw2 = take(L->baseline ? L->dense.w2.size() : 0);
   o.wr = take(L->router.size());
   o.g = take(sizeof(GroupDev) * L->moe.groups.size());
-  o.dg = take(sizeof(GroupDev) * L->dense.groups.size());
+  o.dg = take(L->baseline ? sizeof(GroupDev) * L->dense.groups.size() : 0);
   o.u = take(sizeof(float) * L->n_r);
   o.b = take(sizeof(float) * L->n_r);
   o.total = off;
@@ -588,7 +665,20 @@ size_t cmoe_packed_bytes(const cmoe_layer* L) { return L ? flat_offsets(L).total
 
 size_t cmoe_workspace_bytes(const cmoe_layer* L, int64_t max_tokens) {
   if (!L || max_tokens < 0) return 0;
-  return std::max(ws_layout(L->e_moe, max_tokens).total, ws_layout(L->e_dense, max_tokens).total);
+  const size_t moe = ws_layout(L->e_moe, max_tokens).total;
+  return L->baseline ? std::max(moe, ws_layout(L->e_dense, max_tokens).total) : moe;
+}
+
+int cmoe_set_baseline(cmoe_layer* L, int enabled) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (L->uploaded || L->in_hier) return fail(CMOE_ESTATE, "cmoe_set_baseline must come before cmoe_upload / cmoe_hier_create");
+  if (enabled && !L->baseline) return fail(CMOE_ESTATE, "the dense copy of this layer has been released");
+  if (!enabled && L->baseline) {
+    L->baseline = false;
+    std::vector<uint8_t>().swap(L->dense.w1);       // release the host copy: it is never uploaded
+    std::vector<uint8_t>().swap(L->dense.w2);
+  }
+  return CMOE_OK;
 }
 
 static hipError_t h2d(void* dst, const void* src, size_t bytes, hipStream_t s) {
@@ -605,11 +695,11 @@ int cmoe_upload(cmoe_layer* L, void* dev_weights, void* hip_stream) {
   char* base = static_cast<char*>(dev_weights);
   hipError_t e = h2d(base + o.w1, L->moe.w1.data(), L->moe.w1.size(), s);
   if (e == hipSuccess) e = h2d(base + o.w2, L->moe.w2.data(), L->moe.w2.size(), s);
-  if (e == hipSuccess) e = h2d(base + o.dw1, L->dense.w1.data(), L->dense.w1.size(), s);
-  if (e == hipSuccess) e = h2d(base + o.dw2, L->dense.w2.data(), L->dense.w2.size(), s);
+  if (e == hipSuccess && L->baseline) e = h2d(base + o.dw1, L->dense.w1.data(), L->dense.w1.size(), s);
+  if (e == hipSuccess && L->baseline) e = h2d(base + o.dw2, L->dense.w2.data(), L->dense.w2.size(), s);
   if (e == hipSuccess) e = h2d(base + o.wr, L->router.data(), L->router.size(), s);
   if (e == hipSuccess) e = h2d(base + o.g, L->moe.groups.data(), sizeof(GroupDev) * L->moe.groups.size(), s);
-  if (e == hipSuccess) e = h2d(base + o.dg, L->dense.groups.data(), sizeof(GroupDev) * L->dense.groups.size(), s);
+  if (e == hipSuccess && L->baseline) e = h2d(base + o.dg, L->dense.groups.data(), sizeof(GroupDev) * L->dense.groups.size(), s);
   if (e == hipSuccess) e = h2d(base + o.u, L->u.data(), sizeof(float) * L->n_r, s);
   if (e == hipSuccess) e = h2d(base + o.b, L->b.data(), sizeof(float) * L->n_r, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
@@ -712,6 +802,7 @@ int cmoe_dense_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev,
                        size_t workspace_bytes, void* hip_stream) {
   if (!L) return fail(CMOE_EINVAL, "layer is null");
   if (!L->uploaded) return fail(CMOE_ESTATE, "cmoe_upload has not been called");
+  if (!L->baseline) return fail(CMOE_ESTATE, "the layer was uploaded without its dense baseline (cmoe_set_baseline)");
   return run_engine(L->e_dense, x_dev, T, y_dev, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes,
                     static_cast<hipStream_t>(hip_stream));
 }
@@ -720,6 +811,7 @@ int cmoe_forward_timed(cmoe_layer* L, int dense, const void* x_dev, int64_t T, v
                        size_t workspace_bytes, void* hip_stream, float* stage_ms) {
   if (!L) return fail(CMOE_EINVAL, "layer is null");
   if (!L->uploaded) return fail(CMOE_ESTATE, "cmoe_upload has not been called");
+  if (dense && !L->baseline) return fail(CMOE_ESTATE, "the layer was uploaded without its dense baseline (cmoe_set_baseline)");
   Engine e = dense ? L->e_dense : L->e_moe;
   if (!L->has_u) e.gate_u = nullptr;
   if (!L->has_b) e.gate_b = nullptr;
@@ -739,6 +831,8 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     if (experts[e]->uploaded || experts[e]->in_hier) return fail(CMOE_ESTATE, "expert %d is already uploaded or owned", e);
     if (std::memcmp(&experts[e]->cfg, &experts[0]->cfg, sizeof(cmoe_config)) != 0)
       return fail(CMOE_EINVAL, "expert %d has a different configuration", e);
+    if (experts[e]->baseline != experts[0]->baseline)
+      return fail(CMOE_EINVAL, "expert %d differs from expert 0 in cmoe_set_baseline", e);
   }
   const cmoe_config& c = experts[0]->cfg;
   const int n_r = c.n_experts - c.n_shared;
@@ -753,6 +847,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     H->cfg = c;
     H->n_outer = n_outer;
     H->outer_top_k = outer_top_k;
+    H->baseline = experts[0]->baseline;
     const int d = c.d_model;
     const size_t es = elem_size(c.dtype), row_bytes = (size_t)d * es;
     pack_router_rows(H->router, c.dtype, d, n_outer * n_r);
@@ -823,9 +918,101 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     for (int e = 0; e < n_outer; ++e) experts[e]->in_hier = true;
   } catch (const std::bad_alloc&) {
     return fail(CMOE_ENOMEM, "out of host memory");
+  } catch (const std::exception& ex) {
+    return fail(CMOE_EINVAL, "internal error: %s", ex.what());
+  } catch (...) {
+    return fail(CMOE_EINVAL, "internal error");
   }
   *out = H.release();
   return CMOE_OK;
+}
+
+// Sec. 4.4 end to end: route the calibration tokens through the outer router on the host, restructure every
+// outer expert on the tokens that reach it, and tie the results together.
+int cmoe_hier_build(const cmoe_config* cfg, int32_t n_outer, int32_t outer_top_k, const float* const* w_gate,
+                    const float* const* w_up, const float* const* w_down, const float* w_router,
+                    const float* logit_offset, const float* calib_x, int64_t q, int32_t min_tokens, int on_gpu,
+                    int with_baseline, cmoe_hier** out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!w_gate || !w_up || !w_down || !w_router || !calib_x || !out) return fail(CMOE_EINVAL, "null argument");
+  if (n_outer < 1 || n_outer > IL) return fail(CMOE_EINVAL, "need 1 <= n_outer <= %d", IL);
+  if (outer_top_k < 1 || outer_top_k > n_outer || outer_top_k > MAX_OUTER_TOPK) return fail(CMOE_EINVAL, "bad outer_top_k");
+  if (q < 1) return fail(CMOE_EINVAL, "calibration set is empty");
+  for (int e = 0; e < n_outer; ++e)
+    if (!w_gate[e] || !w_up[e] || !w_down[e]) return fail(CMOE_EINVAL, "weights of outer expert %d are null", e);
+  const int d = cfg->d_model;
+  const int64_t need = std::max<int64_t>(min_tokens > 0 ? min_tokens : 64, cfg->k_act);
+  std::vector<cmoe_layer*> layers;
+  auto drop = [&]() { for (cmoe_layer* L : layers) delete L; };
+  CMOE_TRY
+  // outer routing of the calibration tokens: logits in double precision on the dtype-rounded operands,
+  // top-k with ties to the lowest expert id (the same rule as the forward)
+  auto rnd = [&](float v) { return cfg->dtype == CMOE_BF16 ? host_bf16_to_f32(host_f32_to_bf16(v)) : v; };
+  std::vector<double> wr((size_t)d * n_outer);
+  for (size_t i = 0; i < wr.size(); ++i) wr[i] = (double)rnd(w_router[i]);
+  std::vector<std::vector<int64_t>> rows(n_outer);
+  for (int64_t t = 0; t < q; ++t) {
+    double logit[IL];
+    for (int e = 0; e < n_outer; ++e) logit[e] = logit_offset ? (double)logit_offset[e] : 0.0;
+    for (int k = 0; k < d; ++k) {
+      const float xv = calib_x[(size_t)t * d + k];
+      if (!std::isfinite(xv)) return fail(CMOE_EINVAL, "calibration token %lld has a non-finite entry", (long long)t);
+      const double x = (double)rnd(xv);
+      for (int e = 0; e < n_outer; ++e) logit[e] += x * wr[(size_t)k * n_outer + e];
+    }
+    uint32_t taken = 0u;
+    for (int i = 0; i < outer_top_k; ++i) {
+      int best = -1;
+      for (int e = 0; e < n_outer; ++e)
+        if (((taken >> e) & 1u) == 0u && (best < 0 || logit[e] > logit[best])) best = e;
+      taken |= 1u << best;
+      rows[best].push_back(t);
+    }
+  }
+  for (int e = 0; e < n_outer; ++e) {
+    const std::vector<int64_t>& r = rows[e];
+    const bool whole = (int64_t)r.size() < need;
+    const int64_t n_e = whole ? q : (int64_t)r.size();
+    std::vector<float> xs;
+    if (!whole) {
+      xs.resize((size_t)n_e * d);
+      for (int64_t i = 0; i < n_e; ++i) std::memcpy(&xs[(size_t)i * d], calib_x + (size_t)r[i] * d, sizeof(float) * d);
+    }
+    cmoe_layer* L = nullptr;
+    rc = build_common(cfg, w_gate[e], w_up[e], w_down[e], whole ? calib_x : xs.data(), n_e, nullptr, nullptr, &L, on_gpu != 0);
+    if (rc) {
+      drop();
+      return rc;
+    }
+    L->calib_routed = (int64_t)r.size();
+    L->calib_used = n_e;
+    layers.push_back(L);
+    if (!with_baseline) (void)cmoe_set_baseline(L, 0);
+  }
+  cmoe_hier* H = nullptr;
+  rc = cmoe_hier_create(layers.data(), n_outer, outer_top_k, w_router, logit_offset, &H);
+  if (rc) {
+    drop();
+    return rc;
+  }
+  H->owns_experts = true;
+  *out = H;
+  return CMOE_OK;
+  }
+  catch (const std::bad_alloc&) { drop(); return fail(CMOE_ENOMEM, "out of host memory"); }
+  catch (const std::exception& ex) { drop(); return fail(CMOE_EINVAL, "internal error: %s", ex.what()); }
+  catch (...) { drop(); return fail(CMOE_EINVAL, "internal error"); }
+}
+
+const cmoe_layer* cmoe_hier_expert(const cmoe_hier* H, int32_t e, int64_t* calib_routed, int64_t* calib_used) {
+  if (!H || e < 0 || e >= H->n_outer) {
+    (void)fail(CMOE_EINVAL, "no such outer expert");
+    return nullptr;
+  }
+  if (calib_routed) *calib_routed = H->experts[e]->calib_routed;
+  if (calib_used) *calib_used = H->experts[e]->calib_used;
+  return H->experts[e];
 }
 
 // device buffer of a hierarchy:
@@ -836,7 +1023,11 @@ static HierOffsets hier_offsets(const cmoe_hier* H) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t r = off; off = align256(off + bytes); return r; };
   size_t w1 = 0, w2 = 0, dw1 = 0, dw2 = 0;
-  for (auto* L : H->experts) { w1 += L->moe.w1.size(); w2 += L->moe.w2.size(); dw1 += L->dense.w1.size(); dw2 += L->dense.w2.size(); }
+  for (auto* L : H->experts) {
+    w1 += L->moe.w1.size();
+    w2 += L->moe.w2.size();
+    if (H->baseline) { dw1 += L->dense.w1.size(); dw2 += L->dense.w2.size(); }
+  }
   o.w1 = take(w1);
   o.w2 = take(w2);
   o.dw1 = take(dw1);
@@ -855,12 +1046,14 @@ size_t cmoe_hier_packed_bytes(const cmoe_hier* H) { return H ? hier_offsets(H).t
 
 size_t cmoe_hier_workspace_bytes(const cmoe_hier* H, int64_t max_tokens) {
   if (!H || max_tokens < 0) return 0;
-  return std::max(ws_layout(H->e_moe, max_tokens).total, ws_layout(H->e_dense, max_tokens).total);
+  const size_t moe = ws_layout(H->e_moe, max_tokens).total;
+  return H->baseline ? std::max(moe, ws_layout(H->e_dense, max_tokens).total) : moe;
 }
 
 int cmoe_hier_upload(cmoe_hier* H, void* dev_weights, void* hip_stream) {
   if (!H || !dev_weights) return fail(CMOE_EINVAL, "hierarchy or device buffer is null");
   if (((uintptr_t)dev_weights & 255) != 0) return fail(CMOE_EINVAL, "device weight buffer must be 256-byte aligned");
+  CMOE_TRY
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const HierOffsets o = hier_offsets(H);
   char* base = static_cast<char*>(dev_weights);
@@ -878,12 +1071,14 @@ int cmoe_hier_upload(cmoe_hier* H, void* dev_weights, void* hip_stream) {
     for (const GroupDev& gd : L->dense.groups) g_dense.push_back(GroupDev{gd.width_pad, (int32_t)(gd.w1_row0 + drow_shift), gd.w2_off + del_shift});
     if (e == hipSuccess) e = h2d(base + o.w1 + w1, L->moe.w1.data(), L->moe.w1.size(), s);
     if (e == hipSuccess) e = h2d(base + o.w2 + w2, L->moe.w2.data(), L->moe.w2.size(), s);
-    if (e == hipSuccess) e = h2d(base + o.dw1 + dw1, L->dense.w1.data(), L->dense.w1.size(), s);
-    if (e == hipSuccess) e = h2d(base + o.dw2 + dw2, L->dense.w2.data(), L->dense.w2.size(), s);
+    if (e == hipSuccess && H->baseline) e = h2d(base + o.dw1 + dw1, L->dense.w1.data(), L->dense.w1.size(), s);
+    if (e == hipSuccess && H->baseline) e = h2d(base + o.dw2 + dw2, L->dense.w2.data(), L->dense.w2.size(), s);
     w1 += L->moe.w1.size();
     w2 += L->moe.w2.size();
-    dw1 += L->dense.w1.size();
-    dw2 += L->dense.w2.size();
+    if (H->baseline) {
+      dw1 += L->dense.w1.size();
+      dw2 += L->dense.w2.size();
+    }
     u.insert(u.end(), L->u.begin(), L->u.end());
     b.insert(b.end(), L->b.begin(), L->b.end());
   }
@@ -912,6 +1107,7 @@ int cmoe_hier_upload(cmoe_hier* H, void* dev_weights, void* hip_stream) {
   dn.lin_off = m.lin_off;
   H->uploaded = true;
   return CMOE_OK;
+  CMOE_CATCH
 }
 
 int cmoe_hier_forward(cmoe_hier* H, const void* x_dev, int64_t T, void* y_dev, int32_t* outer_idx_dev,
@@ -926,6 +1122,7 @@ int cmoe_hier_dense_forward(cmoe_hier* H, const void* x_dev, int64_t T, void* y_
                             size_t workspace_bytes, void* hip_stream) {
   if (!H) return fail(CMOE_EINVAL, "hierarchy is null");
   if (!H->uploaded) return fail(CMOE_ESTATE, "cmoe_hier_upload has not been called");
+  if (!H->baseline) return fail(CMOE_ESTATE, "the hierarchy was built without its un-restructured baseline");
   return run_engine(H->e_dense, x_dev, T, y_dev, nullptr, nullptr, nullptr, nullptr, workspace_dev, workspace_bytes,
                     static_cast<hipStream_t>(hip_stream));
 }
@@ -934,14 +1131,28 @@ int cmoe_hier_forward_timed(cmoe_hier* H, int dense, const void* x_dev, int64_t 
                             size_t workspace_bytes, void* hip_stream, float* stage_ms) {
   if (!H) return fail(CMOE_EINVAL, "hierarchy is null");
   if (!H->uploaded) return fail(CMOE_ESTATE, "cmoe_hier_upload has not been called");
+  if (dense && !H->baseline) return fail(CMOE_ESTATE, "the hierarchy was built without its un-restructured baseline");
   return run_engine_timed(dense ? H->e_dense : H->e_moe, x_dev, T, y_dev, workspace_dev, workspace_bytes,
                           static_cast<hipStream_t>(hip_stream), stage_ms);
 }
 
 void cmoe_hier_destroy(cmoe_hier* H) {
   if (!H) return;
-  for (auto* L : H->experts) L->in_hier = false;
+  for (auto* L : H->experts) {
+    L->in_hier = false;
+    if (H->owns_experts) delete L;
+  }
   delete H;
+}
+
+int cmoe_set_tuning(const char* name, int value) {
+  if (!name) return fail(CMOE_EINVAL, "name is null");
+  for (const TuningField& f : kTuningFields)
+    if (std::strcmp(name, f.name) == 0) {
+      tuning().*(f.field) = value;
+      return CMOE_OK;
+    }
+  return fail(CMOE_EINVAL, "unknown tuning switch '%s'", name);
 }
 
 const char* cmoe_last_error(void) { return g_err.c_str(); }

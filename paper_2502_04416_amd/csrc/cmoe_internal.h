@@ -119,6 +119,26 @@ struct Engine {
   bool direct_output() const { return S_dyn == 0 && n_always == 1; }
 };
 
+// Tuning switches: every field defaults to the measured best; the environment variables of the same
+// names (CMOE_GEMM1_CFG, ...) are read once, when the library is first used, and cmoe_set_tuning changes a
+// field afterwards (so that an A/B comparison can run inside one process).  The forward path reads plain ints.
+struct Tuning {
+  int gemm1_cfg = -1;      // tile shape of the gate/up contraction (index into the table of gemm_bf16.hip); -1: per batch
+  int gemm2_cfg = -1;      // same for the down contraction
+  int xcd_remap = 1;       // 0: workgroups take work items in launch order instead of per-XCD shares
+  int splitk = 1;          // 0: never split K
+  int zero_pad = 1;        // 0: tile rows past the end of a group repeat its last row instead of reading zeros
+  int decode_fuse = 1;     // 0: separate down and combine kernels for batches of at most 32 tokens
+  int front_shared = 1;    // 0: the shared expert's gate/up units stay in the gate/up launch at decode
+  int force_simt = 0;      // 1: bf16 layers run the plain FMA kernels
+  int ldpad = 0;           // extra elements in the row stride of a row-major (fp32) packed gate/up matrix
+  int host_threads = 0;    // worker threads of the host-side construction (0: hardware threads, at most 16)
+  int skip_rows = 1;       // 0: the gate/up contraction multiplies the 32-row blocks past the end of a segment too
+  int decode_split = -1;   // K split of the decode gate/up units across workgroups (-1: chosen per batch)
+  int ws_down = 1;         // 0: never use the weight-stationary down contraction
+};
+Tuning& tuning();
+
 size_t elem_size(int dtype);
 // Row stride of a row-major (fp32) packed gate/up matrix for model width d: d plus the optional pad of the
 // CMOE_LDPAD tuning variable (rows a power of two apart all map to the same L2 channel).

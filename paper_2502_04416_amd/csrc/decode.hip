@@ -226,12 +226,11 @@ bool decode_path_ok(const Engine& e, int64_t T) {
 }
 
 // The fused down + combine kernel serves every routed bf16 batch of at most 32 tokens with more than one slot
-// per token, whichever kernel produced the hidden activations (CMOE_DECODE_FUSE=0 selects the separate
+// per token, whichever kernel produced the hidden activations (the decode_fuse tuning switch selects the separate
 // kernels, for comparison).
 constexpr int DOWN_COMBINE_MAX_T = 32;
 bool decode_fuses_combine(const Engine& e, int64_t T) {
-  static const bool off = [] { const char* v = getenv("CMOE_DECODE_FUSE"); return v && v[0] == '0'; }();
-  if (off || use_simt_experts(e.dtype) || e.dtype != 1 || T < 1 || T > DOWN_COMBINE_MAX_T || e.d % 16 != 0) return false;
+  if (tuning().decode_fuse == 0 || use_simt_experts(e.dtype) || e.dtype != 1 || T < 1 || T > DOWN_COMBINE_MAX_T || e.d % 16 != 0) return false;
   return !(e.G == 1 && e.n_always == 1) && e.S_all() > 1;
 }
 

@@ -419,7 +419,7 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
 }
 
 // ---- tile configurations ---------------------------------------------------------------------
-// Tile shapes the tuning environment variables CMOE_GEMM1_CFG / CMOE_GEMM2_CFG can select.
+// Tile shapes (the tuning switches gemm1_cfg / gemm2_cfg select one by index).
 // stages >= 2: ring of whole K tiles; stages == 0: ring of five half tiles.
 struct TileCfg { int bm, bn, wgm, wgn, stages, bk; };
 static const TileCfg kCfgs[] = {
@@ -444,15 +444,8 @@ static const TileCfg kCfgs[] = {
 };
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
-static int env_int(const char* name, int dflt) {
-  const char* v = std::getenv(name);
-  return v ? std::atoi(v) : dflt;
-}
-// Which tile shape for contraction `which` (1: gate/up, 2: down) of a batch of T tokens.  The environment
-// is read at every call (a getenv is nothing next to a kernel launch) so that a tuning script can switch
-// tile shapes inside one process.  Defaults: 256x256 tiles on the half-tile ring for the long-K gate/up
-// contraction; for the short-K down contraction 256x256 tiles when there are enough of them to fill the
-// chip (>= 256), else 128x128 tiles with two workgroups per CU.
+// Which tile shape for contraction `which` (1: gate/up, 2: down) of a batch of T tokens: the tuning switches
+// gemm1_cfg / gemm2_cfg when set, else the models below.
 // Tile shape of the gate/up contraction: the one with the lowest estimated time = rounds x time per round,
 // rounds = ceil(tiles / workgroup slots on the chip).  Relative times per round measured on the
 // LLaMA-shaped layers (K = d for every shape, so the ratios carry over), in units of the eight-wave
@@ -538,9 +531,8 @@ static int cfg_index(int which, const Engine& e, int64_t T) {
       }
     }
   }
-  int c = env_int(which == 1 ? "CMOE_GEMM1_CFG" : "CMOE_GEMM2_CFG", dflt);
-  if (c < 0 || c >= kNumCfgs) c = dflt;
-  return c;
+  const int forced = which == 1 ? tuning().gemm1_cfg : tuning().gemm2_cfg;
+  return (forced >= 0 && forced < kNumCfgs) ? forced : dflt;
 }
 
 // which = 1: BM of gate/up, 2: BM of down, 3: BN of gate/up (packed rows), 4: BN of down
@@ -576,7 +568,7 @@ static int64_t splitk_rows(const Engine& e, int64_t T) { return T * e.S_all(); }
 static int splitk_ldp(const Engine& e, int which) { return which == 1 ? 2 * e.max_width_pad : e.d; }
 
 int bf16_splitk(const Engine& e, int64_t T, int which) {
-  if (T < 1 || T > 1024 || env_int("CMOE_SPLITK", 1) == 0) return 1;
+  if (T < 1 || T > 1024 || tuning().splitk == 0) return 1;
   const TileCfg& c = kCfgs[cfg_index(which, e, T)];
   const int64_t tiles = est_tiles(e, T, which, c.bm, c.bn);
   int k_min = e.d;
@@ -692,7 +684,7 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
 
 hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                hipStream_t s, int stage) {
-  const int remap = env_int("CMOE_XCD_REMAP", 1);
+  const int remap = tuning().xcd_remap;
   GemmArgs a;
   a.groups = e.groups;
   a.seg_off = reinterpret_cast<const int32_t*>(ws + L.seg_off);
@@ -704,7 +696,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.xcd_remap = remap;
-  a.zero_pad = env_int("CMOE_ZERO_PAD", 1);
+  a.zero_pad = tuning().zero_pad;
   // gate/up
   a.A = static_cast<const bf16_t*>(x);
   a.B = static_cast<const bf16_t*>(e.w1);

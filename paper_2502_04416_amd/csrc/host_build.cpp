@@ -10,6 +10,7 @@
 #include <limits>
 #include <numeric>
 #include <queue>
+#include <string>
 #include <vector>
 
 namespace cmoe {
@@ -237,7 +238,15 @@ bool host_construct_from_active(const cmoe_config& cfg, int64_t q, const int32_t
   // feature vectors c_i as sorted token lists; rates mu_i (App. A.2 step 3)
   std::vector<std::vector<int32_t>> feat(d_ff);
   for (int64_t t = 0; t < q; ++t)
-    for (int k = 0; k < k_act; ++k) feat[active[(size_t)t * k_act + k]].push_back((int32_t)t);
+    for (int k = 0; k < k_act; ++k) {
+      // (a token with fewer than K_a comparable magnitudes, i.e. non-finite hidden states, has no valid list)
+      const int32_t i = active[(size_t)t * k_act + k];
+      if (i < 0 || i >= d_ff) {
+        if (msg) *msg = "calibration token " + std::to_string(t) + " has no valid top-K_a list (non-finite hidden states?)";
+        return false;
+      }
+      feat[i].push_back((int32_t)t);
+    }
   std::vector<double> mu(d_ff);
   for (int i = 0; i < d_ff; ++i) {
     mu[i] = (double)feat[i].size() / (double)q;

@@ -704,8 +704,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
 }
 
 bool decode_front_runs_shared(const Engine& e, int64_t T) {
-  static const bool off = [] { const char* v = getenv("CMOE_FRONT_SHARED"); return v && v[0] == '0'; }();
-  return !off && T <= FRONT_SCORE_MAX_T && e.n_always == 1 && decode_front_ok(e, T) && decode_path_ok(e, T);
+  return tuning().front_shared != 0 && T <= FRONT_SCORE_MAX_T && e.n_always == 1 && decode_front_ok(e, T) && decode_path_ok(e, T);
 }
 
 hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,

@@ -21,9 +21,28 @@ def tokenwise_rel_err(y, y_ref):
     return np.abs(y - y_ref).max(axis=1) / den
 
 
-def check_flat(cfg, weights, part, x, out, u=None, b=None, sample=None, score_tol=None, abs_score=False):
+def tail_tokens(topk, n_groups, rows=128, extra=None):
+    """Tokens that sit in the last `rows` rows of every expert's segment (segments are token-ascending, so
+    these are the last tokens that selected the expert) and of the batch itself (the always-on group), i.e.
+    the ragged last row tile of every group, merged with `extra`."""
+    topk = np.asarray(topk)
+    T = topk.shape[0]
+    keep = set(range(max(0, T - rows), T))
+    flat = topk.reshape(T, -1)
+    for g in range(n_groups):
+        toks = np.nonzero((flat == g).any(axis=1))[0]
+        keep.update(toks[-rows:].tolist())
+    if extra is not None:
+        keep.update(int(t) for t in extra)
+    return np.array(sorted(keep), dtype=np.int64)
+
+
+def check_flat(cfg, weights, part, x, out, u=None, b=None, sample=None, score_tol=None, abs_score=False,
+               exact_ties_strict=False):
     """out: dict from binding.Layer.forward.  sample: token indices whose outputs are compared
-    (None = all).  Returns a small report dict."""
+    (None = all).  exact_ties_strict: a token whose k-th and (k+1)-th keys are *equal* (two experts with
+    the same representative neuron) is not excused: the lower expert id has to win.  Returns a small
+    report dict."""
     wg, wu, wd = weights
     T = x.shape[0]
     order, reps = part["neuron_order"], part["rep_neuron"]
@@ -36,6 +55,8 @@ def check_flat(cfg, weights, part, x, out, u=None, b=None, sample=None, score_to
         key = O.softmax_rows(skey) + (0.0 if b is None else np.asarray(b, dtype=np.float64)[None, :])
     sel, gap = O.select_top_k(key, cfg.top_k)
     excused = gap < GAP_EPS
+    if exact_ties_strict:
+        excused &= gap != 0.0
     strict = ~excused
     assert np.array_equal(out["topk"][strict], sel[strict]), \
         "expert indices differ on %d tokens with gap >= 1e-5" % int((out["topk"][strict] != sel[strict]).any(axis=1).sum())
@@ -61,7 +82,8 @@ def check_flat(cfg, weights, part, x, out, u=None, b=None, sample=None, score_to
     err = tokenwise_rel_err(out["y"][idx], ref["y"])
     tol = TOL[cfg.dtype]
     assert err.max() <= tol, "max per-token relative error %g > %g (token %d)" % (err.max(), tol, idx[int(err.argmax())])
-    return {"near_ties": int(excused.sum()), "max_rel_err": float(err.max()), "score_err": float(s_err),
+    return {"near_ties": int(excused.sum()), "exact_ties": int((gap == 0.0).sum()), "checked_tokens": int(len(idx)),
+            "max_rel_err": float(err.max()), "score_err": float(s_err),
             "min_gap": float(gap.min()) if T else np.inf, "union": int((want_counts > 0).sum())}
 
 

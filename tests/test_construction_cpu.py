@@ -210,3 +210,65 @@ def test_profile_activations_on_the_host_matches_the_oracle(dtype):
     assert active.shape == (x.shape[0], cfg.k_act)
     for t in range(x.shape[0]):
         assert set(active[t].tolist()) == set(np.nonzero(a[t])[0].tolist())
+
+
+def _hier_inputs(dtype="bf16", n_outer=4, n_calib=400):
+    cfg = synth.scaled(synth.CONFIGS[4], d_model=64, d_ff=384, n_experts=8, n_shared=2, top_k=2, dtype=dtype,
+                       n_centres=8, n_calib=n_calib, k_act=12, n_outer=n_outer, outer_top_k=2)
+    w_router, offsets = synth.make_outer_router(cfg)
+    ws = [synth.make_outer_expert_weights(cfg, e) for e in range(n_outer)]
+    calib = synth.make_token_source(cfg).calibration()
+    return cfg, w_router, offsets, ws, calib
+
+
+@pytest.mark.parametrize("dtype,min_tokens", [("bf16", 64), ("fp32", 150)])
+def test_hier_build_matches_the_oracle_per_outer_expert(dtype, min_tokens):
+    """cmoe_hier_build (Sec. 4.4): the library routes the calibration tokens through the outer router and
+    restructures each outer expert on the tokens it receives.  Against the oracle's hier_build: the same
+    number of tokens per expert (Zipf-skewed offsets; with min_tokens = 150 the least loaded experts fall back
+    to the whole set), and per expert what is unique in a construction: rates, the shared set, the cost of
+    the optimal assignment, representatives that are valid in the library's own clusters."""
+    cfg, w_router, offsets, ws, calib = _hier_inputs(dtype)
+    h = binding.cmoe_hier_build(binding.make_config(cfg), cfg.outer_top_k, [w[0] for w in ws], [w[1] for w in ws],
+                                [w[2] for w in ws], w_router, offsets, calib, min_tokens=min_tokens)
+    ref = O.hier_build([(w[0], w[1]) for w in ws], w_router, offsets, cfg.outer_top_k, calib, cfg.n_experts,
+                       cfg.n_shared, cfg.k_act, min_tokens=min_tokens)
+    assert sum(ref["routed"]) == calib.shape[0] * cfg.outer_top_k
+    fell_back = 0
+    m, n_s, n_r = cfg.m, cfg.n_shared, cfg.n_routed
+    for e in range(cfg.n_outer):
+        layer, routed, used = binding.cmoe_hier_expert(h, e)
+        assert routed == ref["routed"][e] and used == len(ref["tokens"][e])
+        fell_back += used != routed
+        part = binding.cmoe_export_partition(layer, cfg.d_ff, n_r)
+        p = ref["parts"][e]
+        assert np.array_equal(part["mu"], p["mu"].astype(np.float32))
+        assert np.array_equal(part["neuron_order"][: n_s * m], p["neuron_order"][: n_s * m])
+        assert sorted(part["neuron_order"].tolist()) == list(range(cfg.d_ff))
+        assert part["cost"] == pytest.approx(p["cost"], rel=1e-9)
+        a = O.atopk_matrix(O.hidden_states(calib[ref["tokens"][e]], ws[e][0], ws[e][1]), cfg.k_act)
+        for j in range(n_r):
+            members = np.sort(part["neuron_order"][(n_s + j) * m:(n_s + j + 1) * m])
+            feat = a[:, members].T.astype(float)
+            dd = np.sqrt(((feat - feat.mean(axis=0)[None, :]) ** 2).sum(axis=1))
+            rep = part["rep_neuron"][j]
+            assert rep in members and dd[list(members).index(rep)] <= dd.min() + 1e-9
+    assert (fell_back > 0) == (min_tokens == 150)
+    binding.cmoe_hier_destroy(h)
+
+
+def test_hier_build_argument_errors():
+    cfg, w_router, offsets, ws, calib = _hier_inputs(n_outer=2, n_calib=80)
+    args = ([w[0] for w in ws], [w[1] for w in ws], [w[2] for w in ws], w_router, offsets)
+    with pytest.raises(binding.CmoeError, match="outer_top_k"):
+        binding.cmoe_hier_build(binding.make_config(cfg), 3, *args, calib)
+    bad = calib.copy()
+    bad[5, 0] = np.nan
+    with pytest.raises(binding.CmoeError, match="token 5"):
+        binding.cmoe_hier_build(binding.make_config(cfg), 2, *args, bad)
+    c = binding.make_config(cfg)
+    c.k_act = cfg.d_ff + 1
+    with pytest.raises(binding.CmoeError, match="k_act"):
+        binding.cmoe_hier_build(c, 2, *args, calib)
+    with pytest.raises(binding.CmoeError):
+        binding.cmoe_hier_expert(None, 0)

@@ -8,7 +8,7 @@ import pytest
 
 from oracle import cmoe_oracle as O
 from paper_2502_04416_amd import synth
-from parity_utils import check_dense, check_flat, tokenwise_rel_err
+from parity_utils import check_dense, check_flat, tail_tokens, tokenwise_rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -280,20 +280,34 @@ def test_small_batches_without_decode_kernels(binding, T):
     layer.close()
 
 
+@pytest.fixture
+def tuning(binding):
+    """Set tuning switches of the library for one test; the defaults come back afterwards."""
+    touched = {}
+
+    def set_(name, value, default):
+        touched[name] = default
+        binding.cmoe_set_tuning(name, value)
+    yield set_
+    for name, default in touched.items():
+        binding.cmoe_set_tuning(name, default)
+
+
 @pytest.mark.parametrize("which", ["CMOE_GEMM1_CFG", "CMOE_GEMM2_CFG"])
 @pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
-def test_every_tile_shape(binding, monkeypatch, which, shape):
-    """Each tile shape of the bf16 contraction kernels forced on the gate/up or the down contraction (the
-    library reads the tuning variables at every call) of a layer whose segments end inside tiles: d = 328 (a
-    ragged last K tile at either tile depth), experts of 100 neurons, 333 tokens."""
+def test_every_tile_shape(binding, tuning, which, shape):
+    """Each tile shape of the bf16 contraction kernels forced on the gate/up or the down contraction of a
+    layer whose segments end inside tiles: d = 328 (a ragged last K tile at either tile depth), experts of
+    100 neurons, 333 tokens."""
     cfg = synth.scaled(synth.CONFIGS[1], d_model=328, d_ff=1200, n_experts=12, n_shared=2, top_k=3, n_centres=16)
     weights = synth.make_weights(cfg)
     part = synth.trivial_partition(cfg)
     x = synth.make_token_source(cfg).eval_batch(0, n=333)
     layer = _layer(binding, cfg, weights, part)
-    monkeypatch.setenv("CMOE_SPLITK", "0")          # (a K split adds the parts in another order)
+    tuning("CMOE_SPLITK", 0, 1)                     # (a K split adds the parts in another order)
+    tuning("CMOE_WS_DOWN", 0, 1)                    # (the forced shape must be the one that runs)
     ref = layer.forward(x)
-    monkeypatch.setenv(which, str(shape))
+    tuning(which, shape, -1)
     out = layer.forward(x)
     _say("%s=%d" % (which, shape), check_flat(cfg, weights, part, x, out))
     _say("%s=%d dense" % (which, shape), check_dense(cfg, weights, x, layer.dense_forward(x)))
@@ -439,27 +453,60 @@ def test_bias_update_loop_balances_the_load(binding):
 
 # ---------------------------------------------------------------------------------- full-size configs
 
-def _full(binding, ci, batches, n_sample=48, sizes=None, **scale):
+ALL_TOKENS_UP_TO = 8192     # the oracle evaluates a batch of this size in seconds
+
+
+def _full(binding, ci, batches, n_sample=48, sizes=None, part=None, **scale):
     """Full-size layer `ci` on its evaluation batches, or (sizes) on the first `n` tokens of batch 0;
-    `scale` replaces fields of the configuration (e.g. another expert split of the same dense layer)."""
+    `scale` replaces fields of the configuration (e.g. another expert split of the same dense layer).
+    The routing of every token is checked; outputs are compared for every token up to ALL_TOKENS_UP_TO
+    tokens, above that for a random sample plus the tokens of the ragged last row tile of every expert
+    segment (a defect confined to one tile of one group would sit there or in a full tile, which the random
+    tokens cover)."""
     cfg = synth.CONFIGS[ci] if not scale else synth.scaled(synth.CONFIGS[ci], **scale)
     weights = synth.make_weights(cfg)
-    part = synth.trivial_partition(cfg)
+    part = synth.trivial_partition(cfg) if part is None else part
     src = synth.make_token_source(cfg)
     layer = _layer(binding, cfg, weights, part)
     rng = np.random.Generator(np.random.PCG64(99 + ci))
     for bi in (batches if sizes is None else sizes):
         x = src.eval_batch(bi) if sizes is None else src.eval_batch(0, n=bi)
         T = x.shape[0]
-        sample = np.sort(rng.choice(T, size=min(T, n_sample), replace=False))
         out = layer.forward(x)
+        if T <= ALL_TOKENS_UP_TO:
+            sample = None
+        else:
+            sample = tail_tokens(out["topk"], cfg.n_routed, rows=256, extra=rng.choice(T, size=n_sample, replace=False))
         _say("cfg%d T=%d" % (ci, T), check_flat(cfg, weights, part, x, out, sample=sample))
-        _say("cfg%d T=%d dense" % (ci, T), check_dense(cfg, weights, x, layer.dense_forward(x), sample=sample[:16]))
+        dsample = None if T <= 2048 else np.sort(rng.choice(T, size=256, replace=False))
+        _say("cfg%d T=%d dense" % (ci, T), check_dense(cfg, weights, x, layer.dense_forward(x), sample=dsample))
     layer.close()
 
 
 def test_cfg1_full(binding):
     _full(binding, 1, [0, 1, 2])
+
+
+def test_cfg1_on_the_partition_the_library_constructs(binding):
+    """The forward on the partition cmoe_build produces from the calibration set (Sec. 4.1-4.2, Eq. 7), not an
+    arbitrary one: the analytically built router on clustered tokens gives skewed, ragged expert segments
+    (7 to 1700 tokens per expert at T = 2048), which is the workload the bench times.  The oracle runs on the
+    same partition through cmoe_export_partition; every token of every evaluation batch is compared."""
+    cfg = synth.CONFIGS[1]
+    weights = synth.make_weights(cfg)
+    src = synth.make_token_source(cfg)
+    layer = binding.Layer.build(cfg, *weights, src.calibration())
+    part = layer.export_partition()
+    for bi in range(len(cfg.eval_batches)):
+        x = src.eval_batch(bi)
+        out = layer.forward(x)
+        rep = check_flat(cfg, weights, part, x, out)
+        rep["counts_min_max"] = (int(out["counts"].min()), int(out["counts"].max()))
+        _say("cfg1 library partition T=%d" % x.shape[0], rep)
+        assert np.array_equal(out["y"], layer.forward(x)["y"])
+    x = src.eval_batch(2)
+    assert layer.forward(x)["counts"].max() > 3 * layer.forward(x)["counts"].mean()      # the skew is there
+    layer.close()
 
 
 def test_cfg1_mid_batches(binding):
@@ -470,8 +517,9 @@ def test_cfg1_mid_batches(binding):
 
 def test_cfg1_very_large_batch(binding):
     """32768 tokens (131072 slots, 1 GB of per-slot outputs): many rounds of every tile shape, 64-bit offsets
-    into the hidden and slot buffers; routing of every token and sampled outputs against the oracle."""
-    _full(binding, 1, None, n_sample=96, sizes=[32768])
+    into the hidden and slot buffers; routing of every token, and outputs of a random sample plus the last
+    row tile of every expert segment, against the oracle."""
+    _full(binding, 1, None, n_sample=256, sizes=[32768])
 
 
 @pytest.mark.parametrize("n,n_s,n_k", [(8, 1, 5), (16, 3, 9), (16, 6, 6)])
@@ -486,6 +534,94 @@ def test_cfg2_full(binding):
 
 def test_cfg3_full(binding):
     _full(binding, 3, [0, 1, 2], n_sample=32)
+
+
+@pytest.mark.parametrize("dtype,d,T", [("bf16", 512, 300), ("bf16", 512, 9), ("bf16", 512, 1), ("bf16", 512, 40),
+                                       ("fp32", 256, 70), ("bf16", 328, 100)])
+@pytest.mark.parametrize("gate", [False, True])
+def test_exact_score_ties_go_to_the_lower_expert_id(binding, dtype, d, T, gate):
+    """Two pairs of routed experts share a representative neuron, so their scores (Eq. 8) are equal on every
+    token, bit for bit.  The interface promises descending key with ties to the lowest expert id; the oracle's
+    stable sort does the same, so here a token whose boundary keys are *equal* is not excused: the indices
+    must match.  Sizes cover the one-token path, the team selection of the decode front end, the tile
+    router and the fp32 / odd-width scorer; with the gate of Eq. 9 the tied pair gets equal biases."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=d, d_ff=12 * 64, n_experts=12, n_shared=2, top_k=3, dtype=dtype,
+                       n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    reps = part["rep_neuron"].copy()
+    reps[5] = reps[1]                         # experts 1 and 5, 2 and 3 tie on every token
+    reps[3] = reps[2]
+    part = {"neuron_order": part["neuron_order"], "rep_neuron": reps}
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    u = b = None
+    if gate:
+        u, b = synth.make_gate_params(cfg)
+        b[5], b[3] = b[1], b[2]
+        layer.set_gate_params(u, b)
+    out = layer.forward(x)
+    rep = check_flat(cfg, weights, part, x, out, u=u, b=b, exact_ties_strict=True)
+    _say("exact ties %s d=%d T=%d gate=%s" % (dtype, d, T, gate), rep)
+    sel = out["topk"]
+    for hi, lo in ((5, 1), (3, 2)):
+        has_hi, has_lo = (sel == hi).any(axis=1), (sel == lo).any(axis=1)
+        assert not (has_hi & ~has_lo).any()                    # the higher id never gets in without the lower one
+        both = has_hi & has_lo
+        pos_lo = np.argmax(sel == lo, axis=1)
+        pos_hi = np.argmax(sel == hi, axis=1)
+        assert (pos_lo[both] + 1 == pos_hi[both]).all()        # equal keys: listed next to each other, lower id first
+    if T >= 40:
+        assert rep["exact_ties"] > 0                           # the pair did sit on the boundary for some tokens
+    layer.close()
+
+
+def test_layer_without_its_dense_baseline(binding):
+    """cmoe_set_baseline(0): half the device memory, the same MoE forward, and the dense call says why it cannot run."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=200)
+    full = _layer(binding, cfg, weights, part)
+    lean = _layer(binding, cfg, weights, part, baseline=False)
+    assert binding.cmoe_packed_bytes(lean.h) < 0.6 * binding.cmoe_packed_bytes(full.h)
+    a, b_ = full.forward(x), lean.forward(x)
+    assert np.array_equal(a["y"], b_["y"]) and np.array_equal(a["topk"], b_["topk"])
+    check_flat(cfg, weights, part, x, b_)
+    with pytest.raises(binding.CmoeError, match="baseline"):
+        lean.dense_forward(x)
+    full.close()
+    lean.close()
+
+
+def test_set_gate_params_between_forwards_in_flight(binding):
+    """Gate parameters changed while forwards are queued on a non-blocking stream: the call waits for the
+    device, so every forward enqueued before it used the old values and every one after it the new ones."""
+    import torch
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=2752, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    layer = _layer(binding, cfg, weights, part)
+    xh = synth.make_token_source(cfg).eval_batch(0, n=300)
+    u, b = synth.make_gate_params(cfg)
+    ref0 = layer.forward(xh)["y"]
+    layer.set_gate_params(u, b)
+    ref1 = layer.forward(xh)["y"]
+    layer.set_gate_params(None, None)
+    assert not np.array_equal(ref0, ref1)
+    x = torch.from_numpy(xh).to("cuda", torch.bfloat16)
+    ys = [torch.empty_like(x) for _ in range(6)]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for i in range(3):
+            layer.forward_device(x, ys[i])
+        layer.set_gate_params(u, b)
+        for i in range(3, 6):
+            layer.forward_device(x, ys[i])
+    torch.cuda.synchronize()
+    for i in range(6):
+        assert np.array_equal(ys[i].float().cpu().numpy().astype(np.float64), ref0 if i < 3 else ref1)
+    layer.close()
 
 
 def test_mfma_probe_reports_a_plausible_rate(binding):

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "cmoe.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(cmoe_[a-z_]+)\s*\(", header))
-    assert len(declared) >= 28
+    assert len(declared) >= 32
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -121,6 +121,41 @@ def test_update_bias_matches_the_oracle_on_the_host(lib):
     with pytest.raises(binding.CmoeError):
         binding.cmoe_update_bias(h, -np.ones(cfg.n_routed, dtype=np.int32), 1e-3)
     binding.cmoe_destroy(h)
+
+
+def test_baseline_copy_is_optional(lib):
+    """Without the dense baseline the packed weights are about half the size, and the switch is one-way."""
+    cfg, w, p = _tiny()
+    h = binding.cmoe_build_from_partition(binding.make_config(cfg), *w, p["neuron_order"], p["rep_neuron"])
+    both = binding.cmoe_packed_bytes(h)
+    binding.cmoe_set_baseline(h, False)
+    moe_only = binding.cmoe_packed_bytes(h)
+    assert moe_only < both and both - moe_only >= 3 * cfg.d_model * cfg.d_ff * 4
+    with pytest.raises(binding.CmoeError, match="released"):
+        binding.cmoe_set_baseline(h, True)
+    binding.cmoe_destroy(h)
+
+
+def test_tuning_switches(lib):
+    binding.cmoe_set_tuning("CMOE_SPLITK", 0)
+    binding.cmoe_set_tuning("CMOE_SPLITK", 1)
+    binding.cmoe_set_tuning("CMOE_GEMM1_CFG", -1)
+    with pytest.raises(binding.CmoeError, match="unknown"):
+        binding.cmoe_set_tuning("CMOE_NO_SUCH_SWITCH", 1)
+
+
+def test_non_finite_calibration_tokens_are_rejected(lib):
+    cfg = synth.scaled(synth.CONFIGS[0], d_model=16, d_ff=32, n_experts=4, n_shared=1, top_k=1, k_act=3)
+    w = synth.make_weights(cfg)
+    x = synth.make_token_source(cfg).calibration(n=40).copy()
+    x[17, 3] = np.nan
+    with pytest.raises(binding.CmoeError, match="token 17"):
+        binding.cmoe_build(binding.make_config(cfg), *w, x)
+    with pytest.raises(binding.CmoeError, match="token 17"):
+        binding.cmoe_profile_activations(binding.make_config(cfg), w[0], w[1], x, on_gpu=False)
+    x[17, 3] = np.inf
+    with pytest.raises(binding.CmoeError, match="token 17"):
+        binding.cmoe_build(binding.make_config(cfg), *w, x)
 
 
 def test_bench_refuses_more_than_one_gpu():
