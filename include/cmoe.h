@@ -164,6 +164,23 @@ int cmoe_forward(cmoe_layer* layer, const void* x_dev, int64_t T, void* y_dev,
                  int32_t* topk_idx_dev, float* scores_dev, int32_t* counts_dev,
                  void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* cmoe_forward for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error rules as
+ * cmoe_forward, but the workspace is a static device array inside the library (cmoe_static_scratch_bytes()
+ * = 32 MiB, held by every GPU the library runs on until the process ends); the call allocates nothing and
+ * frees nothing.  The device that holds the layer's weights must be current.  A batch whose workspace would
+ * not fit is rejected with CMOE_EINVAL and a message that names the limit; cmoe_forward_static_max_tokens
+ * gives the largest batch that fits for this layer (about 600 tokens for a 4096-wide layer with four slots
+ * per token).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two host threads) race; calls enqueued on one stream are ordered and safe.  Nothing in the array
+ * has to be cleared between calls.  Partial sums of a K-split contraction get at most 8 MiB here, so a
+ * batch of a few hundred tokens may split K differently than under cmoe_forward (same result within the
+ * bf16 tolerance, not bit for bit). */
+int cmoe_forward_static(cmoe_layer* layer, const void* x_dev, int64_t T, void* y_dev,
+                        int32_t* topk_idx_dev, float* scores_dev, int32_t* counts_dev, void* hip_stream);
+size_t cmoe_static_scratch_bytes(void);
+int64_t cmoe_forward_static_max_tokens(const cmoe_layer* layer);
+
 /* The dense FFN F(x) of Eq. 3 on the same layer, with kernels of the same quality as the MoE
  * path (one group, all tokens, all d_h neurons, no expert padding).  Same argument rules. */
 int cmoe_dense_forward(cmoe_layer* layer, const void* x_dev, int64_t T, void* y_dev,

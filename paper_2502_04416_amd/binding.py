@@ -40,7 +40,7 @@ EXPORTS = [
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
     "cmoe_balanced_assignment", "cmoe_probe_mfma", "cmoe_probe_hbm", "cmoe_get_gate_params", "cmoe_update_bias",
     "cmoe_build_gpu", "cmoe_profile_activations", "cmoe_set_baseline", "cmoe_hier_build", "cmoe_hier_expert",
-    "cmoe_set_tuning",
+    "cmoe_set_tuning", "cmoe_forward_static", "cmoe_static_scratch_bytes", "cmoe_forward_static_max_tokens",
 ]
 
 
@@ -98,6 +98,11 @@ def load():
     lib.cmoe_hier_expert.argtypes = [vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.cmoe_hier_expert.restype = vp
     lib.cmoe_set_tuning.argtypes = [C.c_char_p, C.c_int]
+    lib.cmoe_forward_static.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.cmoe_static_scratch_bytes.argtypes = []
+    lib.cmoe_static_scratch_bytes.restype = sz
+    lib.cmoe_forward_static_max_tokens.argtypes = [vp]
+    lib.cmoe_forward_static_max_tokens.restype = i64
     lib.cmoe_last_error.restype = C.c_char_p
     lib.cmoe_version.restype = C.c_char_p
     _lib = lib
@@ -234,6 +239,18 @@ def cmoe_forward(layer: int, x_ptr: int, T: int, y_ptr: int, topk_ptr, scores_pt
                  ws_bytes: int, stream: int = 0) -> None:
     _check(load().cmoe_forward(layer, x_ptr, T, y_ptr, topk_ptr, scores_ptr, counts_ptr, ws_ptr, ws_bytes, stream),
            "cmoe_forward")
+
+
+def cmoe_forward_static(layer: int, x_ptr: int, T: int, y_ptr: int, topk_ptr, scores_ptr, counts_ptr, stream: int = 0) -> None:
+    _check(load().cmoe_forward_static(layer, x_ptr, T, y_ptr, topk_ptr, scores_ptr, counts_ptr, stream), "cmoe_forward_static")
+
+
+def cmoe_static_scratch_bytes() -> int:
+    return load().cmoe_static_scratch_bytes()
+
+
+def cmoe_forward_static_max_tokens(layer: int) -> int:
+    return load().cmoe_forward_static_max_tokens(layer)
 
 
 def cmoe_dense_forward(layer: int, x_ptr: int, T: int, y_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:

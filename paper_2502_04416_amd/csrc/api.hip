@@ -8,6 +8,7 @@
 #include <cstring>
 #include <exception>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -131,7 +132,7 @@ int64_t gemm_work_bound(const Engine& e, int64_t T, int which) {
   return std::max<int64_t>(total, 1);
 }
 
-WsLayout ws_layout(const Engine& e, int64_t T) {
+WsLayout ws_layout(const Engine& e, int64_t T, size_t splitk_cap) {
   WsLayout L{};
   const size_t es = elem_size(e.dtype);
   const int64_t Tn = std::max<int64_t>(T, 1);
@@ -157,7 +158,7 @@ WsLayout ws_layout(const Engine& e, int64_t T) {
   L.y_slots = take(e.direct_output() ? 0 : es * (size_t)L.n_slots * e.d);
   // Partial sums of a K-split contraction: reserved in full whenever the largest batch runs the tiled
   // contraction kernels (then smaller ones may too, and may split further), so that the size grows with T.
-  L.splitk_bytes = (!use_simt_experts(e.dtype) && !decode_path_ok(e, Tn)) ? bf16_splitk_bytes(e, Tn) : 0;
+  L.splitk_bytes = (!use_simt_experts(e.dtype) && !decode_path_ok(e, Tn)) ? std::min(bf16_splitk_bytes(e, Tn), splitk_cap) : 0;
   L.splitk = take(L.splitk_bytes);
   L.total = off;
   return L;
@@ -723,12 +724,12 @@ int cmoe_upload(cmoe_layer* L, void* dev_weights, void* hip_stream) {
 
 static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_t* topk, int32_t* outer,
                       float* scores, int32_t* counts, void* ws, size_t ws_bytes, hipStream_t s,
-                      hipEvent_t* ev = nullptr) {
+                      hipEvent_t* ev = nullptr, size_t splitk_cap = ~(size_t)0) {
   if (T < 0) return fail(CMOE_EINVAL, "negative token count");
   if (T == 0) return CMOE_OK;
   if (!x || !y || !ws) return fail(CMOE_EINVAL, "x, y or workspace is null");
   if (T * (int64_t)e.S_all() > (int64_t)0x7fffffff / 2) return fail(CMOE_EINVAL, "batch too large for 32-bit slot indices");
-  WsLayout L = ws_layout(e, T);
+  WsLayout L = ws_layout(e, T, splitk_cap);
   if (ws_bytes < L.total) return fail(CMOE_EINVAL, "workspace too small: %zu bytes given, %zu needed", ws_bytes, L.total);
   if (((uintptr_t)ws & 255) != 0) return fail(CMOE_EINVAL, "workspace must be 256-byte aligned");
   char* w = static_cast<char*>(ws);
@@ -796,6 +797,69 @@ int cmoe_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev, int32
   if (!L->has_b) e.gate_b = nullptr;
   return run_engine(e, x_dev, T, y_dev, topk_idx_dev, nullptr, scores_dev, counts_dev, workspace_dev,
                     workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- the forward for callers that cannot allocate: its workspace is a static device array ----------------
+// Each GPU the library runs on holds its own copy of the array from the moment the code object is loaded
+// until the process ends.  In host code the array's name is only a stand-in: the device address of the
+// copy on the current device comes from hipGetSymbolAddress, once per device, and only that pointer is ever
+// handed to a kernel.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)32 << 20;
+constexpr size_t STATIC_SPLITK_CAP = (size_t)8 << 20;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+static int static_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptr_of_device[STATIC_MAX_DEVICES] = {nullptr};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(CMOE_EINVAL, "device index %d is outside the table of %d devices", dev, STATIC_MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+    if (!p || ((uintptr_t)p & 255) != 0) return fail(CMOE_EHIP, "static scratch array has no usable device address");
+    ptr_of_device[dev] = p;
+  }
+  *out = ptr_of_device[dev];
+  return CMOE_OK;
+}
+
+size_t cmoe_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int64_t cmoe_forward_static_max_tokens(const cmoe_layer* L) {
+  if (!L) return 0;
+  int64_t lo = 0, hi = 1 << 20;            // the layout grows with T: bisect the largest batch that fits
+  while (lo < hi) {
+    const int64_t mid = (lo + hi + 1) / 2;
+    if (ws_layout(L->e_moe, mid, STATIC_SPLITK_CAP).total <= STATIC_SCRATCH_BYTES) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
+
+int cmoe_forward_static(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev, int32_t* topk_idx_dev,
+                        float* scores_dev, int32_t* counts_dev, void* hip_stream) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (!L->uploaded) return fail(CMOE_ESTATE, "cmoe_upload has not been called");
+  if (T < 0) return fail(CMOE_EINVAL, "negative token count");
+  if (T == 0) return CMOE_OK;
+  const size_t need = ws_layout(L->e_moe, T, STATIC_SPLITK_CAP).total;
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(CMOE_EINVAL, "batch of %lld tokens needs %zu bytes of workspace, the static scratch array holds %zu "
+                "(at most %lld tokens for this layer): use cmoe_forward with a workspace of your own",
+                (long long)T, need, STATIC_SCRATCH_BYTES, (long long)cmoe_forward_static_max_tokens(L));
+  void* ws = nullptr;
+  const int rc = static_scratch_ptr(&ws);
+  if (rc) return rc;
+  Engine e = L->e_moe;
+  if (!L->has_u) e.gate_u = nullptr;
+  if (!L->has_b) e.gate_b = nullptr;
+  return run_engine(e, x_dev, T, y_dev, topk_idx_dev, nullptr, scores_dev, counts_dev, ws, STATIC_SCRATCH_BYTES,
+                    static_cast<hipStream_t>(hip_stream), nullptr, STATIC_SPLITK_CAP);
 }
 
 int cmoe_dense_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev, void* workspace_dev,

@@ -146,7 +146,9 @@ int w1_row_stride(int d);
 
 // Record the calling thread's error message (what cmoe_last_error returns) and hand `code` back.
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
-WsLayout ws_layout(const Engine& e, int64_t T);
+// splitk_cap: upper limit of the bytes reserved for the partial sums of a K-split contraction (a launch whose
+// slabs would not fit what was reserved does not split).
+WsLayout ws_layout(const Engine& e, int64_t T, size_t splitk_cap = ~(size_t)0);
 
 // Kernel launchers (defined in the .hip files).  All enqueue on `s` and return the launch status.
 hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
