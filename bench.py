@@ -2,14 +2,25 @@
 """Bench of the MoE-FFN forward (router -> top-k -> permute -> shared + routed SwiGLU experts -> combine)
 on one MI355X, through the C ABI of libcmoe.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--batch 2048]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]            # every configuration, one JSON line
+    python bench.py --config 1 [--batch 2048]                      # one flat configuration in detail
+    python bench.py --config 1 --sweep | --batch-sweep             # expert-configuration / batch-size studies
 
 A step is one pass of the whole hot path over one batch of synthetic tokens already resident in HBM.
-The headline workload is the LLaMA-2-7B-shaped layer of config 1 (16 experts of 688 neurons, 1 shared +
-top-3 of 15 routed) on its 2048-token prefill batch.  One JSON line is printed with tokens/s, the
-speedup over the dense-FFN kernels of the same library, per-stage times, the roofline of the dominant
-kernel (gate/up grouped contraction, bf16 MFMA), decode-batch results against the HBM roofline, and
-the CPU oracle timed on the host cores (a reported baseline, not a target).
+Without --config the headline (`value`, `ms_per_step`, `roofline`, `cpu_baseline`) is the largest
+single-GPU workload, config 4: the Mixtral-8x7B-shaped layer of 8 experts whose experts were each
+restructured into 8 sub-experts (2 shared + top-2 of 6), 4096 tokens, constructed by cmoe_hier_build from
+the calibration set.  The `configs` array of the same line carries, for each of configs 1-4 and each of
+their evaluation batches (decode batches included), the forward time, the baseline's time (dense FFN of
+the same kernels; for config 4 the un-restructured MoE layer), the speedup, and the dominant kernel's
+duration and roofline fraction.
+
+The dominant kernel's duration is measured live by difference between two loops of forwards, each between
+two HIP events on the launch stream: for compute-bound batches the loop with the gate/up launch issued twice
+(tuning switch CMOE_REPEAT_STAGE) minus the plain loop, for decode batches the plain loop minus the loop
+without that launch (CMOE_SKIP_STAGE).  What the loop gains or loses is that launch's cost inside the stream,
+launch gap included, which is what a kernel trace reports for back-to-back launches of one stream; no
+event-pair overhead enters (4-5 us on this runtime, half of a decode kernel).
 """
 import argparse
 import json
@@ -23,8 +34,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0     # dense bf16 MFMA
 FP32_VALU_PEAK_TF = 157.3
-# gate/up launch of the headline workload (config 1, T = 2048, library partition): 299.1 MB fetched + 11.5 MB written
-MEASURED_GATE_UP_TRAFFIC_BYTES = 310.6e6
+# HBM bytes (fetched + written) of one gate/up launch from the two rocprofv3 --pmc runs summarised under
+# profiles/ (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 against a copy of known size), keyed by (config, T);
+# a property of the tiling and the workload, not re-measured per run
+MEASURED_GATE_UP_TRAFFIC_BYTES = {(1, 2048): 310.6e6}
+METRIC = "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)"
 
 
 RAMP_MS = 40.0
@@ -58,7 +72,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--config", type=int, default=None,
+                    help="one configuration in detail (1-3 flat, 4 hierarchical); default: all of them in one line")
     ap.add_argument("--batch", type=int, default=None, help="token count (default: the config's largest eval batch)")
     ap.add_argument("--construct", choices=["library", "gpu", "arbitrary"], default="library",
                     help="partition from cmoe_build on the calibration set (host), from cmoe_build_gpu (activation "
@@ -139,7 +154,7 @@ def bench_batches(args, cfg, np, torch, binding, synth):
                      "stage_ms_with_event_overhead": dict(zip(("router", "permute", "gate_up", "down", "combine"), map(float, stage)))})
     head = rows[-1]
     print(json.dumps({
-        "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
+        "metric": METRIC,
         "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
@@ -188,7 +203,7 @@ def bench_hier(args, cfg, np, torch, binding, synth):
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["frac_of_sustained_mfma"] = roofline["achieved"] / tf1
     out = {
-        "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
+        "metric": METRIC,
         "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": ms_moe, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
@@ -242,7 +257,7 @@ def bench_sweep(args, base, np, torch, binding, synth):
         layer.close()
     head = rows[0]
     out = {
-        "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
+        "metric": METRIC,
         "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": base.dtype, "data": "synthetic",
@@ -250,6 +265,216 @@ def bench_sweep(args, base, np, torch, binding, synth):
                    % (base.cfg, base.name, base.d_model, base.d_ff, head["shape"], head["T"]), "partition": "arbitrary"},
         "sweep": rows, "setup_s": time.time() - t_setup,
     }
+    print(json.dumps(out))
+
+
+def event_loop_ms(fn, steps, warmup=8):
+    """Milliseconds per call of `fn`: `steps` calls between two HIP events on the current (launch) stream,
+    after the clock ramp and `warmup` calls."""
+    import torch
+    t_ramp = time.perf_counter()
+    while (time.perf_counter() - t_ramp) * 1e3 < RAMP_MS:
+        for _ in range(8):
+            fn()
+        torch.cuda.synchronize()
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def stage_costs_ms(binding, fn, steps, prefill, timed_fns):
+    """Forward time and the cost of the gate/up launch inside the stream, by difference, both loops measured
+    here back to back.  Compute-bound batches: the loop with that launch issued twice minus the plain loop
+    (same clocks and power as the plain forward; agrees with a kernel trace within 2 %; leaving the launch out
+    instead lets the clock rise for the other kernels and overstates it by 15 %).  Decode batches: the plain
+    loop minus the loop without that launch (a second launch would find its weights in the cache; agrees with
+    a trace within 3-6 %).  The per-stage table comes from events inside the library and contains the 4-5 us an
+    event pair costs on this runtime in every entry."""
+    import numpy as np
+    full = event_loop_ms(fn, steps)
+    out = {"forward": full}
+    try:
+        if prefill:
+            binding.cmoe_set_tuning("CMOE_REPEAT_STAGE", 3)
+            out["gate_up"] = max(event_loop_ms(fn, steps) - full, 1e-6)
+        else:
+            binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 3)
+            out["gate_up"] = max(full - event_loop_ms(fn, steps), 1e-6)
+    finally:
+        binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 0)
+        binding.cmoe_set_tuning("CMOE_REPEAT_STAGE", 0)
+    acc, n = np.zeros(5), 0
+    for f in timed_fns:
+        f()
+    for _ in range(3 if prefill else 2):
+        for f in timed_fns:
+            acc += f()
+            n += 1
+    out["events_raw"] = dict(zip(("router", "permute", "gate_up", "down", "combine"), (float(v) for v in acc / n)))
+    return out
+
+
+def entry(cfg, T, ms, base_ms, costs, act_per_token, union=None, shared_front=False, baseline="dense FFN"):
+    """One row of the `configs` array.  act_per_token: active experts per token ((N_s + N_k), times the outer
+    top-k for the hierarchy); union: routed experts (plus shared ones) whose weights the batch touches (decode)."""
+    d, m, es = cfg.d_model, cfg.m, 2
+    row = {"cfg": cfg.cfg, "name": cfg.name, "T": T, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
+           "baseline": baseline, "baseline_ms_per_step": base_ms, "speedup_vs_baseline": base_ms / ms,
+           "stage_ms_events_raw": costs["events_raw"]}
+    gu = max(costs["gate_up"], 1e-6)
+    if T >= 256:
+        flops_gu = 4.0 * d * m * act_per_token * T
+        n_router = cfg.n_routed * (cfg.n_outer or 1)
+        flops_all = T * (6.0 * d * m * act_per_token + 4.0 * d * n_router + (2.0 * d * cfg.n_outer if cfg.n_outer else 0.0))
+        row.update({"dominant_kernel": "grouped_gemm_bf16_dma<gate_up>", "bound": "mfma", "kernel_ms": gu,
+                    "achieved": flops_gu / (gu * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s",
+                    "frac": flops_gu / (gu * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
+                    "down_frac_from_raw_events": 0.5 * flops_gu / (max(costs["events_raw"]["down"], 1e-6) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF,
+                    "whole_path_frac": flops_all / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF})
+    else:
+        n_shared_groups = cfg.n_shared * (cfg.outer_top_k if cfg.n_outer else 1)
+        bytes_gu = es * 2.0 * d * m * (union - (n_shared_groups if shared_front else 0))
+        n_router = cfg.n_routed * (cfg.n_outer or 1)
+        bytes_all = es * (3.0 * d * m * union + 2.0 * d * n_router)
+        row.update({"dominant_kernel": "decode_gate_up_kernel" if T <= 16 else "grouped_gemm_bf16_dma<gate_up> (64x128 tiles)",
+                    "bound": "hbm", "kernel_ms": gu, "expert_groups_touched": union,
+                    "shared_experts_in_front_launch": bool(shared_front),
+                    "achieved": bytes_gu / (gu * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": bytes_gu / (gu * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "whole_path_frac": bytes_all / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    return row
+
+
+def bench_all(args, np, torch, binding, synth):
+    """Every configuration in one line: headline = config 4 (hierarchical, 4096 tokens)."""
+    dev = torch.device("cuda:0")
+    t_setup = time.time()
+    rows = []
+    sub_steps = max(20, min(args.steps, 60))
+
+    def cycle(fns):
+        st = {"i": 0}
+
+        def step():
+            fns[st["i"] % len(fns)]()
+            st["i"] += 1
+        return step
+
+    # ---- flat layers: configs 1, 2 (same dense layer, two expert splits), 3 ----
+    for ci in (1, 2, 3):
+        cfg = synth.CONFIGS[ci]
+        weights = synth.make_weights(cfg)
+        src = synth.make_token_source(cfg)
+        layer = binding.Layer.build(cfg, *weights, src.calibration(), on_gpu=True)
+        part = layer.export_partition()
+        copies = [layer]
+        if any(T <= 64 for T in cfg.eval_batches):
+            for _ in range(args.layer_copies - 1):
+                copies.append(binding.Layer.from_partition(cfg, *weights, part["neuron_order"], part["rep_neuron"]))
+        for bi, T in enumerate(cfg.eval_batches):
+            decode = T <= 64
+            use = copies if decode else copies[:1]
+            xs = [torch.from_numpy(src.eval_batch(bi) if i == 0 else src.draw(9000 + 100 * T + i, T)).to(dev, torch.bfloat16)
+                  for i in range(len(use))]
+            y = torch.empty_like(xs[0])
+            cnt = torch.zeros((cfg.n_routed,), dtype=torch.int32, device=dev)
+            moe = cycle([(lambda L=L, x=x: L.forward_device(x, y, None, None, None)) for L, x in zip(use, xs)])
+            dense = cycle([(lambda L=L, x=x: L.dense_forward_device(x, y)) for L, x in zip(use, xs)])
+            steps = max(sub_steps, 96) if decode else sub_steps
+            costs = stage_costs_ms(binding, moe, steps, not decode,
+                                   [(lambda L=L, x=x: L.forward_timed(x, y, False)) for L, x in zip(use, xs)])
+            base_ms = event_loop_ms(dense, steps)
+            union = None
+            if decode:
+                touched = 0.0
+                for L, x in zip(use, xs):
+                    L.forward_device(x, y, None, None, cnt)
+                    torch.cuda.synchronize()
+                    touched += float((cnt.cpu().numpy() > 0).sum())
+                union = cfg.n_shared + touched / len(use)
+            rows.append(entry(cfg, T, costs["forward"], base_ms, costs, cfg.n_shared + cfg.top_k, union,
+                              shared_front=shared_in_front(cfg, T)))
+        for L in copies:
+            L.close()
+        del copies, layer, weights
+        torch.cuda.empty_cache()
+
+    # ---- config 4, the headline: constructed by the library from the un-restructured layer ----
+    cfg = synth.CONFIGS[4]
+    w_router, offsets = synth.make_outer_router(cfg)
+    ws = [synth.make_outer_expert_weights(cfg, e) for e in range(cfg.n_outer)]
+    src = synth.make_token_source(cfg)
+    t0 = time.time()
+    hier = binding.Hierarchy.build(cfg, cfg.outer_top_k, [w[0] for w in ws], [w[1] for w in ws], [w[2] for w in ws],
+                                   w_router, offsets, src.calibration(), on_gpu=True)
+    construct_s = time.time() - t0
+    T = max(cfg.eval_batches)
+    x_host = src.eval_batch(0, n=T)
+    x = torch.from_numpy(x_host).to(dev, torch.bfloat16)
+    y = torch.empty_like(x)
+    ms_moe = timed(lambda: hier.forward_device(x, y), args.steps, args.warmup)          # the contract's K steps
+    ms_base = timed(lambda: hier.dense_forward_device(x, y), args.steps, args.warmup)
+    costs = stage_costs_ms(binding, lambda: hier.forward_device(x, y), sub_steps, True, [lambda: hier.forward_timed(x, y, False)])
+    act = cfg.outer_top_k * (cfg.n_shared + cfg.top_k)
+    head = entry(cfg, T, ms_moe, ms_base, costs, act, baseline="un-restructured MoE layer (top-2 of 8 dense experts)")
+    rows.append(head)
+    outer = torch.empty((T, cfg.outer_top_k), dtype=torch.int32, device=dev)
+    hier.forward_device(x, y, outer, None)
+    torch.cuda.synchronize()
+    outer_load = np.bincount(outer.cpu().numpy().ravel(), minlength=cfg.n_outer).tolist()
+    tf0, mhz0 = binding.cmoe_probe_mfma(False, 16384)
+    tf1, mhz1 = binding.cmoe_probe_mfma(True, 16384)
+    roofline = {"kernel": head["dominant_kernel"], "bound": "mfma", "achieved": head["achieved"], "peak": MFMA_BF16_PEAK_TF,
+                "unit": "TFLOP/s", "frac": head["frac"], "traffic": MEASURED_GATE_UP_TRAFFIC_BYTES.get((4, T)),
+                "avg_launch_ms": head["kernel_ms"], "frac_of_sustained_mfma": head["achieved"] / tf1,
+                "how": "loop of forwards with this launch issued twice minus the plain loop, HIP events on the launch stream"}
+    out = {
+        "metric": METRIC, "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "clock_ramp_ms": RAMP_MS, "ms_per_step": ms_moe, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "cfg%d %s: %d outer experts (top-%d, Zipf(1.1) logit offsets) of d=%d d_ff=%d, each restructured "
+                               "into %d sub-experts of %d neurons (%d shared + top-%d of %d routed), T=%d tokens"
+                   % (cfg.cfg, cfg.name, cfg.n_outer, cfg.outer_top_k, cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.m,
+                      cfg.n_shared, cfg.top_k, cfg.n_routed, T),
+                   "partition": "cmoe_hier_build (profiling on the device), %d calibration tokens" % cfg.n_calib,
+                   "k_act": cfg.k_act, "sigma_o": synth.SIGMA_O},
+        "baseline_ms_per_step": ms_base, "speedup_vs_baseline": ms_base / ms_moe, "outer_expert_load": outer_load,
+        "active_fraction": act * cfg.m / float(cfg.outer_top_k * cfg.d_ff),
+        "roofline": roofline, "construct_s": construct_s,
+        "mfma_probe": {"zero_operands_TFLOPs": tf0, "zero_operands_MHz": mhz0, "random_operands_TFLOPs": tf1,
+                       "random_operands_MHz": mhz1},
+        "configs": rows,
+    }
+    try:
+        out["hbm_probe_GBs"] = binding.cmoe_probe_hbm(2 << 30, 5)
+    except binding.CmoeError:
+        out["hbm_probe_GBs"] = None
+    if not args.no_cpu:
+        from oracle import cmoe_oracle as O
+        n_cpu = min(T, 1024)
+        experts = []
+        for e in range(cfg.n_outer):
+            part = hier.expert_partition(e)
+            experts.append({"w_gate": ws[e][0], "w_up": ws[e][1], "w_down": ws[e][2],
+                            "neuron_order": part["neuron_order"], "rep_neuron": part["rep_neuron"]})
+        t0 = time.perf_counter()
+        O.hier_forward(x_host[:n_cpu], w_router, offsets, cfg.outer_top_k, experts, cfg.n_experts, cfg.n_shared, cfg.top_k)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        out["cpu_baseline"] = {"value": n_cpu / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": "first %d tokens of the same batch, fp64 numpy oracle (hier_forward), %.1f s" % (n_cpu, dt)}
+    hier.close()
+    out["setup_s"] = time.time() - t_setup
     print(json.dumps(out))
 
 
@@ -266,7 +491,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no HIP device visible", file=sys.stderr)
         sys.exit(2)
-    cfg = synth.CONFIGS[args.config]
+    if args.config is None and not (args.sweep or args.batch_sweep):
+        bench_all(args, np, torch, binding, synth)
+        return
+    cfg = synth.CONFIGS[1 if args.config is None else args.config]
     if args.batch_sweep:
         bench_batches(args, cfg, np, torch, binding, synth)
         return
@@ -388,7 +616,7 @@ def main():
     if prefill and cfg.cfg == 1 and T == 2048 and args.construct in ("library", "gpu"):
         # HBM bytes of one launch of this kernel on this workload from the two rocprofv3 --pmc runs
         # (FETCH_SIZE x 2.000 scale, WRITE_SIZE x 1.000; profiles/cfg1_T2048_hbm_traffic.md)
-        roofline["traffic"] = MEASURED_GATE_UP_TRAFFIC_BYTES
+        roofline["traffic"] = MEASURED_GATE_UP_TRAFFIC_BYTES.get((1, 2048))
     # what the matrix cores sustain on register operands alone, in this process, right now
     mfma_probe = None
     if cfg.dtype == "bf16":
@@ -402,7 +630,7 @@ def main():
         roofline.update({"bound": "alu", "peak": FP32_VALU_PEAK_TF, "frac": roofline["achieved"] / FP32_VALU_PEAK_TF})
 
     out = {
-        "metric": "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)",
+        "metric": METRIC,
         "value": T / (ms_moe * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_ms": RAMP_MS,
         "ms_per_step": ms_moe, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",

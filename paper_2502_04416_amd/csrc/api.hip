@@ -48,7 +48,8 @@ static const TuningField kTuningFields[] = {
     {"CMOE_FRONT_SHARED", &Tuning::front_shared}, {"CMOE_FORCE_SIMT", &Tuning::force_simt},
     {"CMOE_LDPAD", &Tuning::ldpad},             {"CMOE_HOST_THREADS", &Tuning::host_threads},
     {"CMOE_SKIP_ROWS", &Tuning::skip_rows},     {"CMOE_DECODE_SPLIT", &Tuning::decode_split},
-    {"CMOE_WS_DOWN", &Tuning::ws_down},
+    {"CMOE_WS_DOWN", &Tuning::ws_down},         {"CMOE_SKIP_STAGE", &Tuning::skip_stage},
+    {"CMOE_REPEAT_STAGE", &Tuning::repeat_stage},
 };
 
 Tuning& tuning() {
@@ -751,13 +752,15 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
     if (err != hipSuccess) return fail_hip(err, "permute kernel");
   }
   mark(2);
-  err = launch_experts(e, x, T, w, L, y, s, 1);
+  // (skip: measurement aid, see Tuning::skip_stage; only launches that produce no control data can be left out)
+  const int skip = tuning().skip_stage, twice = tuning().repeat_stage;
+  for (int n = (skip == 3 ? 0 : twice == 3 ? 2 : 1); n > 0 && err == hipSuccess; --n) err = launch_experts(e, x, T, w, L, y, s, 1);
   if (err != hipSuccess) return fail_hip(err, "gate/up expert kernel");
   mark(3);
-  err = launch_experts(e, x, T, w, L, y, s, 2);
+  for (int n = (skip == 4 ? 0 : twice == 4 ? 2 : 1); n > 0 && err == hipSuccess; --n) err = launch_experts(e, x, T, w, L, y, s, 2);
   if (err != hipSuccess) return fail_hip(err, "down expert kernel");
   mark(4);
-  err = launch_combine(e, T, w, L, y, s);
+  for (int n = (skip == 5 ? 0 : twice == 5 ? 2 : 1); n > 0 && err == hipSuccess; --n) err = launch_combine(e, T, w, L, y, s);
   if (err != hipSuccess) return fail_hip(err, "combine kernel");
   mark(5);
   return CMOE_OK;

@@ -136,6 +136,11 @@ struct Tuning {
   int skip_rows = 1;       // 0: the gate/up contraction multiplies the 32-row blocks past the end of a segment too
   int decode_split = -1;   // K split of the decode gate/up units across workgroups (-1: chosen per batch)
   int ws_down = 1;         // 0: never use the weight-stationary down contraction
+  int skip_stage = 0;      // measurement aid: 3, 4 or 5 leaves out the gate/up, down or combine launch of every
+                           // forward (outputs are then meaningless); the time a forward loses is that stage's
+                           // cost inside the stream, launch gap included.  Other values: nothing is skipped.
+  int repeat_stage = 0;    // measurement aid: 3, 4 or 5 launches that stage twice (same inputs, same outputs); the
+                           // time a forward gains is one more launch of it under the forward's own clocks
 };
 Tuning& tuning();
 
