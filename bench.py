@@ -88,6 +88,10 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="the paper's expert configurations SxAyEz at 75 %% active and the sparsity ladder with 16 "
                          "experts, on the config's dense layer (speedup vs dense at two batch sizes)")
+    ap.add_argument("--sparsity", action="store_true",
+                    help="neuron-level activation sparsity inside the routed experts (Sec. 5): forward time at 1, 2, 16 and "
+                         "2048 tokens with the feature off and with thresholds that drop 25 / 50 / 75 %% of the routed "
+                         "activations, on the config's layer")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="the layer against its baseline over batch sizes from 1 token up (arbitrary partition; several "
                          "device copies of the layer and token sets are cycled so that weights come from HBM)")
@@ -478,6 +482,56 @@ def bench_all(args, np, torch, binding, synth):
     print(json.dumps(out))
 
 
+def bench_sparsity(args, cfg, np, torch, binding, synth):
+    """Effect of neuron-level activation sparsity inside the routed experts on the forward time."""
+    from oracle import cmoe_oracle as O          # only to place the thresholds (quantiles of |h| on calibration tokens)
+    dev = torch.device("cuda:0")
+    t_setup = time.time()
+    weights = synth.make_weights(cfg)
+    src = synth.make_token_source(cfg)
+    base = binding.Layer.build(cfg, *weights, src.calibration(), upload=False, on_gpu=True)
+    part = base.export_partition()
+    base.close()
+    h = np.abs(O.hidden_states(src.calibration(n=64), weights[0], weights[1]))
+    copies = []
+    for _ in range(args.layer_copies):
+        L = binding.Layer.from_partition(cfg, *weights, part["neuron_order"], part["rep_neuron"], upload=False, baseline=False)
+        L.set_neuron_sparsity(1, 0.0)
+        L.set_neuron_sparsity(0, 0.0)
+        L.upload()
+        copies.append(L)
+    rows = []
+    for T in ([args.batch] if args.batch else [1, 2, 16, 2048]):
+        use = copies if T <= 64 else copies[:1]
+        xs = [torch.from_numpy(src.draw(9000 + 100 * T + i, T)).to(dev, torch.bfloat16) for i in range(len(use))]
+        y = torch.empty_like(xs[0])
+        st = {"i": 0}
+
+        def step():
+            i = st["i"] % len(use)
+            st["i"] += 1
+            use[i].forward_device(xs[i], y, None, None, None)
+        steps = max(args.steps, 200) if T <= 64 else args.steps
+        row = {"T": T, "off_ms": event_loop_ms(step, steps)}
+        for share in (0.25, 0.5, 0.75):
+            tau = float(np.float32(np.quantile(h, share)))
+            for L in use:
+                L.set_neuron_sparsity(1, tau)
+            row["drop_%d_ms" % int(share * 100)] = event_loop_ms(step, steps)
+            row["tau_%d" % int(share * 100)] = tau
+        for L in use:
+            L.set_neuron_sparsity(0, 0.0)
+        rows.append(row)
+    head = rows[0]
+    print(json.dumps({
+        "metric": METRIC, "value": head["T"] / (head["off_ms"] * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "clock_ramp_ms": RAMP_MS, "ms_per_step": head["off_ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "neuron-level sparsity study on cfg%d %s; headline fields are T=%d with the feature off"
+                   % (cfg.cfg, cfg.name, head["T"]), "partition": "library"},
+        "neuron_sparsity": rows, "setup_s": time.time() - t_setup}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -491,6 +545,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no HIP device visible", file=sys.stderr)
         sys.exit(2)
+    if args.sparsity:
+        bench_sparsity(args, synth.CONFIGS[1 if args.config is None else args.config], np, torch, binding, synth)
+        return
     if args.config is None and not (args.sweep or args.batch_sweep):
         bench_all(args, np, torch, binding, synth)
         return

@@ -122,6 +122,22 @@ int cmoe_export_partition(const cmoe_layer* layer, int32_t* neuron_order, int32_
  * enqueued from another host thread. */
 int cmoe_set_gate_params(cmoe_layer* layer, const float* u, const float* b);
 
+/* Neuron-level activation sparsity inside the routed experts (Sec. 5 "Orthogonality with Activation
+ * Sparsity": training-free activation sparsity applied within the routed experts; the shared experts are
+ * never sparsified).  A hidden activation h_n of a selected routed expert contributes h_n w_n to the output
+ * (Eq. 1) only if
+ *     mode 1 (magnitude):        |h_n| >= tau
+ *     mode 2 (weight-informed):  |h_n| * ||w_n||_2 >= tau,   w_n = row n of W_down (rounded to the layer dtype),
+ * decided on the bf16 value of h_n the kernels hold (norm and product in fp32); mode 0 switches it off.  The
+ * paper names the family of criteria and gives no formula; the threshold is the caller's (such methods
+ * calibrate it offline for a target share of dropped neurons).  bf16 flat layers only (CMOE_EINVAL otherwise;
+ * CMOE_ESTATE for a layer inside a hierarchy).  The first call with mode != 0 must come before cmoe_upload: it
+ * adds a neuron-major copy of the routed experts' down matrices and the row norms to cmoe_packed_bytes (for
+ * batches of one or two tokens the down projection reads only the surviving neurons' rows from it; larger
+ * batches zero the dropped activations and run the usual kernels).  Later calls may change mode and tau at
+ * any time; they take effect at the next forward. */
+int cmoe_set_neuron_sparsity(cmoe_layer* layer, int mode, float tau);
+
 /* Copies the current gate parameters to host arrays u [N_r], b [N_r] (either may be NULL). */
 int cmoe_get_gate_params(const cmoe_layer* layer, float* u, float* b);
 

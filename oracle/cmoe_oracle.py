@@ -25,7 +25,8 @@ notes of the repository):
 
 Parity unpinned by the paper (no printed example fixes them): the signed-score
 reading, the iteration count, the centroid used for the representative neuron,
-per-expert calibration in the hierarchical build (`hier_build`).  `build`,
+per-expert calibration in the hierarchical build (`hier_build`), the form of the
+neuron-level sparsity criterion inside routed experts (`neuron_keep_mask`).  `build`,
 `hier_build` and `hier_forward`'s outer gate therefore carry "parity unpinned"
 for those choices: the code that implements each reading is pinned (hand-worked
 examples, exhaustive search, loops written out in the tests), the choice of
@@ -274,16 +275,64 @@ def expert_output(x: np.ndarray, w_gate, w_up, w_down, neurons: np.ndarray) -> n
     return dense_ffn(x, np.asarray(w_gate)[:, idx], np.asarray(w_up)[:, idx], np.asarray(w_down)[idx, :])
 
 
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 value of every entry, ties to even, returned as float64 (finite inputs).
+    bfloat16 keeps the upper 16 bits of the IEEE single-precision pattern."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    bits = f.view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).reshape(f.shape).astype(F64)
+
+
+def neuron_keep_mask(h: np.ndarray, w_down_rows: np.ndarray, tau: float, weight_informed: bool = False,
+                     decide_in_bf16: bool = False) -> np.ndarray:
+    """Which hidden activations of a routed expert survive neuron-level activation sparsity (Sec. 5,
+    'Orthogonality with Activation Sparsity'; Broader-impact paragraph: training-free activation sparsity
+    applied inside the routed experts).  The paper names the family (magnitude- or weight-informed
+    thresholds) and gives no formula; the reading taken (parity unpinned by the paper):
+      magnitude        keep h_n  iff  |h_n| >= tau
+      weight-informed  keep h_n  iff  |h_n| * ||w_n||_2 >= tau,  w_n = row n of W_down (the neuron's output direction)
+    A dropped neuron contributes nothing to F(x) = sum_n h_n w_n (Eq. 1).  decide_in_bf16: the comparison is
+    made on h rounded to bfloat16 (and the norm rounded to single precision), the precision in which the
+    device kernels of a bf16 layer hold h when they take the same decision; the surviving h_n keep their
+    full-precision value either way."""
+    h = np.asarray(h, dtype=F64)
+    key = np.abs(round_to_bf16(h)) if decide_in_bf16 else np.abs(h)
+    if weight_informed:
+        norm = np.sqrt(np.sum(np.asarray(w_down_rows, dtype=F64) ** 2, axis=1))
+        if decide_in_bf16:
+            norm = norm.astype(np.float32).astype(F64)
+            key = (key.astype(np.float32) * norm.astype(np.float32)[None, :]).astype(F64)      # one fp32 product
+        else:
+            key = key * norm[None, :]
+    return key >= tau
+
+
+def sparse_expert_output(x, w_gate, w_up, w_down, neurons, tau: float, weight_informed: bool = False,
+                         decide_in_bf16: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+    """One routed expert with neuron-level sparsity: sum over the surviving neurons of h_n w_n (Eq. 1 on the
+    expert's slice, Eq. 3 otherwise).  Returns (output [T, d], keep mask [T, m])."""
+    idx = np.asarray(neurons, dtype=np.int64)
+    h = hidden_states(x, np.asarray(w_gate)[:, idx], np.asarray(w_up)[:, idx])
+    wd = np.asarray(w_down, dtype=F64)[idx, :]
+    keep = neuron_keep_mask(h, wd, tau, weight_informed, decide_in_bf16)
+    return (h * keep) @ wd, keep
+
+
 def moe_forward(x, w_gate, w_up, w_down, neuron_order, rep_neuron, n_experts: int, n_shared: int,
                 top_k: int, u: Optional[np.ndarray] = None, b: Optional[np.ndarray] = None,
-                abs_score: bool = False, sel_override: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+                abs_score: bool = False, sel_override: Optional[np.ndarray] = None,
+                neuron_tau: Optional[float] = None, neuron_weight_informed: bool = False,
+                neuron_decide_in_bf16: bool = False) -> Dict[str, np.ndarray]:
     """F_MoE(x) = E^s(x) + sum_i g_i E^r_i(x)  (Eq. 4) with the gate of Eq. 9:
     g_i = 1 + s'_i u_i if s'_i + b_i is among the top N_k, else 0; s' = Softmax(s), s from Eq. 8.
 
     With u = b = None (both zero) the selection key is s itself: Softmax is strictly
     monotone per row, so the ordering is the same and no rounding of exp() can create a tie.
     `sel_override` [T, N_k] replaces the selection (used to evaluate a different but equally
-    valid choice at near-ties).  Returns y, scores, sel (descending key), gap, gate [T, N_k].
+    valid choice at near-ties).  neuron_tau (not None) applies neuron-level activation sparsity inside the
+    routed experts, never the shared ones (see neuron_keep_mask).
+    Returns y, scores, sel (descending key), gap, gate [T, N_k], kept (surviving / evaluated routed neurons).
     """
     x = np.asarray(x, dtype=F64)
     order = np.asarray(neuron_order, dtype=np.int64)
@@ -309,13 +358,22 @@ def moe_forward(x, w_gate, w_up, w_down, neuron_order, rep_neuron, n_experts: in
         for r in range(t):
             gate[r] = 1.0 + s_prime[r, sel[r]] * uu[sel[r]]
     y = expert_output(x, w_gate, w_up, w_down, order[: n_shared * m])          # E^s
+    kept, evaluated = 0, 0
     for j in range(n_routed):
         neurons = order[(n_shared + j) * m: (n_shared + j + 1) * m]
         rows, slot = np.nonzero(sel == j)
         if rows.size == 0:
             continue
-        y[rows] += gate[rows, slot][:, None] * expert_output(x[rows], w_gate, w_up, w_down, neurons)
-    return {"y": y, "scores": s, "sel": sel, "gap": gap, "gate": gate}
+        if neuron_tau is None:
+            e_out = expert_output(x[rows], w_gate, w_up, w_down, neurons)
+        else:
+            e_out, keep = sparse_expert_output(x[rows], w_gate, w_up, w_down, neurons, neuron_tau,
+                                               neuron_weight_informed, neuron_decide_in_bf16)
+            kept += int(keep.sum())
+            evaluated += keep.size
+        y[rows] += gate[rows, slot][:, None] * e_out
+    return {"y": y, "scores": s, "sel": sel, "gap": gap, "gate": gate,
+            "kept": (kept / evaluated) if evaluated else 1.0}
 
 
 def moe_forward_one_token(x_row, w_gate, w_up, w_down, neuron_order, rep_neuron, n_experts, n_shared,
@@ -324,7 +382,7 @@ def moe_forward_one_token(x_row, w_gate, w_up, w_down, neuron_order, rep_neuron,
     so = None if sel_override is None else np.asarray(sel_override).reshape(1, -1)
     out = moe_forward(np.asarray(x_row)[None, :], w_gate, w_up, w_down, neuron_order, rep_neuron,
                       n_experts, n_shared, top_k, u=u, b=b, abs_score=abs_score, sel_override=so)
-    return {k: v[0] for k, v in out.items()}
+    return {k: (v[0] if isinstance(v, np.ndarray) else v) for k, v in out.items()}
 
 
 def bias_update(b: np.ndarray, counts: np.ndarray, gamma: float = 1e-3) -> np.ndarray:

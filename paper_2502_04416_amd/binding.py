@@ -40,7 +40,7 @@ EXPORTS = [
     "cmoe_last_error", "cmoe_version", "cmoe_forward_timed", "cmoe_hier_forward_timed",
     "cmoe_balanced_assignment", "cmoe_probe_mfma", "cmoe_probe_hbm", "cmoe_get_gate_params", "cmoe_update_bias",
     "cmoe_build_gpu", "cmoe_profile_activations", "cmoe_set_baseline", "cmoe_hier_build", "cmoe_hier_expert",
-    "cmoe_set_tuning", "cmoe_forward_static", "cmoe_static_scratch_bytes", "cmoe_forward_static_max_tokens",
+    "cmoe_set_tuning", "cmoe_set_neuron_sparsity", "cmoe_forward_static", "cmoe_static_scratch_bytes", "cmoe_forward_static_max_tokens",
 ]
 
 
@@ -98,6 +98,7 @@ def load():
     lib.cmoe_hier_expert.argtypes = [vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.cmoe_hier_expert.restype = vp
     lib.cmoe_set_tuning.argtypes = [C.c_char_p, C.c_int]
+    lib.cmoe_set_neuron_sparsity.argtypes = [vp, C.c_int, C.c_float]
     lib.cmoe_forward_static.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     lib.cmoe_static_scratch_bytes.argtypes = []
     lib.cmoe_static_scratch_bytes.restype = sz
@@ -315,6 +316,10 @@ def cmoe_set_baseline(layer: int, enabled: bool) -> None:
     _check(load().cmoe_set_baseline(layer, int(enabled)), "cmoe_set_baseline")
 
 
+def cmoe_set_neuron_sparsity(layer: int, mode: int, tau: float) -> None:
+    _check(load().cmoe_set_neuron_sparsity(layer, int(mode), float(tau)), "cmoe_set_neuron_sparsity")
+
+
 def cmoe_set_tuning(name: str, value: int) -> None:
     _check(load().cmoe_set_tuning(name.encode(), int(value)), "cmoe_set_tuning")
 
@@ -396,11 +401,14 @@ class Layer(_DeviceMixin):
 
     @classmethod
     def from_partition(cls, cfg, w_gate, w_up, w_down, neuron_order, rep_neuron, score_mode: int = 0, upload=True,
-                       baseline=True):
+                       baseline=True, neuron_sparsity=None):
+        """neuron_sparsity: (mode, tau) handed to cmoe_set_neuron_sparsity before the upload."""
         h = cmoe_build_from_partition(make_config(cfg, score_mode=score_mode), w_gate, w_up, w_down, neuron_order, rep_neuron)
         self = cls(h, cfg)
         if not baseline:
             cmoe_set_baseline(h, False)
+        if neuron_sparsity is not None:
+            cmoe_set_neuron_sparsity(h, *neuron_sparsity)
         if upload:
             self.upload()
         return self
@@ -427,6 +435,9 @@ class Layer(_DeviceMixin):
 
     def set_gate_params(self, u, b):
         cmoe_set_gate_params(self.h, u, b)
+
+    def set_neuron_sparsity(self, mode: int, tau: float):
+        cmoe_set_neuron_sparsity(self.h, mode, tau)
 
     def gate_params(self):
         """(u, b) as currently stored in the layer."""

@@ -169,6 +169,7 @@ hipError_t launch_experts(const Engine& e, const void* x, int64_t T, char* ws, c
                           hipStream_t s, int stage) {
   if (T == 0) return hipSuccess;
   if (use_simt_experts(e.dtype)) return launch_experts_simt(e, x, T, ws, L, y, s, stage);
+  if (stage == 2 && e.sparse_mode != 0 && decode_sparse_down_ok(e, T)) return launch_decode_down_sparse(e, T, ws, L, y, s);
   if (stage == 2 && decode_fuses_combine(e, T)) return launch_decode_down_combine(e, T, ws, L, y, s);
   if (decode_path_ok(e, T)) return launch_experts_decode(e, x, T, ws, L, y, s, stage);
   return launch_experts_bf16(e, x, T, ws, L, y, s, stage);
@@ -342,6 +343,12 @@ struct cmoe_layer {
   bool uploaded = false;
   bool in_hier = false;
   bool baseline = true;                        // the dense single-group copy is packed and uploaded too
+  // neuron-level sparsity inside the routed experts (cmoe_set_neuron_sparsity)
+  int sparse_mode = 0;
+  float sparse_tau = 0.0f;
+  bool sparse_reserved = false;                // w2n / nscale are built and belong to the packed weights
+  std::vector<uint8_t> w2n;                    // routed groups' down rows, neuron-major [sum width_pad][d]
+  std::vector<float> nscale;                   // [sum of all width_pad] L2 norm of each neuron's down row
   int64_t calib_routed = -1, calib_used = -1;  // cmoe_hier_build: calibration tokens routed to / used for this expert
   Engine e_moe, e_dense;
   float* d_u = nullptr;
@@ -645,7 +652,7 @@ int cmoe_update_bias(cmoe_layer* L, const int32_t* counts, float gamma) {
 }
 
 // device buffer of a flat layer: [moe W1][moe W2][dense W1][dense W2][router][moe groups][dense groups][u][b]
-struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, total; };
+struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, w2n, nscale, total; };
 static FlatOffsets flat_offsets(const cmoe_layer* L) {
   FlatOffsets o{};
   size_t off = 0;
@@ -659,11 +666,63 @@ static FlatOffsets flat_offsets(const cmoe_layer* L) {
   o.dg = take(L->baseline ? sizeof(GroupDev) * L->dense.groups.size() : 0);
   o.u = take(sizeof(float) * L->n_r);
   o.b = take(sizeof(float) * L->n_r);
+  o.w2n = take(L->sparse_reserved ? L->w2n.size() : 0);
+  o.nscale = take(L->sparse_reserved ? sizeof(float) * L->nscale.size() : 0);
   o.total = off;
   return o;
 }
 
 size_t cmoe_packed_bytes(const cmoe_layer* L) { return L ? flat_offsets(L).total : 0; }
+
+int cmoe_set_neuron_sparsity(cmoe_layer* L, int mode, float tau) {
+  if (!L) return fail(CMOE_EINVAL, "layer is null");
+  if (mode < 0 || mode > 2) return fail(CMOE_EINVAL, "mode must be 0 (off), 1 (magnitude) or 2 (weight-informed)");
+  if (mode != 0 && !(tau >= 0.0f)) return fail(CMOE_EINVAL, "tau must be a non-negative number");
+  if (mode == 0) {
+    L->sparse_mode = 0;
+    return CMOE_OK;
+  }
+  if (L->in_hier) return fail(CMOE_ESTATE, "neuron-level sparsity is not available for layers inside a hierarchy");
+  if (L->cfg.dtype != CMOE_BF16) return fail(CMOE_EINVAL, "neuron-level sparsity needs a bf16 layer");
+  if (!L->sparse_reserved) {
+    if (L->uploaded) return fail(CMOE_ESTATE, "the first cmoe_set_neuron_sparsity must come before cmoe_upload (it adds a "
+                                 "neuron-major copy of the routed down matrices to the packed weights)");
+    CMOE_TRY
+    const PackedSet& ps = L->moe;
+    const int d = L->cfg.d_model;
+    const int first = L->cfg.n_shared > 0 ? 1 : 0;
+    int64_t total_wp = 0, routed_wp = 0;
+    for (size_t g = 0; g < ps.groups.size(); ++g) {
+      total_wp += ps.groups[g].width_pad;
+      if ((int)g >= first) routed_wp += ps.groups[g].width_pad;
+    }
+    L->nscale.assign((size_t)total_wp, 0.0f);
+    L->w2n.assign((size_t)routed_wp * d * 2, 0);
+    const uint16_t* w2 = reinterpret_cast<const uint16_t*>(ps.w2.data());
+    uint16_t* out = reinterpret_cast<uint16_t*>(L->w2n.data());
+    const int64_t routed_row0 = ps.groups[first].w1_row0 / 2;
+    for (size_t g = 0; g < ps.groups.size(); ++g) {
+      const GroupDev& gd = ps.groups[g];
+      const int wp = gd.width_pad, kt2 = wp / TILE_K;
+      const int64_t n0 = gd.w1_row0 / 2;
+      parallel_for(wp, [&](int64_t n) {
+        double ss = 0.0;
+        for (int c = 0; c < d; ++c) {
+          const uint16_t v = w2[gd.w2_off + tiled_offset(c, (int)n, kt2)];
+          const double f = (double)host_bf16_to_f32(v);
+          ss += f * f;
+          if ((int)g >= first) out[(size_t)(n0 - routed_row0 + n) * d + c] = v;
+        }
+        L->nscale[(size_t)(n0 + n)] = (float)std::sqrt(ss);
+      });
+    }
+    L->sparse_reserved = true;
+    CMOE_CATCH
+  }
+  L->sparse_mode = mode;
+  L->sparse_tau = tau;
+  return CMOE_OK;
+}
 
 size_t cmoe_workspace_bytes(const cmoe_layer* L, int64_t max_tokens) {
   if (!L || max_tokens < 0) return 0;
@@ -704,9 +763,13 @@ int cmoe_upload(cmoe_layer* L, void* dev_weights, void* hip_stream) {
   if (e == hipSuccess && L->baseline) e = h2d(base + o.dg, L->dense.groups.data(), sizeof(GroupDev) * L->dense.groups.size(), s);
   if (e == hipSuccess) e = h2d(base + o.u, L->u.data(), sizeof(float) * L->n_r, s);
   if (e == hipSuccess) e = h2d(base + o.b, L->b.data(), sizeof(float) * L->n_r, s);
+  if (e == hipSuccess && L->sparse_reserved) e = h2d(base + o.w2n, L->w2n.data(), L->w2n.size(), s);
+  if (e == hipSuccess && L->sparse_reserved) e = h2d(base + o.nscale, L->nscale.data(), sizeof(float) * L->nscale.size(), s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e != hipSuccess) return fail_hip(e, "uploading packed weights");
   Engine& m = L->e_moe;
+  m.w2n = L->sparse_reserved ? base + o.w2n : nullptr;
+  m.nscale = L->sparse_reserved ? reinterpret_cast<const float*>(base + o.nscale) : nullptr;
   m.w1 = base + o.w1;
   m.w2 = base + o.w2;
   m.wr = base + o.wr;
@@ -755,6 +818,7 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   // (skip: measurement aid, see Tuning::skip_stage; only launches that produce no control data can be left out)
   const int skip = tuning().skip_stage, twice = tuning().repeat_stage;
   for (int n = (skip == 3 ? 0 : twice == 3 ? 2 : 1); n > 0 && err == hipSuccess; --n) err = launch_experts(e, x, T, w, L, y, s, 1);
+  if (err == hipSuccess && e.sparse_mode != 0 && !decode_sparse_down_ok(e, T)) err = launch_mask_hidden(e, T, w, L, s);
   if (err != hipSuccess) return fail_hip(err, "gate/up expert kernel");
   mark(3);
   for (int n = (skip == 4 ? 0 : twice == 4 ? 2 : 1); n > 0 && err == hipSuccess; --n) err = launch_experts(e, x, T, w, L, y, s, 2);
@@ -798,6 +862,8 @@ int cmoe_forward(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev, int32
   Engine e = L->e_moe;
   if (!L->has_u) e.gate_u = nullptr;
   if (!L->has_b) e.gate_b = nullptr;
+  e.sparse_mode = L->sparse_reserved ? L->sparse_mode : 0;
+  e.sparse_tau = L->sparse_tau;
   return run_engine(e, x_dev, T, y_dev, topk_idx_dev, nullptr, scores_dev, counts_dev, workspace_dev,
                     workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
@@ -861,6 +927,8 @@ int cmoe_forward_static(cmoe_layer* L, const void* x_dev, int64_t T, void* y_dev
   Engine e = L->e_moe;
   if (!L->has_u) e.gate_u = nullptr;
   if (!L->has_b) e.gate_b = nullptr;
+  e.sparse_mode = L->sparse_reserved ? L->sparse_mode : 0;
+  e.sparse_tau = L->sparse_tau;
   return run_engine(e, x_dev, T, y_dev, topk_idx_dev, nullptr, scores_dev, counts_dev, ws, STATIC_SCRATCH_BYTES,
                     static_cast<hipStream_t>(hip_stream), nullptr, STATIC_SPLITK_CAP);
 }
@@ -882,6 +950,10 @@ int cmoe_forward_timed(cmoe_layer* L, int dense, const void* x_dev, int64_t T, v
   Engine e = dense ? L->e_dense : L->e_moe;
   if (!L->has_u) e.gate_u = nullptr;
   if (!L->has_b) e.gate_b = nullptr;
+  if (!dense) {
+    e.sparse_mode = L->sparse_reserved ? L->sparse_mode : 0;
+    e.sparse_tau = L->sparse_tau;
+  }
   return run_engine_timed(e, x_dev, T, y_dev, workspace_dev, workspace_bytes, static_cast<hipStream_t>(hip_stream), stage_ms);
 }
 
@@ -898,6 +970,7 @@ int cmoe_hier_create(cmoe_layer* const* experts, int32_t n_outer, int32_t outer_
     if (experts[e]->uploaded || experts[e]->in_hier) return fail(CMOE_ESTATE, "expert %d is already uploaded or owned", e);
     if (std::memcmp(&experts[e]->cfg, &experts[0]->cfg, sizeof(cmoe_config)) != 0)
       return fail(CMOE_EINVAL, "expert %d has a different configuration", e);
+    if (experts[e]->sparse_mode != 0) return fail(CMOE_EINVAL, "expert %d has neuron-level sparsity switched on", e);
     if (experts[e]->baseline != experts[0]->baseline)
       return fail(CMOE_EINVAL, "expert %d differs from expert 0 in cmoe_set_baseline", e);
   }

@@ -112,6 +112,14 @@ struct Engine {
   const float* gate_u = nullptr;   // [n_scored] or null
   const float* gate_b = nullptr;   // [n_scored] or null
   const float* lin_off = nullptr;  // [n_lin] or null
+  // Neuron-level activation sparsity inside the routed groups (flat bf16 layers): a hidden activation h_n of a
+  // routed group survives iff |h_n| * nscale[n] >= sparse_tau, nscale = 1 (mode 1) or the L2 norm of the
+  // neuron's row of W_down (mode 2).  w2n: the routed groups' down matrices once more, neuron-major
+  // [sum of routed width_pad][d], so that a dropped neuron's weights are never read.
+  int sparse_mode = 0;             // 0: off
+  float sparse_tau = 0.0f;
+  const void* w2n = nullptr;
+  const float* nscale = nullptr;   // [sum of all width_pad], indexed by w1_row0 / 2 + neuron
   int S_all() const { return n_always + S_dyn; }
   // One always-on group and nothing routed (the dense baseline): slot t is token t with weight 1, so the
   // down contraction writes y itself.  A routed layer with one slot per token (top-1, no shared expert) does
@@ -189,6 +197,11 @@ bool decode_path_ok(const Engine& e, int64_t T);
 bool decode_front_runs_shared(const Engine& e, int64_t T);   // the front end's second launch also runs group 0's gate/up
 bool decode_fuses_combine(const Engine& e, int64_t T);   // the down kernel also does the weighted sum over slots
 hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
+// Neuron-level sparsity (Engine::sparse_mode): the down + combine kernel of one or two tokens that reads only the
+// surviving neurons' rows, and for every other batch the kernel that zeroes the dropped activations in H.
+bool decode_sparse_down_ok(const Engine& e, int64_t T);
+hipError_t launch_decode_down_sparse(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
+hipError_t launch_mask_hidden(const Engine& e, int64_t T, char* ws, const WsLayout& L, hipStream_t s);
 hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L, void* y,
                                  hipStream_t s, int stage);
 // Upper bound of work items of grouped GEMM `which` (1: gate/up, 2: down) for T tokens.

@@ -17,6 +17,13 @@
 
 namespace cmoe {
 
+// The LDS operations of one wave complete in issue order: waiting for them (and keeping the compiler from
+// moving LDS accesses across) is enough to order a wave's own LDS updates.
+__device__ __forceinline__ void wave_lds_sync_decode() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // Which unit is this workgroup?  Returns false when past the end of the list.
 __device__ __forceinline__ bool find_unit(const DecArgs& p, int units_single, int& g, int& local, int& seg0, int& cnt,
                                           int& wp, int64_t& hoff) {
@@ -213,6 +220,159 @@ __global__ __launch_bounds__(DC_WAVES * 64) void decode_down_combine_kernel(DecA
 }
 
 
+// ---- neuron-level activation sparsity inside the routed experts (Sec. 5; Eq. 1 restricted to surviving neurons) ----
+// A hidden activation h_n of a routed group survives iff |h_n| * scale_n >= tau, decided on the bf16 value the
+// gate/up kernels stored (scale_n = 1, or the L2 norm of the neuron's row of W_down).
+__device__ __forceinline__ bool neuron_survives(bf16_t v, int mode, float scale, float tau) {
+  const float key = fabsf(bf16_to_f32(v)) * (mode == 2 ? scale : 1.0f);
+  return key >= tau;                                          // (a NaN is dropped)
+}
+
+// Every batch but the one- and two-token ones: the dropped activations are zeroed in H after the gate/up
+// contraction, so that the layer computes the same function at every batch size; one workgroup per slot row.
+__global__ __launch_bounds__(256) void mask_hidden_kernel(bf16_t* __restrict__ h, const GroupDev* __restrict__ groups,
+                                                          const int32_t* __restrict__ seg_off,
+                                                          const int64_t* __restrict__ h_off,
+                                                          const float* __restrict__ nscale, int G, int n_always, int mode,
+                                                          float tau) {
+  const int row = blockIdx.x;
+  if (row >= seg_off[G]) return;
+  const int g = find_group(seg_off, G, row);
+  if (g < n_always) return;                                   // shared experts are never sparsified
+  const int wp = groups[g].width_pad;
+  const int64_t base = h_off[g] + (int64_t)(row - seg_off[g]) * wp;
+  const int n0 = groups[g].w1_row0 / 2;
+  for (int n = threadIdx.x; n < wp; n += 256)
+    if (!neuron_survives(h[base + n], mode, nscale[n0 + n], tau)) h[base + n] = 0;
+}
+
+// One or two tokens: down projection + weighted sum over slots that reads only the surviving neurons' weights.
+// A workgroup owns 16 output columns of both tokens.  The always-on groups go through the matrix cores as in
+// decode_down_combine_kernel.  For a routed group every thread looks at one neuron: if it survives, the thread
+// reads the 32 bytes of that neuron's row of the neuron-major copy of W_down that belong to the workgroup's
+// columns and adds h_n * w_n (Eq. 1); the rows of dropped neurons are never touched.  The per-thread sums are
+// added across the wave by exchanges in a fixed pattern, across waves in wave order: deterministic.
+// Column blocks are dealt so that the four workgroups sharing a 128-byte line of a row run on one XCD.
+constexpr int DS_WAVES = 16;
+__global__ __launch_bounds__(DS_WAVES * 64) void decode_down_sparse_kernel(DecArgs p, const float* __restrict__ w_by_slot,
+                                                                           bf16_t* __restrict__ y_out,
+                                                                           const bf16_t* __restrict__ w2n,
+                                                                           const float* __restrict__ nscale, int n_always,
+                                                                           int mode, float tau, int cb_per_xcd) {
+  __shared__ float yacc[DS_WAVES][2][16];
+  __shared__ int32_t item0[MAX_GROUPS + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int cb = (blockIdx.x & 7) * cb_per_xcd + (blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= cb_per_xcd || cb >= p.d / 16) return;
+  const int c0 = cb * 16;
+  if (lane < 32) yacc[wave][lane >> 4][lane & 15] = 0.0f;
+  if (wave == 0) {
+    int run0 = 0;
+#pragma unroll
+    for (int k = 0; k < MAX_GROUPS / 64; ++k) {
+      const int g = lane + 64 * k;
+      int n = 0;
+      if (g < n_always && p.seg_off[g + 1] > p.seg_off[g]) n = cdiv(p.groups[g].width_pad / 32, DC_CH);
+      const int inc = wave_incl_scan(n, lane);
+      if (g < p.G) item0[g] = run0 + inc - n;
+      run0 += __shfl(inc, 63, 64);
+    }
+    if (lane == 0) item0[p.G] = run0;
+  }
+  __syncthreads();
+  // ---- always-on groups: 16 columns x 8 K steps per work item, matrix cores ----
+  const int n_items = item0[p.G];
+  for (int u = wave; u < n_items; u += DS_WAVES) {
+    const int g = find_group(item0, p.G, u);
+    const int ks0 = (u - item0[g]) * DC_CH;
+    const int seg0 = p.seg_off[g], cnt = p.seg_off[g + 1] - seg0;
+    const int wp = p.groups[g].width_pad;
+    const int ns = min(DC_CH, wp / 32 - ks0);
+    const int kadv = p.tiled ? TILE_ELEMS : 32;
+    const bf16_t* wrow = p.w2 + p.groups[g].w2_off +
+                         (p.tiled ? tiled_offset(c0 + r16, ks0 * 32 + kq * 8, wp / TILE_K)
+                                  : (int64_t)(c0 + r16) * wp + kq * 8 + ks0 * 32);
+    const bool ok = r16 < cnt;
+    const bf16_t* hrow = p.h + p.h_off[g] + kq * 8 + ks0 * 32 + (int64_t)(ok ? r16 : 0) * wp;
+    bf16x8_t a[DC_CH], b[DC_CH];
+#pragma unroll
+    for (int s = 0; s < DC_CH; ++s) {
+      a[s] = s < ns ? ld_frag(wrow + s * kadv) : zero_frag();
+      b[s] = (ok && s < ns) ? ld_frag(hrow + s * 32) : zero_frag();
+    }
+    const int tok = ok ? p.slot2tok[seg0 + r16] : -1;
+    const float wt = ok ? w_by_slot[seg0 + r16] : 0.0f;
+    floatx4_t acc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < DC_CH; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], b[s], acc, 0, 0, 0);
+    if (tok >= 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) yacc[wave][tok][kq * 4 + i] += wt * acc[i];
+    }
+  }
+  // ---- routed groups: one neuron per thread, surviving rows only ----
+  float a0[16], a1[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { a0[i] = 0.0f; a1[i] = 0.0f; }
+  const int routed_row0 = p.groups[n_always].w1_row0 / 2;
+  for (int g = n_always; g < p.G; ++g) {
+    const int seg0 = p.seg_off[g], cnt = p.seg_off[g + 1] - seg0;
+    if (cnt == 0) continue;
+    const int wp = p.groups[g].width_pad;
+    const int64_t hoff = p.h_off[g];
+    const int n0 = p.groups[g].w1_row0 / 2;
+    for (int col = 0; col < cnt; ++col) {
+      const int tok = p.slot2tok[seg0 + col];
+      const float wt = w_by_slot[seg0 + col];
+      for (int n = tid; n < wp; n += DS_WAVES * 64) {
+        const bf16_t hv = p.h[hoff + (int64_t)col * wp + n];
+        if (!neuron_survives(hv, mode, nscale[n0 + n], tau)) continue;
+        const uint4* src = reinterpret_cast<const uint4*>(w2n + (int64_t)(n0 - routed_row0 + n) * p.d + c0);
+        const uint4 q0 = src[0], q1 = src[1];
+        const uint32_t w[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+        const float coef = wt * bf16_to_f32(hv);
+        if (tok == 0) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            a0[2 * i] = fmaf(coef, __uint_as_float(w[i] << 16), a0[2 * i]);
+            a0[2 * i + 1] = fmaf(coef, __uint_as_float(w[i] & 0xffff0000u), a0[2 * i + 1]);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            a1[2 * i] = fmaf(coef, __uint_as_float(w[i] << 16), a1[2 * i]);
+            a1[2 * i + 1] = fmaf(coef, __uint_as_float(w[i] & 0xffff0000u), a1[2 * i + 1]);
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    a0[i] = wave_sum(a0[i]);
+    a1[i] = wave_sum(a1[i]);
+  }
+  wave_lds_sync_decode();                                   // the MFMA part's LDS updates of this wave are done
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      yacc[wave][0][i] += a0[i];
+      yacc[wave][1][i] += a1[i];
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < (int)p.T * 16; e += DS_WAVES * 64) {
+    const int t = e >> 4, cc = e & 15;
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < DS_WAVES; ++w) s += yacc[w][t][cc];
+    y_out[(int64_t)t * p.d + c0 + cc] = f32_to_bf16(s);
+  }
+}
+
 // Up to 16 tokens (one MFMA token tile) the weight-streaming kernels are the fastest form of both
 // contractions; from 17 tokens on a second token tile would double their register footprint, and the tiled
 // contraction on skinny tiles is as fast for the routed layer and 10-20 us faster for the dense one
@@ -280,6 +440,27 @@ hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, cons
   bf16_t* yo = static_cast<bf16_t*>(y);
   if (T > 16) hipLaunchKernelGGL((decode_down_combine_kernel<2>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
   else hipLaunchKernelGGL((decode_down_combine_kernel<1>), dim3(e.d / 16), dim3(DC_WAVES * 64), 0, s, a, wbs, yo);
+  return hipGetLastError();
+}
+
+bool decode_sparse_down_ok(const Engine& e, int64_t T) {
+  return e.sparse_mode != 0 && e.w2n != nullptr && T >= 1 && T <= 2 && decode_fuses_combine(e, T);
+}
+
+hipError_t launch_decode_down_sparse(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s) {
+  const DecArgs a = make_dec_args(e, nullptr, T, ws, L, y);
+  const float* wbs = reinterpret_cast<const float*>(ws + L.w_by_slot);
+  const int per_xcd = cdiv(e.d / 16, 8);
+  hipLaunchKernelGGL(decode_down_sparse_kernel, dim3(8 * per_xcd), dim3(DS_WAVES * 64), 0, s, a, wbs, static_cast<bf16_t*>(y),
+                     static_cast<const bf16_t*>(e.w2n), e.nscale, e.n_always, e.sparse_mode, e.sparse_tau, per_xcd);
+  return hipGetLastError();
+}
+
+hipError_t launch_mask_hidden(const Engine& e, int64_t T, char* ws, const WsLayout& L, hipStream_t s) {
+  if (e.sparse_mode == 0 || e.nscale == nullptr || e.G <= e.n_always) return hipSuccess;
+  hipLaunchKernelGGL(mask_hidden_kernel, dim3((unsigned)(T * e.S_all())), dim3(256), 0, s, reinterpret_cast<bf16_t*>(ws + L.h),
+                     e.groups, reinterpret_cast<const int32_t*>(ws + L.seg_off), reinterpret_cast<const int64_t*>(ws + L.h_off),
+                     e.nscale, e.G, e.n_always, e.sparse_mode, e.sparse_tau);
   return hipGetLastError();
 }
 

@@ -37,12 +37,34 @@ def tail_tokens(topk, n_groups, rows=128, extra=None):
     return np.array(sorted(keep), dtype=np.int64)
 
 
+def fragile_sparsity_tokens(cfg, weights, part, x, sel, tau, weight_informed, rel=5e-6):
+    """Tokens for which the keep/drop decision of neuron-level sparsity is not robust: some neuron of a selected
+    routed expert has |h| so close to a bfloat16 rounding boundary next to the threshold that fp32 and fp64
+    evaluation may round it to different sides.  (Like near-ties of the router, these are counted and excused.)"""
+    wg, wu, wd = weights
+    order = np.asarray(part["neuron_order"], dtype=np.int64)
+    m, n_s = cfg.m, cfg.n_shared
+    bad = np.zeros(x.shape[0], dtype=bool)
+    for j in range(cfg.n_routed):
+        rows = np.nonzero((sel == j).any(axis=1))[0]
+        if rows.size == 0:
+            continue
+        idx = order[(n_s + j) * m:(n_s + j + 1) * m]
+        h = O.hidden_states(x[rows], wg[:, idx], wu[:, idx])
+        lo = O.neuron_keep_mask(h * (1 - rel), wd[idx], tau, weight_informed, True)
+        hi = O.neuron_keep_mask(h * (1 + rel), wd[idx], tau, weight_informed, True)
+        bad[rows] |= (lo != hi).any(axis=1)
+    return bad
+
+
 def check_flat(cfg, weights, part, x, out, u=None, b=None, sample=None, score_tol=None, abs_score=False,
-               exact_ties_strict=False):
+               exact_ties_strict=False, neuron=None):
     """out: dict from binding.Layer.forward.  sample: token indices whose outputs are compared
     (None = all).  exact_ties_strict: a token whose k-th and (k+1)-th keys are *equal* (two experts with
-    the same representative neuron) is not excused: the lower expert id has to win.  Returns a small
-    report dict."""
+    the same representative neuron) is not excused: the lower expert id has to win.  neuron: (tau,
+    weight_informed) of the neuron-level sparsity inside the routed experts; the oracle decides on the
+    bfloat16 value of h as the kernels do, and tokens whose decision is not robust to fp32 rounding are
+    excused and counted.  Returns a small report dict."""
     wg, wu, wd = weights
     T = x.shape[0]
     order, reps = part["neuron_order"], part["rep_neuron"]
@@ -77,13 +99,20 @@ def check_flat(cfg, weights, part, x, out, u=None, b=None, sample=None, score_to
     assert out["counts"].sum() == T * cfg.top_k
     # outputs
     idx = np.arange(T) if sample is None else np.asarray(sample)
+    kw, fragile = {}, 0
+    if neuron is not None:
+        kw = {"neuron_tau": float(neuron[0]), "neuron_weight_informed": bool(neuron[1]), "neuron_decide_in_bf16": cfg.dtype == "bf16"}
+        bad = fragile_sparsity_tokens(cfg, weights, part, x[idx], out["topk"][idx], float(neuron[0]), bool(neuron[1]))
+        fragile = int(bad.sum())
+        idx = idx[~bad]
     ref = O.moe_forward(x[idx], wg, wu, wd, order, reps, cfg.n_experts, cfg.n_shared, cfg.top_k, u=u, b=b,
-                        abs_score=abs_score, sel_override=out["topk"][idx])
+                        abs_score=abs_score, sel_override=out["topk"][idx], **kw)
     err = tokenwise_rel_err(out["y"][idx], ref["y"])
     tol = TOL[cfg.dtype]
     assert err.max() <= tol, "max per-token relative error %g > %g (token %d)" % (err.max(), tol, idx[int(err.argmax())])
     return {"near_ties": int(excused.sum()), "exact_ties": int((gap == 0.0).sum()), "checked_tokens": int(len(idx)),
             "max_rel_err": float(err.max()), "score_err": float(s_err),
+            **({"kept": float(ref["kept"]), "fragile_tokens": fragile} if neuron is not None else {}),
             "min_gap": float(gap.min()) if T else np.inf, "union": int((want_counts > 0).sum())}
 
 

@@ -478,6 +478,78 @@ def test_abs_score_ranks_experts_by_magnitude():
     assert np.array_equal(hz["sub_sel"][:, 0, :], mag["sel"]) and np.allclose(hz["y"], mag["y"], rtol=1e-12, atol=1e-12)
 
 
+def test_bf16_rounding_matches_torch():
+    r = _rng(60)
+    a = np.concatenate([r.standard_normal(20000) * 5, [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.0e-39, 65280.0]])
+    want = torch.from_numpy(a.astype(np.float32)).bfloat16().float().numpy().astype(np.float64)
+    assert np.array_equal(O.round_to_bf16(a), want)
+    # ties to even by hand: 1 + 2^-8 lies halfway between 1 and 1 + 2^-7 -> 1; 1 + 3 * 2^-8 -> 1 + 2^-6
+    assert O.round_to_bf16(np.array([1.00390625, 1.01171875])).tolist() == [1.0, 1.015625]
+
+
+def test_neuron_sparsity_hand_example():
+    """Neuron-level activation sparsity inside a routed expert (Sec. 5), by hand.  Expert of two neurons on
+    d = 1, x = 1: gate weights (1, 2), up weights (1, 0.1), so h = (silu(1), 0.1 silu(2)) = (0.7311, 0.1762);
+    down rows w_0 = (1, 0), w_1 = (30, 40) with norms 1 and 50.
+      magnitude, tau = 0.5        keeps neuron 0 only      -> y = h_0 w_0
+      weight-informed, tau = 0.8  |h| ||w|| = (0.73, 8.8)  -> keeps neuron 1 only -> y = h_1 w_1
+    The two criteria keep opposite neurons, so a swapped criterion or a transposed norm fails."""
+    wg, wu = np.array([[1.0, 2.0]]), np.array([[1.0, 0.1]])
+    wd = np.array([[1.0, 0.0], [30.0, 40.0]])
+    x = np.array([[1.0]])
+    h0 = 1.0 / (1.0 + math.exp(-1.0))
+    h1 = 0.1 * 2.0 / (1.0 + math.exp(-2.0))
+    y, keep = O.sparse_expert_output(x, wg, wu, wd, [0, 1], 0.5)
+    assert keep.tolist() == [[True, False]] and np.allclose(y, [[h0, 0.0]], rtol=1e-14)
+    y, keep = O.sparse_expert_output(x, wg, wu, wd, [0, 1], 0.8, weight_informed=True)
+    assert keep.tolist() == [[False, True]] and np.allclose(y, [[30 * h1, 40 * h1]], rtol=1e-14)
+    # the boundary belongs to the kept side, and the decision can be taken on the bfloat16 value of h:
+    # bf16(h_0) = 0.73046875 < h_0 = 0.7310585..., so a threshold between them separates the two
+    tau = 0.7308
+    assert O.sparse_expert_output(x, wg, wu, wd, [0, 1], tau)[1].tolist() == [[True, False]]
+    y, keep = O.sparse_expert_output(x, wg, wu, wd, [0, 1], tau, decide_in_bf16=True)
+    assert keep.tolist() == [[False, False]] and np.allclose(y, 0.0)
+    assert O.sparse_expert_output(x, wg, wu, wd, [0, 1], 0.73046875, decide_in_bf16=True)[1].tolist() == [[True, False]]
+
+
+@pytest.mark.parametrize("weight_informed", [False, True])
+def test_neuron_sparsity_in_the_forward_against_a_neuron_loop(weight_informed):
+    """F_MoE with neuron-level sparsity = shared experts in full + for every selected routed expert the sum over
+    its neurons that pass the threshold of g h_n w_n (Eq. 1 inside Eq. 4), written out as loops here.  tau = 0
+    changes nothing; a threshold above every |h| leaves the shared experts only."""
+    n_experts, n_shared, top_k = 6, 2, 2
+    wg, wu, wd = _tiny_layer(61)
+    x = _rng(62).standard_normal((12, 8))
+    order, reps = _random_partition(63, 12, n_experts, n_shared)
+    u = _rng(64).uniform(-0.5, 0.5, 4)
+    plain = O.moe_forward(x, wg, wu, wd, order, reps, n_experts, n_shared, top_k, u=u)
+    zero = O.moe_forward(x, wg, wu, wd, order, reps, n_experts, n_shared, top_k, u=u, neuron_tau=0.0,
+                         neuron_weight_informed=weight_informed)
+    assert np.allclose(zero["y"], plain["y"], rtol=1e-13, atol=1e-13) and zero["kept"] == 1.0
+    none = O.moe_forward(x, wg, wu, wd, order, reps, n_experts, n_shared, top_k, u=u, neuron_tau=1e9,
+                         neuron_weight_informed=weight_informed)
+    assert np.allclose(none["y"], O.expert_output(x, wg, wu, wd, order[:4]), rtol=1e-13, atol=1e-13) and none["kept"] == 0.0
+    tau = 0.4
+    out = O.moe_forward(x, wg, wu, wd, order, reps, n_experts, n_shared, top_k, u=u, neuron_tau=tau,
+                        neuron_weight_informed=weight_informed)
+    assert np.array_equal(out["sel"], plain["sel"]) and np.array_equal(out["gate"], plain["gate"])
+    kept = total = 0
+    for t in range(12):
+        want = np.zeros(8)
+        for i in order[:4]:
+            want += _loops_hidden(x[t:t + 1], wg[:, [i]], wu[:, [i]])[0, 0] * wd[i]
+        for k, j in enumerate(plain["sel"][t]):
+            for i in order[(n_shared + j) * 2:(n_shared + j + 1) * 2]:
+                h = _loops_hidden(x[t:t + 1], wg[:, [i]], wu[:, [i]])[0, 0]
+                crit = abs(h) * (math.sqrt(sum(v * v for v in wd[i])) if weight_informed else 1.0)
+                total += 1
+                if crit >= tau:
+                    kept += 1
+                    want += plain["gate"][t, k] * h * wd[i]
+        assert np.allclose(out["y"][t], want, rtol=1e-12, atol=1e-12)
+    assert 0 < kept < total and out["kept"] == pytest.approx(kept / total)
+
+
 def test_gate_neutral_at_initialisation():
     """u = 0 and b = 0 give g = 1 and the same selection as ranking by s (Softmax is monotone)."""
     wg, wu, wd = _tiny_layer(22, d=8, d_h=24)
