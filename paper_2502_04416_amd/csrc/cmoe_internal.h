@@ -175,7 +175,8 @@ hipError_t launch_combine(const Engine& e, int64_t T, char* ws, const WsLayout& 
 
 // Tile sizes of the two grouped GEMMs (the permute kernel builds their work lists from them):
 // which = 1: rows of a gate/up tile, 2: rows of a down tile, 3: packed gate/up rows (columns of the
-// product) of a gate/up tile, 4: columns of a down tile.
+// product) of a gate/up tile, 4: columns of a down tile, 5 / 6: rows per height step when the gate/up / down
+// contraction runs tiles of dynamic height, else 0.
 int gemm_tile(const Engine& e, int64_t T, int which);
 bool use_simt_experts(int dtype);
 int bf16_gemm_tile(int which, const Engine& e, int64_t T);

@@ -54,8 +54,9 @@ __global__ __launch_bounds__(512) void decode_gate_up_kernel(DecArgs p) {
   __shared__ DecGateUpRed<NTT> red;
   int g, local, seg0, cnt, wp;
   int64_t hoff;
-  if (!find_unit(p, p.single ? p.groups[0].width_pad / 16 : 0, g, local, seg0, cnt, wp, hoff)) return;
-  decode_gate_up_unit<NTT, KSTEPS>(p, g, local, seg0, cnt, wp, hoff, red);
+  if (!find_unit(p, p.single ? p.groups[0].width_pad / p.unit1 : 0, g, local, seg0, cnt, wp, hoff)) return;
+  if (p.unit1 == 8) decode_gate_up_unit8<NTT, KSTEPS>(p, g, local, seg0, cnt, wp, hoff, red);
+  else decode_gate_up_unit<NTT, KSTEPS>(p, g, local, seg0, cnt, wp, hoff, red);
 }
 
 // ---- down: Y[slot][c] = sum_n H[slot][n] * Wdown[n][c] for 16 output columns of one group --------------
@@ -394,9 +395,21 @@ bool decode_fuses_combine(const Engine& e, int64_t T) {
   return !(e.G == 1 && e.n_always == 1) && e.S_all() > 1;
 }
 
+// 8-neuron units when they still number at most one per CU (the always-on groups count unless the routing
+// front end runs them).  Measured at one token: four routed experts of 448 neurons (224 units of 8) 10.1 ->
+// 8.9 us for the gate/up launch, three of 688 (258 units of 8) 12.0 -> 14.8 us; at 16 tokens 28.7 -> 32.4 us.
+// CMOE_DECODE_SPLIT = 8 / 16 forces a size.
+int decode_unit_neurons(const Engine& e, int64_t T) {
+  const int forced = tuning().decode_split;
+  if (forced == 8 || forced == 16) return forced;
+  const int64_t dyn_groups = std::min<int64_t>(T * e.S_dyn, e.G - e.n_always);
+  const int64_t groups = dyn_groups + (decode_front_runs_shared(e, T) ? 0 : e.n_always);
+  return groups * (e.max_width_pad / 8) <= 256 ? 8 : 16;
+}
+
 int64_t decode_unit_bound(const Engine& e, int64_t T, int which) {
   const int64_t dyn_groups = std::min<int64_t>(T * e.S_dyn, e.G - e.n_always);
-  const int64_t per_group = which == 1 ? e.max_width_pad / 16 : e.d / 16;
+  const int64_t per_group = which == 1 ? e.max_width_pad / decode_unit_neurons(e, T) : e.d / 16;
   return std::max<int64_t>((e.n_always + dyn_groups) * per_group, 1);
 }
 
@@ -430,6 +443,7 @@ DecArgs make_dec_args(const Engine& e, const void* x, int64_t T, char* ws, const
   a.T = T;
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
+  a.unit1 = decode_unit_neurons(e, T);
   return a;
 }
 
@@ -469,7 +483,7 @@ hipError_t launch_experts_decode(const Engine& e, const void* x, int64_t T, char
   DecArgs a = make_dec_args(e, x, T, ws, L, y);
   if (stage != 2) {
     a.work = reinterpret_cast<const int32_t*>(ws + L.work1);
-    const int64_t nb = a.single ? e.max_width_pad / 16 : decode_unit_bound(e, T, 1);
+    const int64_t nb = a.single ? e.max_width_pad / a.unit1 : decode_unit_bound(e, T, 1);
     hipError_t err = launch_gate_up<1>(a, e.d / 256, nb, s);
     if (err != hipSuccess || stage == 1) return err;
   }

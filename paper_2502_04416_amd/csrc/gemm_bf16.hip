@@ -82,7 +82,11 @@ constexpr int min_waves_per_simd(int bm, int bn, int bkt, int stages, int nw) {
   return (stages >= 2 && nw == 4 && bm * bn >= 256 * 128 && stages * (bm + bn) * bkt * 2 <= 80 * 1024) ? 2 : 1;
 }
 
-template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE>
+// DYN: the number of 32-row blocks of the tile that hold rows of the segment is found at run time and the rest
+// of the kernel runs in the instantiation for exactly that many blocks per wave (MI_ACT below; the blocks are
+// dealt to the WGM wave rows in turn): blocks past the end of a ragged segment are neither fetched nor
+// multiplied, so a tile costs what its rows cost, in steps of 32 * WGM rows.
+template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE, bool DYN = false>
 __global__ __launch_bounds__(WGM* WGN * 64)
 __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* WGN)))) void grouped_gemm_bf16_dma(GemmArgs p) {
   constexpr int NW = WGM * WGN;
@@ -173,15 +177,26 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
   const int mt = sr * GM + rem % rows_in_sr;
   const int nt = rem / rows_in_sr;
 
+  using std::integral_constant;
+  using std::false_type;
+  using std::true_type;
+  auto body = [&](auto act_tag) {
+  constexpr int MI_ACT = decltype(act_tag)::value;              // 32-row blocks per wave that are computed
+  // tile rows that are fetched: with a dynamic height the 32-row blocks of the tile are dealt to the WGM wave
+  // rows in turn (wave row wm owns blocks wm, wm + WGM, ...), so MI_ACT blocks per wave cover the first
+  // MI_ACT * WGM blocks of the tile; DMA instructions per wave that cover them:
+  constexpr int A_ACT = DYN ? (MI_ACT * WGM * 32 + RPI * NW - 1) / (RPI * NW) : A_CH;
+  auto row_block = [&](int mi) { return DYN ? mi * WGM + wm : wm * MI + mi; };
+  constexpr int LPT_ACT = A_ACT + B_CH;
   // every offset a row source is read at stays below K_full rounded up to a whole K tile
   const bool use_zero_row = p.zero_pad && K_full + BKT <= ZERO_ROW_ELEMS;
   // per-lane sources: transfer i of this wave covers tile rows rg*8 .. rg*8+7, rg = wave + i*NW; the lane
   // writes physical chunk lane%8 of row rg*8 + lane/8 and therefore fetches logical chunk (lane%8) ^ swz(row)
-  const bf16_t* a_src[A_CH];
+  const bf16_t* a_src[A_ACT];
   const bf16_t* b_src[B_CH];
-  int a_coff[A_CH], b_coff[B_CH];                      // element offset of the lane's chunk inside a 64-wide K tile
+  int a_coff[A_ACT], b_coff[B_CH];                      // element offset of the lane's chunk inside a 64-wide K tile
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
+  for (int i = 0; i < A_ACT; ++i) {
     const int row = (wave + i * NW) * RPI + lane / CPR;
     a_coff[i] = (((lane % CPR) ^ ((row >> SWZ_SHIFT) & (CPR - 1))) << 3);
     int r = mt * BM + row;
@@ -236,16 +251,16 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
   };
   auto issue_tile_a = [&](int kt) {
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) issue_a(kt, i, true);
+    for (int i = 0; i < A_ACT; ++i) issue_a(kt, i, true);
   };
   auto issue_tile_b = [&](int kt) {
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) issue_b(kt, i, true);
   };
 
-  floatx16_t acc[MI][NI];
+  floatx16_t acc[MI_ACT][NI];
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi)
+  for (int mi = 0; mi < MI_ACT; ++mi)
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -277,10 +292,10 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
     constexpr int AHEAD = decltype(ahead_tag)::value;
     constexpr bool MAYBE_LAST = decltype(last_tag)::value;   // a tile fetched in this step may be tile KT-1
     if (HR) {
-      if (AHEAD >= 1) wait_vmcnt<A_CH>();            // A(kt+1) may still be in flight; A(kt), B(kt) are older
+      if (AHEAD >= 1) wait_vmcnt<A_ACT>();           // A(kt+1) may still be in flight; A(kt), B(kt) are older
       else wait_vmcnt<0>();
     } else {
-      if (AHEAD >= 1) wait_vmcnt<HR ? 0 : (STAGES - 2) * LPT>();
+      if (AHEAD >= 1) wait_vmcnt<HR ? 0 : (STAGES - 2) * LPT_ACT>();
       else wait_vmcnt<0>();
     }
     // Bare barrier: __syncthreads() would add a fence that drains every outstanding load (vmcnt(0)) and with
@@ -292,11 +307,11 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
     const bf16_t* as = a_slot(kt);
     const bf16_t* bs = b_slot(kt);
     constexpr int NKS = BKT / 16;                    // sub-steps (one MFMA depth each)
-    constexpr int NMS = MI * NI;                     // MFMAs per sub-step
+    constexpr int NMS = MI_ACT * NI;                 // MFMAs per sub-step
     constexpr int NM = NKS * NMS;                    // MFMAs per step
     // DMA instructions of this step, in issue order: half ring B(kt+1) then A(kt+2); whole ring A then B
-    constexpr int N_FIRST = HR ? B_CH : A_CH;
-    constexpr int L = A_CH + B_CH;
+    constexpr int N_FIRST = HR ? B_CH : A_ACT;
+    constexpr int L = A_ACT + B_CH;
     auto issue_nth = [&](int i) {
       if (HR) {
         if (i < N_FIRST) issue_b(kt + 1, i, MAYBE_LAST);
@@ -306,14 +321,18 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
         else issue_b(kt + STAGES - 1, i - N_FIRST, MAYBE_LAST);
       }
     };
-    // fragment f of sub-step ks: f < MI is a row block of A, the rest column blocks of B
-    bf16x8_t af[2][MI], bfr[2][NI];
-    auto load_frag = [&](int ks, int f, int set) {
-      if (f < MI) af[set][f] = *reinterpret_cast<const bf16x8_t*>(as + lds_off_t<BKT>(wm * TM + f * 32 + l32, ks * 2 + lh));
-      else bfr[set][f - MI] = *reinterpret_cast<const bf16x8_t*>(bs + lds_off_t<BKT>(wn * TN + (f - MI) * 32 + l32, ks * 2 + lh));
+    // Fragments of a sub-step in the order of their first use by its MFMAs (row block mi is first needed by
+    // MFMA mi * NI, column block ni by MFMA ni): A0, B0 .. B(NI-1), A1, A2, ...  LDS reads complete in issue
+    // order, so the wait in front of an MFMA covers exactly the reads issued up to its own operands; with the
+    // B fragments last, the first MFMA of every sub-step waited for all of them.
+    bf16x8_t af[2][MI_ACT], bfr[2][NI];
+    auto load_frag = [&](int ks, int k, int set) {
+      const int mi = k == 0 ? 0 : k - NI;               // valid when k == 0 or k > NI
+      if (k == 0 || k > NI) af[set][mi] = *reinterpret_cast<const bf16x8_t*>(as + lds_off_t<BKT>(row_block(mi) * 32 + l32, ks * 2 + lh));
+      else bfr[set][k - 1] = *reinterpret_cast<const bf16x8_t*>(bs + lds_off_t<BKT>(wn * TN + (k - 1) * 32 + l32, ks * 2 + lh));
     };
 #pragma unroll
-    for (int f = 0; f < MI + NI; ++f) load_frag(0, f, 0);
+    for (int f = 0; f < MI_ACT + NI; ++f) load_frag(0, f, 0);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       const int cur = ks & 1;
@@ -326,8 +345,8 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
         // fragments of the next sub-step, spread over this sub-step's MFMAs (several per MFMA only when
         // a sub-step has fewer MFMAs than fragments)
 #pragma unroll
-        for (int f = 0; f < MI + NI; ++f)
-          if (ks + 1 < NKS && f * NMS / (MI + NI) == j) load_frag(ks + 1, f, cur ^ 1);
+        for (int f = 0; f < MI_ACT + NI; ++f)
+          if (ks + 1 < NKS && f * NMS / (MI_ACT + NI) == j) load_frag(ks + 1, f, cur ^ 1);
         if (AHEAD >= 1) {
           const int m = ks * NMS + j;
           // (a skinny tile has more DMA instructions than MFMAs: then several follow one MFMA)
@@ -340,9 +359,6 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
     __builtin_amdgcn_sched_barrier(0);
   };
   int kt = 0;
-  using std::integral_constant;
-  using std::false_type;
-  using std::true_type;
   if (HR) {
     for (; kt + 3 < KT; ++kt) k_tile(kt, integral_constant<int, 2>{}, false_type{});   // fetches B(kt+1), A(kt+2)
     for (; kt + 2 < KT; ++kt) k_tile(kt, integral_constant<int, 2>{}, true_type{});    // A(KT-1)
@@ -360,10 +376,10 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
   if (p.k_split > 1) {
     float* slab = p.P + (int64_t)k_part * p.p_rows * p.ldp;
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+    for (int mi = 0; mi < MI_ACT; ++mi)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int r = mt * BM + wm * TM + mi * 32 + (i / 4) * 8 + lh * 4 + (i % 4);
+        const int r = mt * BM + row_block(mi) * 32 + (i / 4) * 8 + lh * 4 + (i % 4);
         if (r >= cnt) continue;
         float* prow = slab + (int64_t)(seg0 + r) * p.ldp;
 #pragma unroll
@@ -388,7 +404,7 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
   bf16_t* out_base = (MODE == 1) ? p.C + hoff : p.C + (int64_t)seg0 * p.d;
   const int64_t out_ld = (MODE == 1) ? wp : p.d;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
+  for (int mi = 0; mi < MI_ACT; ++mi) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int rr = (i / 4) * 8 + lh * 4 + (i % 4);
@@ -409,12 +425,29 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
 #pragma unroll
     for (int q = lane; q < 32 * CPRO; q += 64) {
       const int rr = q / CPRO, cc = q % CPRO;
-      const int r = mt * BM + wm * TM + mi * 32 + rr;
+      const int r = mt * BM + row_block(mi) * 32 + rr;
       const int col = out_col0 + cc * 8;
       const uint4 v = *reinterpret_cast<const uint4*>(strip + rr * LDO + cc * 8);
       if (r < cnt && col < out_cols) *reinterpret_cast<uint4*>(out_base + (int64_t)r * out_ld + col) = v;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // reads done before the strip is overwritten
+  }
+};   // body
+  if constexpr (DYN) {
+    const int rows_here = cnt - mt * BM;
+    const int nb = rows_here >= BM ? MI : ((rows_here + 31) / 32 + WGM - 1) / WGM;      // blocks per wave row
+    switch (nb) {
+      case 1: body(integral_constant<int, 1>{}); break;
+      case 2: if constexpr (MI >= 2) body(integral_constant<int, 2>{}); break;
+      case 3: if constexpr (MI >= 3) body(integral_constant<int, 3>{}); break;
+      case 4: if constexpr (MI >= 4) body(integral_constant<int, 4>{}); break;
+      case 5: if constexpr (MI >= 5) body(integral_constant<int, 5>{}); break;
+      case 6: if constexpr (MI >= 6) body(integral_constant<int, 6>{}); break;
+      case 7: if constexpr (MI >= 7) body(integral_constant<int, 7>{}); break;
+      default: body(integral_constant<int, MI>{}); break;
+    }
+  } else {
+    body(integral_constant<int, MI>{});
   }
 }
 
@@ -441,7 +474,16 @@ static const TileCfg kCfgs[] = {
     {224, 256, 1, 4, 0, 64},   // 9: four waves of 224x64 (all rows, a quarter of the columns each): 7/8 of the
                                //    MFMA work of 6 per tile, for segments that fill 256-row tiles poorly
     {192, 256, 1, 4, 0, 64},   // 10: four waves of 192x64
+    {256, 256, 1, 4, 0, 64},   // 11: four waves of 256x64 with a dynamic tile height (DYN): a ragged segment's last tile
+                               //     costs its rows in steps of 32, so the tallest tile wastes the least
+    {128, 256, 1, 4, 3, 32},   // 12: the arrangement of 8 (two workgroups per CU, three K tiles of 32) with four waves
+                               //     of 128x64 and a dynamic tile height
+    {256, 256, 2, 2, 0, 64},   // 13: shape 6 (four waves of 128x128) with a dynamic tile height in steps of 64 rows: a
+                               //     wave reads each A fragment for 128 columns, which the LDS keeps up with; four
+                               //     waves of 256x64 (11) read a quarter more and are bound by it
+    {128, 256, 2, 2, 3, 32},   // 14: shape 8 with a dynamic tile height in steps of 64 rows
 };
+static bool cfg_is_dyn(int ci) { return ci >= 11 && ci <= 14; }
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
 // Which tile shape for contraction `which` (1: gate/up, 2: down) of a batch of T tokens: the tuning switches
@@ -535,13 +577,16 @@ static int cfg_index(int which, const Engine& e, int64_t T) {
   return (forced >= 0 && forced < kNumCfgs) ? forced : dflt;
 }
 
-// which = 1: BM of gate/up, 2: BM of down, 3: BN of gate/up (packed rows), 4: BN of down
+// which = 1: BM of gate/up, 2: BM of down, 3: BN of gate/up (packed rows), 4: BN of down,
+// 5 / 6: rows per height step when the gate/up / down contraction runs tiles of dynamic height, else 0
 int bf16_gemm_tile(int which, const Engine& e, int64_t T) {
   switch (which) {
     case 1: return kCfgs[cfg_index(1, e, T)].bm;
     case 2: return kCfgs[cfg_index(2, e, T)].bm;
     case 3: return kCfgs[cfg_index(1, e, T)].bn;
-    default: return kCfgs[cfg_index(2, e, T)].bn;
+    case 4: return kCfgs[cfg_index(2, e, T)].bn;
+    case 5: return cfg_is_dyn(cfg_index(1, e, T)) ? 32 * kCfgs[cfg_index(1, e, T)].wgm : 0;
+    default: return cfg_is_dyn(cfg_index(2, e, T)) ? 32 * kCfgs[cfg_index(2, e, T)].wgm : 0;
   }
 }
 
@@ -658,11 +703,11 @@ static hipError_t launch_kernel(K kern, size_t smem, int threads, bool& attr_don
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE>
+template <int BM, int BN, int BKT, int STAGES, int WGM, int WGN, int MODE, bool DYN = false>
 static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   static bool attr_done = false;
   constexpr size_t smem = (STAGES == 0 ? 5 * (size_t)(BM > BN ? BM : BN) : STAGES * (size_t)(BM + BN)) * BKT * sizeof(bf16_t);
-  return launch_kernel(grouped_gemm_bf16_dma<BM, BN, BKT, STAGES, WGM, WGN, MODE>, smem, WGM * WGN * 64, attr_done, a, s);
+  return launch_kernel(grouped_gemm_bf16_dma<BM, BN, BKT, STAGES, WGM, WGN, MODE, DYN>, smem, WGM * WGN * 64, attr_done, a, s);
 }
 
 template <int MODE>
@@ -678,6 +723,10 @@ static hipError_t launch_cfg(int ci, const GemmArgs& a, hipStream_t s) {
     case 8: return launch_dma<128, 256, 32, 3, 2, 2, MODE>(a, s);
     case 9: return launch_dma<224, 256, 64, 0, 1, 4, MODE>(a, s);
     case 10: return launch_dma<192, 256, 64, 0, 1, 4, MODE>(a, s);
+    case 11: return launch_dma<256, 256, 64, 0, 1, 4, MODE, true>(a, s);
+    case 12: return launch_dma<128, 256, 32, 3, 1, 4, MODE, true>(a, s);
+    case 13: return launch_dma<256, 256, 64, 0, 2, 2, MODE, true>(a, s);
+    case 14: return launch_dma<128, 256, 32, 3, 2, 2, MODE, true>(a, s);
     default: return launch_dma<256, 256, 32, 4, 2, 4, MODE>(a, s);
   }
 }
@@ -703,7 +752,19 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.C = reinterpret_cast<bf16_t*>(ws + L.h);
   a.work = reinterpret_cast<const int32_t*>(ws + L.work1);
   a.slot2tok = a.single ? nullptr : reinterpret_cast<const int32_t*>(ws + L.slot2tok);
-  a.n_blocks = (int)round_up64(gemm_work_bound(e, T, 1), 8);
+  {
+    // An XCD's share of a work list has equal estimated cost, not equal length (see place_tile): with tiles of
+    // dynamic height the cheapest tile counts 3 blocks of 32 rows and a full one bm / 32, so the longest share
+    // can hold that many times an eighth of the list.
+    const int ci = cfg_index(1, e, T);
+    const int64_t bound = gemm_work_bound(e, T, 1);
+    int64_t share = (bound + 7) / 8;
+    if (cfg_is_dyn(ci) && remap && !a.single) {
+      const int full = kCfgs[ci].bm / 32, low = std::min(full, 3);
+      share = std::min<int64_t>(bound, (bound * full + 8 * low - 1) / (8 * low) + 2);
+    }
+    a.n_blocks = (int)(8 * share);
+  }
   a.P = reinterpret_cast<float*>(ws + L.splitk);
   a.p_rows = splitk_rows(e, T);
   a.k_split = splitk_that_fits(e, T, 1, L);
@@ -728,10 +789,12 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
     // share made of the cheapest tiles is longer than an eighth of the list.
     const int64_t bound = gemm_work_bound(e, T, 2);
     int c_min = 1 << 30, c_max = 1;
+    const int ci2 = cfg_index(2, e, T);
+    const int full2 = kCfgs[ci2].bm / 32, low2 = cfg_is_dyn(ci2) ? std::min(full2, 3) : full2;
     for (int g = 0; g < e.G; ++g) {
       const int c = cdiv(e.width_pad_host[g], 64) + 4;
-      c_min = std::min(c_min, c);
-      c_max = std::max(c_max, c);
+      c_min = std::min(c_min, c * low2);
+      c_max = std::max(c_max, c * full2);
     }
     const int64_t share = std::min<int64_t>(bound, (bound * c_max + 8 * c_min - 1) / (8 * c_min) + 2);
     a.n_blocks = (int)(remap && !a.single ? 8 * share : round_up64(bound, 8));

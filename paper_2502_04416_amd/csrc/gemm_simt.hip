@@ -168,6 +168,6 @@ hipError_t launch_experts_simt(const Engine& e, const void* x, int64_t T, char* 
   return run_simt<float>(e, x, T, ws, L, y, s, stage);
 }
 
-int simt_gemm_tile(int) { return SB; }
+int simt_gemm_tile(int which) { return which >= 5 ? 0 : SB; }   // (5, 6: no tiles of dynamic height here)
 
 }  // namespace cmoe

@@ -10,6 +10,7 @@
 // combine_kernel: y[t] = sum over the token's slots of weight * Y[slot]  (Eq. 4 / Eq. 10), a gather,
 // so there are no floating-point atomics and the result does not depend on scheduling.
 #include "cmoe_internal.h"
+#include "decode_device.h"
 #include "device_utils.h"
 #include "place_device.h"
 
@@ -46,8 +47,11 @@ PlaceArgs make_place_args(const Engine& e, int64_t T, char* ws, const WsLayout& 
   p.bm2 = gemm_tile(e, T, 2);
   p.bn2 = gemm_tile(e, T, 4);
   p.d = e.d;
+  p.dyn1 = gemm_tile(e, T, 5);
+  p.dyn2 = gemm_tile(e, T, 6);
   p.decode = (!use_simt_experts(e.dtype) && decode_path_ok(e, T)) ? 1 : 0;
   p.skip_always = L.skip_always;
+  p.dec_unit1 = p.decode ? decode_unit_neurons(e, T) : 16;
   return p;
 }
 

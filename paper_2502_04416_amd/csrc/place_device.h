@@ -26,7 +26,10 @@ struct PlaceArgs {
   int64_t T;
   int G, n_always, S_dyn, n_tiles;
   int bm1, bn1, bm2, bn2, d;   // tile sizes of the grouped GEMMs (bn1 in packed gate/up rows)
-  int decode;                  // 1: the work lists count decode units (16 neurons / 16 output columns per unit)
+  int dyn1, dyn2;              // > 0: that contraction runs tiles of dynamic height, in steps of this many rows (a
+                               // ragged last tile costs its rows)
+  int decode;                  // 1: the work lists count decode units (dec_unit1 neurons / 16 output columns per unit)
+  int dec_unit1;               // neurons per gate/up unit of the decode kernels (16 or 8)
   int skip_always;             // 1: no gate/up work items for the always-on groups (another launch ran them)
 };
 
@@ -135,7 +138,7 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     const int cnt = tot[k], wp = lw.w[k];
     int a1, a2;
     if (p.decode) {
-      a1 = cnt > 0 ? wp / 16 : 0;
+      a1 = cnt > 0 ? wp / p.dec_unit1 : 0;
       a2 = cnt > 0 ? p.d / 16 : 0;
     } else {
       a1 = cdiv(cnt, p.bm1) * cdiv(2 * wp, p.bn1);
@@ -176,35 +179,59 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
   if (tile == 0 && !p.decode) {            // (the decode kernels take their units in list order: no shares)
     // Where each XCD's share of a work list starts (entries G+1 .. G+9 of the list): contiguous ranges of
     // equal estimated cost, so that the tiles sharing operands stay in one L2 while the eight dies finish
-    // together.  The gate/up tiles all have the full depth d; a down tile costs its group's width
-    // (the shared group is N_s times as deep as a routed expert) plus a fixed part for prologue and epilogue.
+    // together.  A tile costs its depth (K steps of 64, plus a fixed part for prologue and epilogue: the shared
+    // group's down tiles are N_s times as deep as a routed expert's) times its height in 32-row blocks; with
+    // tiles of dynamic height the ragged last row tile of a group costs its own blocks (at least three: below
+    // that a tile is bound by fetching its weights), otherwise as much as a full one.  Inside a group the
+    // boundary falls in proportion to the cost.
     __shared__ int32_t xs[2][N_XCD + 1];
     if (lane <= N_XCD) {
       xs[0][lane] = lane == N_XCD ? w1_0 : 0;
       xs[1][lane] = lane == N_XCD ? w2_0 : 0;
     }
     wave_lds_sync();
-    int cx[GPL], c2[GPL];
-    int c0 = 0;
 #pragma unroll
-    for (int k = 0; k < GPL; ++k) {
-      c2[k] = cdiv(lw.w[k], 64) + TILE_FIXED_COST;
-      if (k > 0 && 64 * k >= p.G) { cx[k] = c0; continue; }
-      const int cost = n2[k] * c2[k];
-      const int ci = wave_incl_scan(cost, lane);
-      cx[k] = c0 + ci - cost;
-      c0 += __shfl(ci, 63, 64);
-    }
-#pragma unroll
-    for (int x = 1; x < N_XCD; ++x) {
+    for (int list = 0; list < 2; ++list) {
+      const int bm = list == 0 ? p.bm1 : p.bm2, dyn = list == 0 ? p.dyn1 : p.dyn2;
+      const int blocks_full = bm / 32 > 0 ? bm / 32 : 1;
+      long long gc[GPL], gx[GPL];             // cost of this lane's groups and their exclusive prefix
+      long long c0 = 0;
 #pragma unroll
       for (int k = 0; k < GPL; ++k) {
+        gc[k] = 0;
+        gx[k] = c0;
         if (k > 0 && 64 * k >= p.G) continue;
-        // list 1: equal item counts; list 2: equal cost
-        const int t1 = (int)((long long)x * w1_0 / N_XCD);
-        if (n1[k] > 0 && w1x[k] <= t1 && t1 < w1x[k] + n1[k]) xs[0][x] = t1;
-        const int t2 = (int)((long long)x * c0 / N_XCD);
-        if (n2[k] > 0 && cx[k] <= t2 && t2 < cx[k] + n2[k] * c2[k]) xs[1][x] = w2x[k] + (t2 - cx[k]) / c2[k];
+        const int n_items = list == 0 ? n1[k] : n2[k];
+        const int cnt = tot[k], wp = lw.w[k];
+        if (n_items > 0) {
+          const int row_tiles = cdiv(cnt, bm), col_tiles = n_items / row_tiles;
+          const int depth = (list == 0 ? cdiv(p.d, 64) : cdiv(wp, 64)) + TILE_FIXED_COST;
+          const int full = cnt / bm, rem = cnt - full * bm;
+          int last = 0;
+          if (rem > 0) {
+            last = blocks_full;
+            if (dyn) {
+              last = cdiv(rem, dyn) * (dyn / 32);           // dyn = rows per height step
+              const int floor_blocks = blocks_full < 3 ? blocks_full : 3;
+              if (last < floor_blocks) last = floor_blocks;
+            }
+          }
+          gc[k] = (long long)col_tiles * depth * (full * blocks_full + last);
+        }
+        const long long ci = wave_incl_scan(gc[k], lane);
+        gx[k] = c0 + ci - gc[k];
+        c0 += __shfl(ci, 63, 64);
+      }
+#pragma unroll
+      for (int x = 1; x < N_XCD; ++x) {
+        const long long t = (long long)x * c0 / N_XCD;
+#pragma unroll
+        for (int k = 0; k < GPL; ++k) {
+          if (k > 0 && 64 * k >= p.G) continue;
+          const int n_items = list == 0 ? n1[k] : n2[k];
+          if (n_items > 0 && gx[k] <= t && t < gx[k] + gc[k])
+            xs[list][x] = (list == 0 ? w1x[k] : w2x[k]) + (int)((t - gx[k]) * n_items / gc[k]);
+        }
       }
     }
     wave_lds_sync();

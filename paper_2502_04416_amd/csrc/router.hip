@@ -585,7 +585,8 @@ __global__ __launch_bounds__(512) void route_place_shared_kernel(RouterDev r, Ro
     route_place_body(r, io, pl, partial, n_slices, T, pre);
     return;
   }
-  decode_gate_up_unit<1, KSTEPS>(da, 0, (int)blockIdx.x - 1, 0, T, da.groups[0].width_pad, 0, red);
+  if (da.unit1 == 8) decode_gate_up_unit8<1, KSTEPS>(da, 0, (int)blockIdx.x - 1, 0, T, da.groups[0].width_pad, 0, red);
+  else decode_gate_up_unit<1, KSTEPS>(da, 0, (int)blockIdx.x - 1, 0, T, da.groups[0].width_pad, 0, red);
 }
 
 // Per-tile histogram of the routed entries (used when the scoring kernel did not produce one).
@@ -690,7 +691,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
     DecArgs da = make_dec_args(e, x, T, ws, L, nullptr);
     da.slot2tok = nullptr;                        // group 0's slots are the tokens in order; the map is not written yet
     da.work = nullptr;
-    const dim3 grid(1 + e.width_pad_host[0] / 16), block(512);
+    const dim3 grid(1 + e.width_pad_host[0] / da.unit1), block(512);
     switch (e.d / 256) {
       case 16: hipLaunchKernelGGL(route_place_shared_kernel<16>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da); break;
       case 8: hipLaunchKernelGGL(route_place_shared_kernel<8>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da); break;

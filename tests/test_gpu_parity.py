@@ -294,7 +294,7 @@ def tuning(binding):
 
 
 @pytest.mark.parametrize("which", ["CMOE_GEMM1_CFG", "CMOE_GEMM2_CFG"])
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
 def test_every_tile_shape(binding, tuning, which, shape):
     """Each tile shape of the bf16 contraction kernels forced on the gate/up or the down contraction of a
     layer whose segments end inside tiles: d = 328 (a ragged last K tile at either tile depth), experts of
