@@ -37,7 +37,7 @@ FP32_VALU_PEAK_TF = 157.3
 # HBM bytes (fetched + written) of one gate/up launch from the two rocprofv3 --pmc runs summarised under
 # profiles/ (FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 against a copy of known size), keyed by (config, T);
 # a property of the tiling and the workload, not re-measured per run
-MEASURED_GATE_UP_TRAFFIC_BYTES = {(1, 2048): 310.6e6}
+MEASURED_GATE_UP_TRAFFIC_BYTES = {(1, 2048): 310.6e6, (4, 4096): 2642.2e6}
 METRIC = "MoE-FFN layer tokens/s (+ speedup vs dense FFN; % HBM BW decode, % MFMA prefill)"
 
 
@@ -361,6 +361,13 @@ def bench_all(args, np, torch, binding, synth):
     t_setup = time.time()
     rows = []
     sub_steps = max(20, min(args.steps, 60))
+    if args.copy_probe:
+        # a copy of known size: 2^30 bytes read + 2^30 bytes written; scales FETCH_SIZE / WRITE_SIZE readings
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        a.copy_(b)
+        torch.cuda.synchronize()
+        del a, b
 
     def cycle(fns):
         st = {"i": 0}

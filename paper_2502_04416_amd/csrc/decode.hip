@@ -403,8 +403,10 @@ int decode_unit_neurons(const Engine& e, int64_t T) {
   const int forced = tuning().decode_split;
   if (forced == 8 || forced == 16) return forced;
   const int64_t dyn_groups = std::min<int64_t>(T * e.S_dyn, e.G - e.n_always);
-  const int64_t groups = dyn_groups + (decode_front_runs_shared(e, T) ? 0 : e.n_always);
-  return groups * (e.max_width_pad / 8) <= 256 ? 8 : 16;
+  int64_t units8 = e.G > e.n_always ? dyn_groups * (e.width_pad_host[e.n_always] / 8) : 0;
+  if (!decode_front_runs_shared(e, T))
+    for (int g = 0; g < e.n_always; ++g) units8 += e.width_pad_host[g] / 8;
+  return units8 <= 256 ? 8 : 16;
 }
 
 int64_t decode_unit_bound(const Engine& e, int64_t T, int which) {
