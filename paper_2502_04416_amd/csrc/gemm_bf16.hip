@@ -759,6 +759,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
     const int ci = cfg_index(1, e, T);
     const int64_t bound = gemm_work_bound(e, T, 1);
     int64_t share = (bound + 7) / 8;
+    if (remap && !a.single) share = std::min<int64_t>(bound, share + 1);   // (a boundary inside a group is rounded)
     if (cfg_is_dyn(ci) && remap && !a.single) {
       const int full = kCfgs[ci].bm / 32, low = std::min(full, 3);
       share = std::min<int64_t>(bound, (bound * full + 8 * low - 1) / (8 * low) + 2);

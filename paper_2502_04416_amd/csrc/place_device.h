@@ -194,6 +194,10 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
     for (int list = 0; list < 2; ++list) {
       const int bm = list == 0 ? p.bm1 : p.bm2, dyn = list == 0 ? p.dyn1 : p.dyn2;
       const int blocks_full = bm / 32 > 0 ? bm / 32 : 1;
+      // (Which group a boundary falls into is decided in exact integers, so that every item lands in exactly
+      // one share; where inside the group, in single precision: the shares need to be about equal, not exact,
+      // and this wave is on the critical path of the whole forward: 64-bit divisions here doubled the
+      // kernel's duration.)
       long long gc[GPL], gx[GPL];             // cost of this lane's groups and their exclusive prefix
       long long c0 = 0;
 #pragma unroll
@@ -223,14 +227,20 @@ __device__ __forceinline__ void place_tile(const PlaceArgs& p, int tile, const i
         c0 += __shfl(ci, 63, 64);
       }
 #pragma unroll
-      for (int x = 1; x < N_XCD; ++x) {
-        const long long t = (long long)x * c0 / N_XCD;
+      for (int k = 0; k < GPL; ++k) {
+        if (k > 0 && 64 * k >= p.G) continue;
+        const int n_items = list == 0 ? n1[k] : n2[k];
+        if (n_items <= 0) continue;
+        const float per_item = (float)n_items / (float)gc[k];
+        static_assert(N_XCD == 8, "the share boundaries divide by a shift");
 #pragma unroll
-        for (int k = 0; k < GPL; ++k) {
-          if (k > 0 && 64 * k >= p.G) continue;
-          const int n_items = list == 0 ? n1[k] : n2[k];
-          if (n_items > 0 && gx[k] <= t && t < gx[k] + gc[k])
-            xs[list][x] = (list == 0 ? w1x[k] : w2x[k]) + (int)((t - gx[k]) * n_items / gc[k]);
+        for (int x = 1; x < N_XCD; ++x) {
+          const long long t = (x * c0) >> 3;
+          if (gx[k] <= t && t < gx[k] + gc[k]) {
+            int local = (int)((float)(t - gx[k]) * per_item);
+            if (local > n_items - 1) local = n_items - 1;
+            xs[list][x] = (list == 0 ? w1x[k] : w2x[k]) + local;
+          }
         }
       }
     }
