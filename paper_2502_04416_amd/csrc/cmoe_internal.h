@@ -143,7 +143,8 @@ struct Tuning {
   int host_threads = 0;    // worker threads of the host-side construction (0: hardware threads, at most 16)
   int skip_rows = 1;       // 0: the gate/up contraction multiplies the 32-row blocks past the end of a segment too
   int decode_split = -1;   // K split of the decode gate/up units across workgroups (-1: chosen per batch)
-  int ws_down = 1;         // 0: never use the weight-stationary down contraction
+  int ws_down = 0;         // 1: the weight-stationary down contraction where the batch gives it enough work items,
+                           // 2: wherever it has an instantiation for the widths; 0 (default): never (measured slower)
   int skip_stage = 0;      // measurement aid: 3, 4 or 5 leaves out the gate/up, down or combine launch of every
                            // forward (outputs are then meaningless); the time a forward loses is that stage's
                            // cost inside the stream, launch gap included.  Other values: nothing is skipped.

@@ -34,6 +34,7 @@ struct GemmArgs {
   int n_blocks;              // grid size (multiple of 8) before the K split
   int xcd_remap;             // 1: consecutive work items run on the same XCD
   int zero_pad;              // 1: tile rows past the end of a group read zeros instead of repeating its last row
+  int ws_skip;               // 1 (down contraction): groups the weight-stationary kernel handles are left to it
   // K split: k_split > 1 workgroups share one tile, each multiplies a contiguous range of K tiles and
   // stores its fp32 partial sums to P [k_split][p_rows][ldp] (row = slot, column = column of the tile
   // grid); a finishing kernel adds the parts in order and applies the epilogue.  Used when a launch has
@@ -155,6 +156,7 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
     cnt = p.seg_off[g + 1] - seg0;
     wp = p.groups[g].width_pad;
     hoff = p.h_off[g];
+    if (MODE == 2 && p.ws_skip && (wp == 352 || wp == 448 || wp == 704)) return;
   }
   // this workgroup's range of K tiles (all of them without a K split); from here on K and the tile
   // index count from the start of that range and the source pointers are shifted accordingly
@@ -482,8 +484,19 @@ static const TileCfg kCfgs[] = {
                                //     wave reads each A fragment for 128 columns, which the LDS keeps up with; four
                                //     waves of 256x64 (11) read a quarter more and are bound by it
     {128, 256, 2, 2, 3, 32},   // 14: shape 8 with a dynamic tile height in steps of 64 rows
+    // 15-18: the weight-stationary down contraction (ws_down.hip): work items of 128 / 256 / 512 / 1024 rows x 256 columns,
+    // cost in steps of 64 rows; groups it has no instantiation for run shape 8 (128 rows) or 6 (256 rows) over
+    // the same list
+    {128, 256, 2, 2, 3, 32},
+    {256, 256, 2, 2, 0, 32},
+    {512, 256, 2, 2, 0, 32},
+    {1024, 256, 2, 2, 0, 32},  // 18: the same with 1024 rows per item
 };
-static bool cfg_is_dyn(int ci) { return ci >= 11 && ci <= 14; }
+static bool cfg_is_ws(int ci) { return ci >= 15 && ci <= 18; }
+static bool cfg_is_dyn(int ci) { return ci >= 11 && ci <= 18; }
+bool ws_down_handles(int width_pad);
+hipError_t launch_ws_down(const Engine& e, char* ws, const WsLayout& L, const void* y_slots, int rc, int n_blocks,
+                          int xcd_remap, hipStream_t s);
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 
 // Which tile shape for contraction `which` (1: gate/up, 2: down) of a batch of T tokens: the tuning switches
@@ -574,7 +587,25 @@ static int cfg_index(int which, const Engine& e, int64_t T) {
     }
   }
   const int forced = which == 1 ? tuning().gemm1_cfg : tuning().gemm2_cfg;
-  return (forced >= 0 && forced < kNumCfgs) ? forced : dflt;
+  if (forced >= 0 && forced < kNumCfgs && !(which == 1 && cfg_is_ws(forced))) return forced;
+  if (which == 2 && tuning().ws_down != 0 && !(e.G == 1 && e.n_always == 1) && e.w_tiled && e.d % 256 == 0) {
+    // The weight-stationary kernel for the groups it handles, when the batch gives it enough work items to
+    // fill the chip several times over: the largest row chunk that still leaves four rounds of items (a chunk
+    // pays once for loading its strip of weights into registers).  Groups of other widths keep a 128- or
+    // 256-row tile of the general kernel over the same list.
+    bool any = false, all = true;
+    for (int g = 0; g < e.G; ++g) {
+      if (ws_down_handles(e.width_pad_host[g])) any = true;
+      else all = false;
+    }
+    if (any) {
+      if (all && est_tiles(e, T, 2, 1024, 256) >= 1024) return 18;
+      if (all && est_tiles(e, T, 2, 512, 256) >= 1024) return 17;
+      if (est_tiles(e, T, 2, 256, 256) >= 1024) return 16;
+      if (est_tiles(e, T, 2, 128, 256) >= 768 || tuning().ws_down == 2) return 15;
+    }
+  }
+  return dflt;
 }
 
 // which = 1: BM of gate/up, 2: BM of down, 3: BN of gate/up (packed rows), 4: BN of down,
@@ -614,6 +645,7 @@ static int splitk_ldp(const Engine& e, int which) { return which == 1 ? 2 * e.ma
 
 int bf16_splitk(const Engine& e, int64_t T, int which) {
   if (T < 1 || T > 1024 || tuning().splitk == 0) return 1;
+  if (cfg_is_ws(cfg_index(which, e, T))) return 1;
   const TileCfg& c = kCfgs[cfg_index(which, e, T)];
   const int64_t tiles = est_tiles(e, T, which, c.bm, c.bn);
   int k_min = e.d;
@@ -746,6 +778,7 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   a.single = (e.G == 1 && e.n_always == 1) ? 1 : 0;
   a.xcd_remap = remap;
   a.zero_pad = tuning().zero_pad;
+  a.ws_skip = 0;
   // gate/up
   a.A = static_cast<const bf16_t*>(x);
   a.B = static_cast<const bf16_t*>(e.w1);
@@ -802,6 +835,21 @@ hipError_t launch_experts_bf16(const Engine& e, const void* x, int64_t T, char* 
   }
   a.k_split = splitk_that_fits(e, T, 2, L);
   a.ldp = splitk_ldp(e, 2);
+  {
+    const int ci2 = cfg_index(2, e, T);
+    if (cfg_is_ws(ci2)) {
+      bool wide = false;
+      for (int g = 0; g < e.G; ++g) wide = wide || !ws_down_handles(e.width_pad_host[g]);
+      hipError_t err = hipSuccess;
+      if (wide) {
+        a.ws_skip = 1;
+        a.k_split = 1;
+        err = launch_cfg<2>(kCfgs[ci2].bm == 128 ? 8 : 6, a, s);
+      }
+      if (err == hipSuccess) err = launch_ws_down(e, ws, L, a.C, kCfgs[ci2].bm, a.n_blocks, a.xcd_remap, s);
+      return err;
+    }
+  }
   hipError_t err = launch_cfg<2>(cfg_index(2, e, T), a, s);
   if (err == hipSuccess && a.k_split > 1) {
     hipLaunchKernelGGL(splitk_finish_down, dim3((unsigned)a.p_rows), dim3(256), 0, s, a.P, a.k_split, a.p_rows, e.d, a.C);

@@ -305,7 +305,7 @@ def test_every_tile_shape(binding, tuning, which, shape):
     x = synth.make_token_source(cfg).eval_batch(0, n=333)
     layer = _layer(binding, cfg, weights, part)
     tuning("CMOE_SPLITK", 0, 1)                     # (a K split adds the parts in another order)
-    tuning("CMOE_WS_DOWN", 0, 1)                    # (the forced shape must be the one that runs)
+    tuning("CMOE_WS_DOWN", 0, 0)                    # (the forced shape must be the one that runs)
     ref = layer.forward(x)
     tuning(which, shape, -1)
     out = layer.forward(x)
@@ -315,6 +315,29 @@ def test_every_tile_shape(binding, tuning, which, shape):
     # every shape multiplies K in the same order with the same instruction, so without a K split the tile
     # shape does not change a single bit of the output
     assert np.array_equal(out["y"], ref["y"])
+    layer.close()
+
+
+@pytest.mark.parametrize("m,n_s,T", [(344, 1, 700), (344, 2, 129), (448, 1, 1000), (688, 1, 333), (448, 3, 515), (344, 0, 64)])
+def test_weight_stationary_down_contraction(binding, tuning, m, n_s, T):
+    """The weight-stationary down kernel forced on reduced layers whose expert widths it has instantiations for
+    (344 -> 352, 448, 688 -> 704 neurons), with row chunks that end inside a 64-row piece, empty and tiny
+    segments, a shared group of the same or of twice the width (also handled) or three times (left to the
+    tiled kernel over the same work list), against the oracle and bit for bit against the tiled kernel."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=512, d_ff=12 * m, n_experts=12, n_shared=n_s, top_k=3, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    tuning("CMOE_SPLITK", 0, 1)
+    tuning("CMOE_WS_DOWN", 0, 0)
+    ref = layer.forward(x)
+    tuning("CMOE_WS_DOWN", 2, 0)
+    out = layer.forward(x)
+    _say("ws down m=%d N_s=%d T=%d" % (m, n_s, T), check_flat(cfg, weights, part, x, out))
+    # both kernels multiply K in steps of 16 in ascending order with the same instruction: identical bits
+    assert np.array_equal(out["y"], ref["y"])
+    assert np.array_equal(out["y"], layer.forward(x)["y"])
     layer.close()
 
 
