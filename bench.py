@@ -309,7 +309,15 @@ def stage_costs_ms(binding, fn, steps, prefill, timed_fns):
             out["gate_up"] = max(event_loop_ms(fn, steps) - full, 1e-6)
         else:
             binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 3)
-            out["gate_up"] = max(full - event_loop_ms(fn, steps), 1e-6)
+            out["gate_up"] = max(full - event_loop_ms(fn, steps), 0.0)
+            if out["gate_up"] < 0.1 * full:
+                # one token on a flat layer: there is no gate/up launch, the selection launch runs every gate/up
+                # unit; its cost = (loop without the down launch) - (loop with the scoring launch only)
+                binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 4)
+                no_down = event_loop_ms(fn, steps)
+                binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 6)
+                out["gate_up"] = max(no_down - event_loop_ms(fn, steps), 1e-6)
+                out["fused_front"] = True
     finally:
         binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 0)
         binding.cmoe_set_tuning("CMOE_REPEAT_STAGE", 0)
@@ -343,12 +351,14 @@ def entry(cfg, T, ms, base_ms, costs, act_per_token, union=None, shared_front=Fa
                     "whole_path_frac": flops_all / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF})
     else:
         n_shared_groups = cfg.n_shared * (cfg.outer_top_k if cfg.n_outer else 1)
-        bytes_gu = es * 2.0 * d * m * (union - (n_shared_groups if shared_front else 0))
+        fused = bool(costs.get("fused_front"))
+        bytes_gu = es * 2.0 * d * m * (union - (n_shared_groups if (shared_front and not fused) else 0))
         n_router = cfg.n_routed * (cfg.n_outer or 1)
         bytes_all = es * (3.0 * d * m * union + 2.0 * d * n_router)
-        row.update({"dominant_kernel": "decode_gate_up_kernel" if T <= 16 else "grouped_gemm_bf16_dma<gate_up> (64x128 tiles)",
+        row.update({"dominant_kernel": ("route_place_all_kernel (selection + every gate/up unit)" if fused else
+                                        "decode_gate_up_kernel" if T <= 16 else "grouped_gemm_bf16_dma<gate_up> (64x128 tiles)"),
                     "bound": "hbm", "kernel_ms": gu, "expert_groups_touched": union,
-                    "shared_experts_in_front_launch": bool(shared_front),
+                    "shared_experts_in_front_launch": bool(shared_front), "all_gate_up_units_in_front_launch": fused,
                     "achieved": bytes_gu / (gu * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": bytes_gu / (gu * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "whole_path_frac": bytes_all / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})

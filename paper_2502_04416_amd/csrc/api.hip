@@ -49,7 +49,7 @@ static const TuningField kTuningFields[] = {
     {"CMOE_LDPAD", &Tuning::ldpad},             {"CMOE_HOST_THREADS", &Tuning::host_threads},
     {"CMOE_SKIP_ROWS", &Tuning::skip_rows},     {"CMOE_DECODE_SPLIT", &Tuning::decode_split},
     {"CMOE_WS_DOWN", &Tuning::ws_down},         {"CMOE_SKIP_STAGE", &Tuning::skip_stage},
-    {"CMOE_REPEAT_STAGE", &Tuning::repeat_stage},
+    {"CMOE_REPEAT_STAGE", &Tuning::repeat_stage}, {"CMOE_FRONT_ALL", &Tuning::front_all},
 };
 
 Tuning& tuning() {
@@ -803,6 +803,7 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   // decode batches: scoring is one kernel, selection + permutation a second one
   const bool front = !single && !use_simt_experts(e.dtype) && decode_front_ok(e, T);
   L.skip_always = (front && decode_front_runs_shared(e, T)) ? 1 : 0;
+  L.gate_up_done = (front && decode_front_runs_all(e, T)) ? 1 : 0;
   mark(0);
   if (!single) {
     err = front ? launch_decode_front(e, x, T, w, L, topk, outer, scores, counts, s)
@@ -810,6 +811,7 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
     if (err != hipSuccess) return fail_hip(err, "router kernel");
   }
   mark(1);
+  if (front && tuning().skip_stage == 6) return CMOE_OK;   // (measurement aid: nothing after the scoring launch)
   if (!single && !front) {
     err = launch_permute(e, T, w, L, counts, s);
     if (err != hipSuccess) return fail_hip(err, "permute kernel");
@@ -817,7 +819,7 @@ static int run_engine(const Engine& e, const void* x, int64_t T, void* y, int32_
   mark(2);
   // (skip: measurement aid, see Tuning::skip_stage; only launches that produce no control data can be left out)
   const int skip = tuning().skip_stage, twice = tuning().repeat_stage;
-  for (int n = (skip == 3 ? 0 : twice == 3 ? 2 : 1); n > 0 && err == hipSuccess; --n) err = launch_experts(e, x, T, w, L, y, s, 1);
+  for (int n = ((skip == 3 || L.gate_up_done) ? 0 : twice == 3 ? 2 : 1); n > 0 && err == hipSuccess; --n) err = launch_experts(e, x, T, w, L, y, s, 1);
   if (err == hipSuccess && e.sparse_mode != 0 && !decode_sparse_down_ok(e, T)) err = launch_mask_hidden(e, T, w, L, s);
   if (err != hipSuccess) return fail_hip(err, "gate/up expert kernel");
   mark(3);

@@ -89,6 +89,7 @@ struct WsLayout {
   int n_tok_tiles;
   int skip_always;                   // 1: the gate/up work list leaves out the always-on group (the routing front end
                                      // runs its units itself, next to selection and placement)
+  int gate_up_done;                  // 1: the routing front end ran every gate/up unit (one token): no gate/up launch
 };
 
 // A grouped SwiGLU problem on the device: router (optional) -> permute -> experts -> combine.
@@ -138,6 +139,7 @@ struct Tuning {
   int zero_pad = 1;        // 0: tile rows past the end of a group repeat its last row instead of reading zeros
   int decode_fuse = 1;     // 0: separate down and combine kernels for batches of at most 32 tokens
   int front_shared = 1;    // 0: the shared expert's gate/up units stay in the gate/up launch at decode
+  int front_all = 1;       // 0: at one token the routed gate/up units keep a launch of their own
   int force_simt = 0;      // 1: bf16 layers run the plain FMA kernels
   int ldpad = 0;           // extra elements in the row stride of a row-major (fp32) packed gate/up matrix
   int host_threads = 0;    // worker threads of the host-side construction (0: hardware threads, at most 16)
@@ -147,7 +149,10 @@ struct Tuning {
                            // 2: wherever it has an instantiation for the widths; 0 (default): never (measured slower)
   int skip_stage = 0;      // measurement aid: 3, 4 or 5 leaves out the gate/up, down or combine launch of every
                            // forward (outputs are then meaningless); the time a forward loses is that stage's
-                           // cost inside the stream, launch gap included.  Other values: nothing is skipped.
+                           // cost inside the stream, launch gap included.  6: a batch that takes the decode front
+                           // end runs its scoring launch and nothing else (with 4, the difference is the cost of
+                           // the selection launch, which at one token holds every gate/up unit).  Other values:
+                           // nothing is skipped.
   int repeat_stage = 0;    // measurement aid: 3, 4 or 5 launches that stage twice (same inputs, same outputs); the
                            // time a forward gains is one more launch of it under the forward's own clocks
 };
@@ -197,6 +202,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
 // see decode.hip.
 bool decode_path_ok(const Engine& e, int64_t T);
 bool decode_front_runs_shared(const Engine& e, int64_t T);   // the front end's second launch also runs group 0's gate/up
+bool decode_front_runs_all(const Engine& e, int64_t T);      // ... and every routed unit too (one token, flat layer)
 bool decode_fuses_combine(const Engine& e, int64_t T);   // the down kernel also does the weighted sum over slots
 hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
 // Neuron-level sparsity (Engine::sparse_mode): the down + combine kernel of one or two tokens that reads only the

@@ -589,6 +589,62 @@ __global__ __launch_bounds__(512) void route_place_shared_kernel(RouterDev r, Ro
   else decode_gate_up_unit<1, KSTEPS>(da, 0, (int)blockIdx.x - 1, 0, T, da.groups[0].width_pad, 0, red);
 }
 
+// One token on a flat layer: the launch that selects and places also runs *every* gate/up unit, the routed
+// ones included.  Workgroup 0 is route_place_kernel's body; workgroups 1 .. U_s run the shared group's units;
+// workgroup 1 + U_s + k * U_r + j runs unit j of the k-th selected expert, which it finds by itself: its wave 0
+// adds the K-slice partials of the router pre-activations in the same order as workgroup 0 does, scores them
+// with the same arithmetic and runs the same top-N_k, so every workgroup arrives at the same experts with no
+// hand-off between workgroups.  What it needs is 8 slices x the router rows (a few KB, the same few lines for
+// all workgroups), not the router matrix.  The rows of H follow the placement rule: segments in ascending
+// group id, so the expert's row of H starts after the shared group's and after the rows of the selected
+// experts with smaller ids.  One launch and its gap less than scoring + (selection, shared units) + routed
+// units; the separate gate/up launch is skipped.
+template <int KSTEPS>
+__global__ __launch_bounds__(512) void route_place_all_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
+                                                              const float* __restrict__ partial, int n_slices,
+                                                              DecArgs da, int units_shared, int units_routed) {
+  extern __shared__ float pre[];
+  __shared__ DecGateUpRed<1> red;
+  __shared__ int32_t my_sel_g[MAX_DYN];
+  __shared__ float my_sel_w[MAX_DYN];
+  if (blockIdx.x == 0) {
+    route_place_body(r, io, pl, partial, n_slices, 1, pre);
+    return;
+  }
+  const int b = (int)blockIdx.x - 1;
+  if (b < units_shared) {
+    if (da.unit1 == 8) decode_gate_up_unit8<1, KSTEPS>(da, 0, b, 0, 1, da.groups[0].width_pad, 0, red);
+    else decode_gate_up_unit<1, KSTEPS>(da, 0, b, 0, 1, da.groups[0].width_pad, 0, red);
+    return;
+  }
+  const int k = (b - units_shared) / units_routed, local = (b - units_shared) % units_routed;
+  const int tid = threadIdx.x;
+  if (tid < 64) {
+    const int n_rows = r.n_sw_rows + r.n_lin_rows;
+    for (int row = tid; row < n_rows; row += 64) {
+      float acc = 0.0f;
+      for (int sl = 0; sl < n_slices; ++sl) acc += partial[(int64_t)sl * n_rows + row];     // T = 1: [slice][row]
+      pre[row] = acc;
+    }
+    wave_lds_sync();
+    RouteIO mine = io;
+    mine.sel_group = my_sel_g;
+    mine.sel_weight = my_sel_w;
+    mine.topk_out = nullptr;
+    mine.outer_out = nullptr;
+    mine.scores_out = nullptr;
+    route_token(r, mine, pre, 0, nullptr);
+  }
+  __syncthreads();
+  const int g = my_sel_g[k];
+  int rank = 0;
+  for (int i = 0; i < r.top_k; ++i) rank += my_sel_g[i] < g ? 1 : 0;
+  const int wp = da.groups[g].width_pad;
+  const int64_t hoff = (r.n_always ? (int64_t)da.groups[0].width_pad : 0) + (int64_t)rank * wp;
+  if (da.unit1 == 8) decode_gate_up_unit8<1, KSTEPS>(da, g, local, 0, 1, wp, hoff, red);
+  else decode_gate_up_unit<1, KSTEPS>(da, g, local, 0, 1, wp, hoff, red);
+}
+
 // Per-tile histogram of the routed entries (used when the scoring kernel did not produce one).
 __global__ __launch_bounds__(64) void tile_count_kernel(const int32_t* __restrict__ sel_group, int64_t T, int S_dyn,
                                                         int G, int32_t* __restrict__ tile_counts) {
@@ -685,7 +741,24 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
     err = launch_scorer_gemm(e, x, T, pre_g, s, n_slices);
   }
   if (err != hipSuccess) return err;
+  if (tuning().skip_stage == 6) return hipSuccess;        // measurement aid: the scoring launch only
   const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
+  if (L.gate_up_done) {
+    // (the caller set this from decode_front_runs_all: one token, flat layer, routed groups of one width)
+    DecArgs da = make_dec_args(e, x, T, ws, L, nullptr);
+    da.slot2tok = nullptr;                        // one token: every slot is token 0
+    da.work = nullptr;
+    const int us = e.n_always ? e.width_pad_host[0] / da.unit1 : 0;
+    const int ur = e.width_pad_host[e.n_always] / da.unit1;
+    const dim3 grid(1 + us + e.r.top_k * ur), block(512);
+    switch (e.d / 256) {
+      case 16: hipLaunchKernelGGL(route_place_all_kernel<16>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
+      case 8: hipLaunchKernelGGL(route_place_all_kernel<8>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
+      case 4: hipLaunchKernelGGL(route_place_all_kernel<4>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
+      default: hipLaunchKernelGGL(route_place_all_kernel<2>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
+    }
+    return hipGetLastError();
+  }
   if (L.skip_always) {
     // (the caller set this from decode_front_runs_shared: one always-on group, decode kernels, T <= 16)
     DecArgs da = make_dec_args(e, x, T, ws, L, nullptr);
@@ -706,6 +779,18 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
 
 bool decode_front_runs_shared(const Engine& e, int64_t T) {
   return tuning().front_shared != 0 && T <= FRONT_SCORE_MAX_T && e.n_always == 1 && decode_front_ok(e, T) && decode_path_ok(e, T);
+}
+
+// One token, a flat routed layer whose routed groups all have one width, at most one always-on group, the
+// decode kernels' model widths (tuning switch front_shared = 0 switches this off together with the shared
+// units in the front end).
+bool decode_front_runs_all(const Engine& e, int64_t T) {
+  if (T != 1 || tuning().front_shared == 0 || tuning().front_all == 0) return false;
+  if (e.r.outer_top_k != 0 || e.n_always > 1 || e.G <= e.n_always || e.S_dyn != e.r.top_k) return false;
+  if (!decode_front_ok(e, T) || !decode_path_ok(e, T)) return false;
+  for (int g = e.n_always; g < e.G; ++g)
+    if (e.width_pad_host[g] != e.width_pad_host[e.n_always]) return false;
+  return true;
 }
 
 hipError_t launch_router(const Engine& e, const void* x, int64_t T, char* ws, const WsLayout& L,
