@@ -312,11 +312,15 @@ def stage_costs_ms(binding, fn, steps, prefill, timed_fns):
             out["gate_up"] = max(full - event_loop_ms(fn, steps), 0.0)
             if out["gate_up"] < 0.1 * full:
                 # one token on a flat layer: there is no gate/up launch, the selection launch runs every gate/up
-                # unit; its cost = (loop without the down launch) - (loop with the scoring launch only)
+                # unit.  Without the down launch the forward is scoring + that launch; the scoring launch's cost
+                # is what a second one adds to the plain loop (a loop of scoring launches alone would run at the
+                # host's launch rate, 8 us, and say nothing about the 5-6 us kernel).
                 binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 4)
                 no_down = event_loop_ms(fn, steps)
-                binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 6)
-                out["gate_up"] = max(no_down - event_loop_ms(fn, steps), 1e-6)
+                binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 0)
+                binding.cmoe_set_tuning("CMOE_REPEAT_STAGE", 6)
+                out["score"] = max(event_loop_ms(fn, steps) - full, 0.0)
+                out["gate_up"] = max(no_down - out["score"], 1e-6)
                 out["fused_front"] = True
     finally:
         binding.cmoe_set_tuning("CMOE_SKIP_STAGE", 0)

@@ -652,7 +652,12 @@ int cmoe_update_bias(cmoe_layer* L, const int32_t* counts, float gamma) {
 }
 
 // device buffer of a flat layer: [moe W1][moe W2][dense W1][dense W2][router][moe groups][dense groups][u][b]
-struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, w2n, nscale, total; };
+// [neuron-major routed W2][neuron norms][router in operand order]
+static bool router_tiled_ok(const cmoe_layer* L) {
+  const int d = L->cfg.d_model;
+  return L->cfg.dtype == CMOE_BF16 && d % 256 == 0 && !L->router.empty() && (L->router.size() / ((size_t)d * 2)) % 16 == 0;
+}
+struct FlatOffsets { size_t w1, w2, dw1, dw2, wr, g, dg, u, b, w2n, nscale, wrt, total; };
 static FlatOffsets flat_offsets(const cmoe_layer* L) {
   FlatOffsets o{};
   size_t off = 0;
@@ -668,8 +673,30 @@ static FlatOffsets flat_offsets(const cmoe_layer* L) {
   o.b = take(sizeof(float) * L->n_r);
   o.w2n = take(L->sparse_reserved ? L->w2n.size() : 0);
   o.nscale = take(L->sparse_reserved ? sizeof(float) * L->nscale.size() : 0);
+  o.wrt = take(router_tiled_ok(L) ? L->router.size() : 0);
   o.total = off;
   return o;
+}
+
+// Second copy of a bf16 router in the MFMA operand order of the one-token front end: the 1 KB that one wave
+// loads as an A operand (16 rows x 32 columns; lane = (column / 8) * 16 + row holds 8 consecutive columns) is
+// consecutive memory, [row block][K step][lane][8].  In the row-major matrix the 16 rows of an operand lie a
+// power of two apart and meet in one L2 channel, which does not matter for the one scoring launch that reads
+// the matrix once but does when hundreds of workgroups read it at the same time.
+static std::vector<uint8_t> tile_router_rows(const std::vector<uint8_t>& rows, int d) {
+  const size_t n_rows = rows.size() / ((size_t)d * 2);
+  std::vector<uint8_t> out(rows.size());
+  const uint16_t* src = reinterpret_cast<const uint16_t*>(rows.data());
+  uint16_t* dst = reinterpret_cast<uint16_t*>(out.data());
+  const int ksteps = d / 32;
+  for (size_t rb = 0; rb < n_rows / 16; ++rb)
+    for (int kk = 0; kk < ksteps; ++kk)
+      for (int lane = 0; lane < 64; ++lane) {
+        const size_t row = rb * 16 + (lane & 15);
+        const int col = kk * 32 + (lane >> 4) * 8;
+        std::memcpy(dst + ((rb * ksteps + kk) * 64 + lane) * 8, src + row * d + col, 16);
+      }
+  return out;
 }
 
 size_t cmoe_packed_bytes(const cmoe_layer* L) { return L ? flat_offsets(L).total : 0; }
@@ -765,9 +792,15 @@ int cmoe_upload(cmoe_layer* L, void* dev_weights, void* hip_stream) {
   if (e == hipSuccess) e = h2d(base + o.b, L->b.data(), sizeof(float) * L->n_r, s);
   if (e == hipSuccess && L->sparse_reserved) e = h2d(base + o.w2n, L->w2n.data(), L->w2n.size(), s);
   if (e == hipSuccess && L->sparse_reserved) e = h2d(base + o.nscale, L->nscale.data(), sizeof(float) * L->nscale.size(), s);
+  std::vector<uint8_t> wrt;                      // (alive until the stream has been synchronised)
+  if (e == hipSuccess && router_tiled_ok(L)) {
+    wrt = tile_router_rows(L->router, L->cfg.d_model);
+    e = h2d(base + o.wrt, wrt.data(), wrt.size(), s);
+  }
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e != hipSuccess) return fail_hip(e, "uploading packed weights");
   Engine& m = L->e_moe;
+  m.wr_tiled = router_tiled_ok(L) ? base + o.wrt : nullptr;
   m.w2n = L->sparse_reserved ? base + o.w2n : nullptr;
   m.nscale = L->sparse_reserved ? reinterpret_cast<const float*>(base + o.nscale) : nullptr;
   m.w1 = base + o.w1;

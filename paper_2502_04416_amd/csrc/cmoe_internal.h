@@ -109,6 +109,7 @@ struct Engine {
   const void* w1 = nullptr;        // [rows][d] interleaved gate/up rows of all groups
   const void* w2 = nullptr;        // per group [d][width_pad]
   const void* wr = nullptr;        // router rows
+  const void* wr_tiled = nullptr;  // flat bf16 layers: the same rows in MFMA operand order [row block][K step][lane][8]
   const GroupDev* groups = nullptr;
   const float* gate_u = nullptr;   // [n_scored] or null
   const float* gate_b = nullptr;   // [n_scored] or null
@@ -139,7 +140,11 @@ struct Tuning {
   int zero_pad = 1;        // 0: tile rows past the end of a group repeat its last row instead of reading zeros
   int decode_fuse = 1;     // 0: separate down and combine kernels for batches of at most 32 tokens
   int front_shared = 1;    // 0: the shared expert's gate/up units stay in the gate/up launch at decode
-  int front_all = 1;       // 0: at one token the routed gate/up units keep a launch of their own
+  int front_all = 1;       // one token on a flat layer.  0: the routed gate/up units keep a launch of their own;
+                           // 1: the selection launch runs them; 2: that launch also scores, every workgroup
+                           // for itself, and there is no scoring launch (measured slower: 31.8 against 28.3 us
+                           // per forward with 16 experts of 688, 34.0 against 30.7 with 32 of 448; the 300-odd
+                           // workgroups each pull the router matrix through L2 at the same time)
   int force_simt = 0;      // 1: bf16 layers run the plain FMA kernels
   int ldpad = 0;           // extra elements in the row stride of a row-major (fp32) packed gate/up matrix
   int host_threads = 0;    // worker threads of the host-side construction (0: hardware threads, at most 16)
@@ -150,11 +155,14 @@ struct Tuning {
   int skip_stage = 0;      // measurement aid: 3, 4 or 5 leaves out the gate/up, down or combine launch of every
                            // forward (outputs are then meaningless); the time a forward loses is that stage's
                            // cost inside the stream, launch gap included.  6: a batch that takes the decode front
-                           // end runs its scoring launch and nothing else (with 4, the difference is the cost of
-                           // the selection launch, which at one token holds every gate/up unit).  Other values:
-                           // nothing is skipped.
+                           // end runs its scoring launch and nothing else (such a loop is bound by the host's
+                           // launch rate, not by the kernel).  Other values: nothing is skipped.
   int repeat_stage = 0;    // measurement aid: 3, 4 or 5 launches that stage twice (same inputs, same outputs); the
-                           // time a forward gains is one more launch of it under the forward's own clocks
+                           // time a forward gains is one more launch of it under the forward's own clocks.  At
+                           // one token on a flat layer the gate/up stage is the selection launch, which 3 then
+                           // issues twice (the second finds the weights in the cache: a lower bound).  6: the
+                           // decode front end's scoring launch twice (small operands, cached either way), so
+                           // that (loop without the down launch) - (this gain) is the selection launch's cost.
 };
 Tuning& tuning();
 

@@ -517,6 +517,42 @@ __global__ __launch_bounds__(64) void decode_score_kernel(const bf16_t* __restri
   }
 }
 
+// The same partials computed inside a workgroup of eight waves instead of by a launch of its own: wave w takes
+// K slice w of every block of 16 router rows, with decode_score_kernel's operands and MFMA sequence (the
+// router read from its copy in operand order), so the values are the same bits; they go to LDS as part[slice][token][row].  For at most 16 tokens.  The caller
+// puts a barrier between this and the first read of `part`.
+template <int KSTEPS>
+__device__ __forceinline__ void score_slices_in_workgroup(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wr,
+                                                          int d, int T, int n_rows, float* part) {
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int kbase = slice * (KSTEPS * 32) + kq * 8;
+  const bool ok = r16 < T;
+  bf16x8_t b[KSTEPS];
+  const bf16_t* xr = x + (int64_t)(ok ? r16 : 0) * d + kbase;
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) {
+    if (ok) b[ks] = *reinterpret_cast<const bf16x8_t*>(xr + ks * 32);
+    else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) b[ks][i] = (__bf16)0.0f;
+    }
+  }
+  for (int row0 = 0; row0 < n_rows; row0 += 16) {
+    // wr is the copy in operand order: K step kk of row block rb is the 1 KB at ((rb * d/32 + kk) * 64 + lane) * 8
+    const bf16_t* wop = wr + (((int64_t)(row0 >> 4) * (d >> 5) + slice * KSTEPS) * 64 + lane) * 8;
+    bf16x8_t a[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) a[ks] = *reinterpret_cast<const bf16x8_t*>(wop + ks * 512);
+    floatx4_t acc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], b[ks], acc, 0, 0, 0);
+    if (ok) *reinterpret_cast<floatx4_t*>(part + ((int64_t)slice * T + r16) * n_rows + row0 + kq * 4) = acc;
+  }
+}
+
 // route_place_kernel: a batch that fits one 64-token tile is selected and permuted by one workgroup:
 // the 256 threads add the K-slice partials of the pre-activations in slice order and route the tokens in
 // teams of four lanes, then wave 0 places the tile.  Histogram and routed entries are handed over in LDS (the
@@ -602,25 +638,36 @@ __global__ __launch_bounds__(512) void route_place_shared_kernel(RouterDev r, Ro
 template <int KSTEPS>
 __global__ __launch_bounds__(512) void route_place_all_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
                                                               const float* __restrict__ partial, int n_slices,
-                                                              DecArgs da, int units_shared, int units_routed) {
+                                                              DecArgs da, int units_shared, int units_routed,
+                                                              const bf16_t* __restrict__ wr) {
   extern __shared__ float pre[];
   __shared__ DecGateUpRed<1> red;
   __shared__ int32_t my_sel_g[MAX_DYN];
   __shared__ float my_sel_w[MAX_DYN];
-  if (blockIdx.x == 0) {
-    route_place_body(r, io, pl, partial, n_slices, 1, pre);
-    return;
-  }
+  const int n_rows = r.n_sw_rows + r.n_lin_rows;
   const int b = (int)blockIdx.x - 1;
-  if (b < units_shared) {
+  if (b >= 0 && b < units_shared) {
     if (da.unit1 == 8) decode_gate_up_unit8<1, KSTEPS>(da, 0, b, 0, 1, da.groups[0].width_pad, 0, red);
     else decode_gate_up_unit<1, KSTEPS>(da, 0, b, 0, 1, da.groups[0].width_pad, 0, red);
+    return;
+  }
+  if (wr) {
+    // no scoring launch: every workgroup that needs the pre-activations computes the K-slice partials itself
+    // (the router matrix is a few hundred KB that all of them find in L2 after the first) and keeps them in
+    // LDS behind the selection's arrays
+    float* part = pre + ((n_rows + 1 + MAX_SCORED + 1 + 3) & ~3);      // 16-byte aligned
+    score_slices_in_workgroup<KSTEPS>(da.x, wr, da.d, 1, n_rows, part);
+    __syncthreads();
+    partial = part;
+    n_slices = DEC_SLICES;
+  }
+  if (blockIdx.x == 0) {
+    route_place_body(r, io, pl, partial, n_slices, 1, pre);
     return;
   }
   const int k = (b - units_shared) / units_routed, local = (b - units_shared) % units_routed;
   const int tid = threadIdx.x;
   if (tid < 64) {
-    const int n_rows = r.n_sw_rows + r.n_lin_rows;
     for (int row = tid; row < n_rows; row += 64) {
       float acc = 0.0f;
       for (int sl = 0; sl < n_slices; ++sl) acc += partial[(int64_t)sl * n_rows + row];     // T = 1: [slice][row]
@@ -722,19 +769,24 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   float* pre_g = reinterpret_cast<float*>(ws + L.scores);
   const int Ti = (int)T;
   int n_slices = DEC_SLICES;
-  hipError_t err;
-  if (T <= FRONT_SCORE_MAX_T) {
+  hipError_t err = hipSuccess;
+  // one token, every gate/up unit in the selection launch: with front_all = 2 that launch also scores
+  const bool own_scores = L.gate_up_done && tuning().front_all >= 2 && e.wr_tiled != nullptr;
+  if (own_scores) {
+  } else if (T <= FRONT_SCORE_MAX_T) {
     dim3 grid(n_rows / 16, DEC_SLICES), block(64);
     const bf16_t* xx = static_cast<const bf16_t*>(x);
     const bf16_t* ww = static_cast<const bf16_t*>(e.wr);
     const int ksteps = e.d / 256;                 // K steps of 32 per slice: d / (8 slices * 32)
 #define CMOE_SCORE(NTT, KS) hipLaunchKernelGGL((decode_score_kernel<NTT, KS>), grid, block, 0, s, xx, ww, e.d, Ti, n_rows, pre_g)
-    switch (ksteps) {
-      case 16: CMOE_SCORE(1, 16); break;
-      case 8: CMOE_SCORE(1, 8); break;
-      case 4: CMOE_SCORE(1, 4); break;
-      default: CMOE_SCORE(1, 2); break;
-    }
+    // (measurement aid: repeat_stage = 6 issues the scoring launch twice; it overwrites its partials)
+    for (int rep = tuning().repeat_stage == 6 ? 2 : 1; rep > 0; --rep)
+      switch (ksteps) {
+        case 16: CMOE_SCORE(1, 16); break;
+        case 8: CMOE_SCORE(1, 8); break;
+        case 4: CMOE_SCORE(1, 4); break;
+        default: CMOE_SCORE(1, 2); break;
+      }
 #undef CMOE_SCORE
     err = hipGetLastError();
   } else {
@@ -742,7 +794,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   }
   if (err != hipSuccess) return err;
   if (tuning().skip_stage == 6) return hipSuccess;        // measurement aid: the scoring launch only
-  const size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
+  size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
   if (L.gate_up_done) {
     // (the caller set this from decode_front_runs_all: one token, flat layer, routed groups of one width)
     DecArgs da = make_dec_args(e, x, T, ws, L, nullptr);
@@ -751,12 +803,18 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
     const int us = e.n_always ? e.width_pad_host[0] / da.unit1 : 0;
     const int ur = e.width_pad_host[e.n_always] / da.unit1;
     const dim3 grid(1 + us + e.r.top_k * ur), block(512);
-    switch (e.d / 256) {
-      case 16: hipLaunchKernelGGL(route_place_all_kernel<16>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
-      case 8: hipLaunchKernelGGL(route_place_all_kernel<8>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
-      case 4: hipLaunchKernelGGL(route_place_all_kernel<4>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
-      default: hipLaunchKernelGGL(route_place_all_kernel<2>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur); break;
-    }
+    const bf16_t* wr_in = own_scores ? static_cast<const bf16_t*>(e.wr_tiled) : nullptr;
+    if (own_scores) smem = sizeof(float) * (size_t)(((n_rows + 1 + MAX_SCORED + 1 + 3) & ~3) + DEC_SLICES * n_rows);
+    // (measurement aid: this launch is the layer's gate/up stage, so repeat_stage = 3 issues it twice; it reads
+    // only the scorer's partials, the token and the weights, and every write is a plain store of a value that
+    // depends on those alone, so the second launch leaves the same bits)
+    for (int rep = tuning().repeat_stage == 3 ? 2 : 1; rep > 0; --rep)
+      switch (e.d / 256) {
+        case 16: hipLaunchKernelGGL(route_place_all_kernel<16>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur, wr_in); break;
+        case 8: hipLaunchKernelGGL(route_place_all_kernel<8>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur, wr_in); break;
+        case 4: hipLaunchKernelGGL(route_place_all_kernel<4>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur, wr_in); break;
+        default: hipLaunchKernelGGL(route_place_all_kernel<2>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, da, us, ur, wr_in); break;
+      }
     return hipGetLastError();
   }
   if (L.skip_always) {

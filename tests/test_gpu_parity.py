@@ -341,6 +341,28 @@ def test_weight_stationary_down_contraction(binding, tuning, m, n_s, T):
     layer.close()
 
 
+@pytest.mark.parametrize("d,m,n_s", [(512, 64, 1), (1024, 48, 0), (2048, 32, 1)])
+def test_one_token_front_end_variants(binding, tuning, d, m, n_s):
+    """One token on a flat layer: the routed gate/up units in a launch of their own (0), inside the selection
+    launch (1, the default), and with the scoring inside that launch too, every workgroup for itself from the
+    router's copy in operand order (2).  Same arithmetic in the same order in all three: identical bits."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=d, d_ff=16 * m, n_experts=16, n_shared=n_s, top_k=3, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=1)
+    layer = _layer(binding, cfg, weights, part)
+    outs = []
+    for v in (1, 0, 2):
+        tuning("CMOE_FRONT_ALL", v, 1)
+        outs.append(layer.forward(x))
+    _say("one-token front end d=%d m=%d N_s=%d" % (d, m, n_s), check_flat(cfg, weights, part, x, outs[0]))
+    for o in outs[1:]:
+        assert np.array_equal(o["y"], outs[0]["y"])
+        assert np.array_equal(o["topk"], outs[0]["topk"])
+        assert np.array_equal(o["scores"], outs[0]["scores"])
+    layer.close()
+
+
 def _random_shapes(n, seed):
     """Seeded layer shapes and batch sizes inside the documented limits: model widths with and without the
     decode kernels (d / 256 in {2, 4} or not) and with a ragged last K tile (d = 200), expert counts up to 64,
