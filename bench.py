@@ -92,6 +92,11 @@ def parse():
                     help="neuron-level activation sparsity inside the routed experts (Sec. 5): forward time at 1, 2, 16 and "
                          "2048 tokens with the feature off and with thresholds that drop 25 / 50 / 75 %% of the routed "
                          "activations, on the config's layer")
+    ap.add_argument("--balance", action="store_true",
+                    help="load-balancing study (Sec. 4.3): the +-gamma bias step of Eq. 9 run on a stream of batches, and "
+                         "what the routing skew costs the expert kernels before and after")
+    ap.add_argument("--balance-steps", type=int, default=200, help="bias steps of the load-balancing study")
+    ap.add_argument("--gamma", type=float, default=1e-3, help="step size of the bias update (the paper's 1e-3)")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="the layer against its baseline over batch sizes from 1 token up (arbitrary partition; several "
                          "device copies of the layer and token sets are cycled so that weights come from HBM)")
@@ -332,7 +337,7 @@ def stage_costs_ms(binding, fn, steps, prefill, timed_fns):
         for f in timed_fns:
             acc += f()
             n += 1
-    out["events_raw"] = dict(zip(("router", "permute", "gate_up", "down", "combine"), (float(v) for v in acc / n)))
+    out["events_raw"] = dict(zip(("router", "permute", "gate_up", "down", "combine"), (float(v) for v in acc / max(n, 1))))
     return out
 
 
@@ -553,6 +558,60 @@ def bench_sparsity(args, cfg, np, torch, binding, synth):
         "neuron_sparsity": rows, "setup_s": time.time() - t_setup}))
 
 
+def bench_balance(args, cfg, np, torch, binding, synth):
+    """What routing skew costs, and what the bias step of Sec. 4.3 (Eq. 9) buys: forward and gate/up time of
+    held-out batches with b = 0 and after `--balance-steps` bias steps on a stream of other batches."""
+    dev = torch.device("cuda:0")
+    t_setup = time.time()
+    weights = synth.make_weights(cfg)
+    src = synth.make_token_source(cfg)
+    layer = binding.Layer.build(cfg, *weights, src.calibration(), on_gpu=True)
+    T = args.batch or max(cfg.eval_batches)
+    held = [torch.from_numpy(src.draw(7000 + i, T)).to(dev, torch.bfloat16) for i in range(4)]
+    y = torch.empty_like(held[0])
+    topk = torch.empty((T, cfg.top_k), dtype=torch.int32, device=dev)
+    counts = torch.zeros(cfg.n_routed, dtype=torch.int32, device=dev)
+    bm = 256                                      # rows of the gate/up tile at this batch size
+
+    def measure():
+        st = {"i": 0}
+
+        def step():
+            layer.forward_device(held[st["i"] % len(held)], y, None, None, None)
+            st["i"] += 1
+        costs = stage_costs_ms(binding, step, args.steps, True, [])
+        shares, tiles, rows = [], [], []
+        for x in held:
+            layer.forward_device(x, y, topk, None, counts)
+            torch.cuda.synchronize()
+            c = counts.cpu().numpy().astype(np.int64)
+            shares.append(float(c.max()) / float(c.sum()))
+            tiles.append(int(np.sum((c + bm - 1) // bm)))
+            rows.append(int(c.sum()))
+        return {"forward_ms": costs["forward"], "gate_up_ms": costs["gate_up"], "busiest_expert_share": float(np.mean(shares)),
+                "routed_row_tiles": float(np.mean(tiles)), "routed_rows_over_tile_rows": float(np.mean(rows)) / (bm * float(np.mean(tiles)))}
+    layer.set_gate_params(None, np.zeros(cfg.n_routed, dtype=np.float32))
+    before = measure()
+    gamma, n_steps = args.gamma, args.balance_steps
+    pool = [torch.from_numpy(src.draw(8000 + i, T)).to(dev, torch.bfloat16) for i in range(16)]   # the stream: 16 batches in turn
+    for i in range(n_steps):
+        layer.forward_device(pool[i % len(pool)], y, topk, None, counts)
+        torch.cuda.synchronize()
+        layer.update_bias(counts.cpu().numpy(), gamma)
+        if (i + 1) % 100 == 0:
+            print("bench.py: %d bias steps" % (i + 1), file=sys.stderr, flush=True)
+    after = measure()
+    _, b = layer.gate_params()
+    print(json.dumps({
+        "metric": METRIC, "value": T / (after["forward_ms"] * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "clock_ramp_ms": RAMP_MS, "ms_per_step": after["forward_ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "load-balancing study on cfg%d %s, T=%d; headline fields are the forward after %d bias steps of "
+                   "gamma=%g on a stream of other batches" % (cfg.cfg, cfg.name, T, n_steps, gamma), "partition": "library"},
+        "balance": {"before": before, "after": after, "uniform_share": 1.0 / cfg.n_routed, "bias_min": float(b.min()),
+                    "bias_max": float(b.max())}, "setup_s": time.time() - t_setup}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -568,6 +627,9 @@ def main():
         sys.exit(2)
     if args.sparsity:
         bench_sparsity(args, synth.CONFIGS[1 if args.config is None else args.config], np, torch, binding, synth)
+        return
+    if args.balance:
+        bench_balance(args, synth.CONFIGS[1 if args.config is None else args.config], np, torch, binding, synth)
         return
     if args.config is None and not (args.sweep or args.batch_sweep):
         bench_all(args, np, torch, binding, synth)
