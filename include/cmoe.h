@@ -286,7 +286,7 @@ int cmoe_probe_hbm(size_t bytes, int reps, double* gbytes_per_s);
 /* Tuning switch `name` (the names of the environment variables the library reads once at first use:
  * CMOE_GEMM1_CFG, CMOE_GEMM2_CFG, CMOE_XCD_REMAP, CMOE_SPLITK, CMOE_ZERO_PAD, CMOE_DECODE_FUSE,
  * CMOE_FRONT_SHARED, CMOE_FORCE_SIMT, CMOE_LDPAD, CMOE_HOST_THREADS, CMOE_SKIP_ROWS, CMOE_DECODE_SPLIT,
- * CMOE_WS_DOWN, CMOE_SKIP_STAGE, CMOE_REPEAT_STAGE, CMOE_FRONT_ALL) takes `value` from the next call on; -1
+ * CMOE_WS_DOWN, CMOE_SKIP_STAGE, CMOE_REPEAT_STAGE, CMOE_FRONT_ALL, CMOE_FRONT_TILE) takes `value` from the next call on; -1
  * restores the per-batch choice of the tile-shape switches.  For A/B measurements and tests inside one process; every default is the measured best.  Not
  * synchronised against forwards being enqueued from other host threads.  CMOE_SKIP_STAGE = 3, 4 or 5 is a
  * measurement aid: every forward then leaves out its gate/up, down or combine launch (its output is

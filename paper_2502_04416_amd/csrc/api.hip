@@ -50,6 +50,7 @@ static const TuningField kTuningFields[] = {
     {"CMOE_SKIP_ROWS", &Tuning::skip_rows},     {"CMOE_DECODE_SPLIT", &Tuning::decode_split},
     {"CMOE_WS_DOWN", &Tuning::ws_down},         {"CMOE_SKIP_STAGE", &Tuning::skip_stage},
     {"CMOE_REPEAT_STAGE", &Tuning::repeat_stage}, {"CMOE_FRONT_ALL", &Tuning::front_all},
+    {"CMOE_FRONT_TILE", &Tuning::front_tile},
 };
 
 Tuning& tuning() {

@@ -89,7 +89,7 @@ struct WsLayout {
   int n_tok_tiles;
   int skip_always;                   // 1: the gate/up work list leaves out the always-on group (the routing front end
                                      // runs its units itself, next to selection and placement)
-  int gate_up_done;                  // 1: the routing front end ran every gate/up unit (one token): no gate/up launch
+  int gate_up_done;                  // 1: the routing front end ran every gate/up unit (up to 16 tokens): no gate/up launch
 };
 
 // A grouped SwiGLU problem on the device: router (optional) -> permute -> experts -> combine.
@@ -145,6 +145,11 @@ struct Tuning {
                            // for itself, and there is no scoring launch (measured slower: 31.8 against 28.3 us
                            // per forward with 16 experts of 688, 34.0 against 30.7 with 32 of 448; the 300-odd
                            // workgroups each pull the router matrix through L2 at the same time)
+  int front_tile = 0;      // 0: batches of 2-16 tokens keep a gate/up launch for the routed experts; 1: every
+                           // routed unit runs in the selection launch, each workgroup selecting the batch itself
+                           // (measured slower: the team selection of up to 16 tokens in 700 workgroups at once
+                           // costs more than the launch it saves: 51.4 against 37.8 us at 2 tokens, 71.8 against
+                           // 62.4 us at 16, 16 experts of 688)
   int force_simt = 0;      // 1: bf16 layers run the plain FMA kernels
   int ldpad = 0;           // extra elements in the row stride of a row-major (fp32) packed gate/up matrix
   int host_threads = 0;    // worker threads of the host-side construction (0: hardware threads, at most 16)
@@ -210,7 +215,7 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
 // see decode.hip.
 bool decode_path_ok(const Engine& e, int64_t T);
 bool decode_front_runs_shared(const Engine& e, int64_t T);   // the front end's second launch also runs group 0's gate/up
-bool decode_front_runs_all(const Engine& e, int64_t T);      // ... and every routed unit too (one token, flat layer)
+bool decode_front_runs_all(const Engine& e, int64_t T);      // ... and every routed unit too (up to 16 tokens, flat layer)
 bool decode_fuses_combine(const Engine& e, int64_t T);   // the down kernel also does the weighted sum over slots
 hipError_t launch_decode_down_combine(const Engine& e, int64_t T, char* ws, const WsLayout& L, void* y, hipStream_t s);
 // Neuron-level sparsity (Engine::sparse_mode): the down + combine kernel of one or two tokens that reads only the

@@ -559,8 +559,19 @@ __device__ __forceinline__ void score_slices_in_workgroup(const bf16_t* __restri
 // workspace copies of the entries are not written: nothing after this kernel reads them).
 // The body works with the first 256 threads of the workgroup; every thread of it must call (barriers).
 // `pre`: dynamic shared memory, [T][n_rows + 1] pre-activations, then scores [T][MAX_SCORED + 1].
+// What a workgroup that runs gate/up units of routed group `group` learns from selecting the tile itself
+// (route_place_body with `mine` set): the group's tokens in ascending order (its slots, by the placement rule),
+// their number, and where the group's rows of H start (the exclusive prefix of count x padded width over the
+// groups in id order, as place_tile computes it).
+struct OwnSegment {
+  int32_t tok[16];
+  int32_t cnt;
+  long long h_off;
+};
+
 __device__ __forceinline__ void route_place_body(const RouterDev& r, RouteIO io, const PlaceArgs& pl,
-                                                 const float* __restrict__ partial, int n_slices, int T, float* pre) {
+                                                 const float* __restrict__ partial, int n_slices, int T, float* pre,
+                                                 int group = -1, OwnSegment* mine = nullptr) {
   __shared__ int32_t hist[MAX_GROUPS];
   __shared__ int32_t sel_g[TOK_TILE * MAX_DYN];
   __shared__ float sel_w[TOK_TILE * MAX_DYN];
@@ -572,6 +583,11 @@ __device__ __forceinline__ void route_place_body(const RouterDev& r, RouteIO io,
   constexpr int LDS_SC = MAX_SCORED + 1;
   LaneWidths lw;
   if (wave == 0) lw = load_lane_widths(pl, lane);          // needed last, requested first
+  if (mine) {                                              // (nothing of the tile's routing is written by this workgroup)
+    io.topk_out = nullptr;
+    io.outer_out = nullptr;
+    io.scores_out = nullptr;
+  }
   GateRegs flat_gr;
   if (worker) {
     if (r.outer_top_k == 0) flat_gr = load_gate_regs(r, io, 0, r.n_scored, tid % TEAM);
@@ -597,6 +613,25 @@ __device__ __forceinline__ void route_place_body(const RouterDev& r, RouteIO io,
     if (tok < T) route_select_team(r, io, sc + tok * LDS_SC, pre + tok * ld + r.n_sw_rows, tok, hist, tid % TEAM, flat_gr);
   }
   __syncthreads();
+  if (mine) {
+    // T <= 16 tokens, G <= 64 groups (the caller checked): lane g holds group g's count and width, lane t token t
+    if (wave == 0) {
+      const int cnt = lane < pl.n_always ? T : (lane < pl.G ? hist[lane] : 0);
+      const long long ah = (long long)cnt * lw.w[0];
+      const long long h_incl = wave_incl_scan(ah, lane);
+      if (lane == group) {
+        mine->cnt = cnt;
+        mine->h_off = h_incl - ah;
+      }
+      bool has = false;
+      if (lane < T)
+        for (int i = 0; i < pl.S_dyn; ++i) has = has || sel_g[lane * pl.S_dyn + i] == group;
+      const unsigned long long m = __ballot(has);
+      if (has) mine->tok[__popcll(m & ((1ull << lane) - 1ull))] = lane;
+    }
+    __syncthreads();
+    return;
+  }
   if (wave == 0) place_tile(pl, 0, hist, lane, sel_g, sel_w, lw);
 }
 
@@ -690,6 +725,39 @@ __global__ __launch_bounds__(512) void route_place_all_kernel(RouterDev r, Route
   const int64_t hoff = (r.n_always ? (int64_t)da.groups[0].width_pad : 0) + (int64_t)rank * wp;
   if (da.unit1 == 8) decode_gate_up_unit8<1, KSTEPS>(da, g, local, 0, 1, wp, hoff, red);
   else decode_gate_up_unit<1, KSTEPS>(da, g, local, 0, 1, wp, hoff, red);
+}
+
+// Two to sixteen tokens on a flat layer, the same idea: workgroup 0 selects and places the batch, the next
+// workgroups run the shared group's units, and every unit of *every* routed expert has a workgroup that
+// selects the whole batch by itself (the 256-thread team selection of route_place_kernel on the scorer's
+// partials, 16 KB that all workgroups share in L2), learns which tokens chose its expert and where the
+// expert's rows of H start, and runs its unit on them; the workgroups of experts nobody chose leave.  The
+// separate gate/up launch, which could not start before selection and placement had finished in one
+// workgroup, is gone.  Bit-identical to the two launches and slower than them at every batch size (the team
+// selection run by hundreds of workgroups at once takes 15 us instead of the 8 us it takes one workgroup on
+// an otherwise idle chip), so it is off unless the tuning switch front_tile asks for it.
+template <int KSTEPS>
+__global__ __launch_bounds__(512) void route_place_tile_all_kernel(RouterDev r, RouteIO io, PlaceArgs pl,
+                                                                   const float* __restrict__ partial, int n_slices, int T,
+                                                                   DecArgs da, int units_shared, int units_routed) {
+  extern __shared__ float pre[];
+  __shared__ DecGateUpRed<1> red;
+  __shared__ OwnSegment own;
+  const int b = (int)blockIdx.x - 1;
+  if (b >= 0 && b < units_shared) {
+    decode_gate_up_unit<1, KSTEPS>(da, 0, b, 0, T, da.groups[0].width_pad, 0, red);
+    return;
+  }
+  if (blockIdx.x == 0) {
+    route_place_body(r, io, pl, partial, n_slices, T, pre);
+    return;
+  }
+  const int g = r.n_always + (b - units_shared) / units_routed, local = (b - units_shared) % units_routed;
+  route_place_body(r, io, pl, partial, n_slices, T, pre, g, &own);
+  const int cnt = own.cnt;
+  if (cnt == 0) return;
+  da.slot2tok = own.tok;                          // slot j of this group = its j-th token in ascending order
+  decode_gate_up_unit<1, KSTEPS>(da, g, local, 0, cnt, da.groups[g].width_pad, own.h_off, red);
 }
 
 // Per-tile histogram of the routed entries (used when the scoring kernel did not produce one).
@@ -795,6 +863,24 @@ hipError_t launch_decode_front(const Engine& e, const void* x, int64_t T, char* 
   if (err != hipSuccess) return err;
   if (tuning().skip_stage == 6) return hipSuccess;        // measurement aid: the scoring launch only
   size_t smem = sizeof(float) * (size_t)T * (n_rows + 1 + MAX_SCORED + 1);
+  if (L.gate_up_done && T > 1) {
+    // (the caller set this from decode_front_runs_all: 2-16 tokens, flat layer of at most 64 groups, routed
+    // groups of one width, 16-neuron units)
+    DecArgs da = make_dec_args(e, x, T, ws, L, nullptr);
+    da.slot2tok = nullptr;                        // group 0's slots are the tokens in order
+    da.work = nullptr;
+    const int us = e.n_always ? e.width_pad_host[0] / 16 : 0;
+    const int ur = e.width_pad_host[e.n_always] / 16;
+    const dim3 grid(1 + us + (e.G - e.n_always) * ur), block(512);
+    for (int rep = tuning().repeat_stage == 3 ? 2 : 1; rep > 0; --rep)       // (measurement aid, as below)
+      switch (e.d / 256) {
+        case 16: hipLaunchKernelGGL(route_place_tile_all_kernel<16>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da, us, ur); break;
+        case 8: hipLaunchKernelGGL(route_place_tile_all_kernel<8>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da, us, ur); break;
+        case 4: hipLaunchKernelGGL(route_place_tile_all_kernel<4>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da, us, ur); break;
+        default: hipLaunchKernelGGL(route_place_tile_all_kernel<2>, grid, block, smem, s, e.r, io, pl, pre_g, n_slices, Ti, da, us, ur); break;
+      }
+    return hipGetLastError();
+  }
   if (L.gate_up_done) {
     // (the caller set this from decode_front_runs_all: one token, flat layer, routed groups of one width)
     DecArgs da = make_dec_args(e, x, T, ws, L, nullptr);
@@ -839,11 +925,13 @@ bool decode_front_runs_shared(const Engine& e, int64_t T) {
   return tuning().front_shared != 0 && T <= FRONT_SCORE_MAX_T && e.n_always == 1 && decode_front_ok(e, T) && decode_path_ok(e, T);
 }
 
-// One token, a flat routed layer whose routed groups all have one width, at most one always-on group, the
-// decode kernels' model widths (tuning switch front_shared = 0 switches this off together with the shared
-// units in the front end).
+// One token (switch front_all), or two to sixteen (switch front_tile; at most 64 groups, 16-neuron units), on a
+// flat routed layer whose routed groups all have one width, at most one always-on group, the decode kernels'
+// model widths (tuning switch front_shared = 0 switches this off together with the shared units in the front
+// end).
 bool decode_front_runs_all(const Engine& e, int64_t T) {
-  if (T != 1 || tuning().front_shared == 0 || tuning().front_all == 0) return false;
+  if (T < 1 || T > FRONT_SCORE_MAX_T || tuning().front_shared == 0) return false;
+  if (T == 1 ? tuning().front_all == 0 : (tuning().front_tile == 0 || e.G > 64 || tuning().decode_split == 8)) return false;
   if (e.r.outer_top_k != 0 || e.n_always > 1 || e.G <= e.n_always || e.S_dyn != e.r.top_k) return false;
   if (!decode_front_ok(e, T) || !decode_path_ok(e, T)) return false;
   for (int g = e.n_always; g < e.G; ++g)

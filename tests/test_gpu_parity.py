@@ -363,6 +363,25 @@ def test_one_token_front_end_variants(binding, tuning, d, m, n_s):
     layer.close()
 
 
+@pytest.mark.parametrize("T,n_s", [(2, 1), (7, 1), (16, 1), (5, 0)])
+def test_small_batch_front_end_with_every_unit(binding, tuning, T, n_s):
+    """Two to sixteen tokens: every routed gate/up unit inside the selection launch (each workgroup selects the
+    batch by itself and derives its expert's tokens and rows of H; off by default) against the oracle and bit
+    for bit against the default path with its separate gate/up launch."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=1024, d_ff=16 * 48, n_experts=16, n_shared=n_s, top_k=3, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    ref = layer.forward(x)
+    tuning("CMOE_FRONT_TILE", 1, 0)
+    out = layer.forward(x)
+    _say("small-batch front end T=%d N_s=%d" % (T, n_s), check_flat(cfg, weights, part, x, out))
+    for k in ("y", "topk", "scores", "counts"):
+        assert np.array_equal(out[k], ref[k])
+    layer.close()
+
+
 def _random_shapes(n, seed):
     """Seeded layer shapes and batch sizes inside the documented limits: model widths with and without the
     decode kernels (d / 256 in {2, 4} or not) and with a ragged last K tile (d = 200), expert counts up to 64,
