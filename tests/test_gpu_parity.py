@@ -418,6 +418,22 @@ def test_random_bf16_shapes(binding, i, d, N, m, N_s, N_k, T, gate):
     layer.close()
 
 
+@pytest.mark.parametrize("T", [1, 40, 300])
+def test_wide_model(binding, T):
+    """d = 8192 (twice the width of the study's layers): 128 K tiles per gate/up tile, a router scorer with
+    1024 of K per slice, and no weight-streaming decode kernels (their K split covers d up to 4096), so one
+    token runs the tile kernels too."""
+    cfg = synth.scaled(synth.CONFIGS[1], d_model=8192, d_ff=8 * 352, n_experts=8, n_shared=1, top_k=2, n_centres=16)
+    weights = synth.make_weights(cfg)
+    part = synth.trivial_partition(cfg)
+    x = synth.make_token_source(cfg).eval_batch(0, n=T)
+    layer = _layer(binding, cfg, weights, part)
+    out = layer.forward(x)
+    _say("d=8192 T=%d" % T, check_flat(cfg, weights, part, x, out))
+    check_dense(cfg, weights, x, layer.dense_forward(x))
+    layer.close()
+
+
 def _random_fp32_shapes(n, seed):
     rng = np.random.Generator(np.random.PCG64(seed))
     out = []
