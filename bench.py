@@ -487,7 +487,7 @@ def bench_all(args, np, torch, binding, synth):
         out["hbm_probe_GBs"] = None
     if not args.no_cpu:
         from oracle import cmoe_oracle as O
-        n_cpu = min(T, 1024)
+        n_cpu = min(T, 2048)                       # 10-12 s of oracle time on the box's 16 threads
         experts = []
         for e in range(cfg.n_outer):
             part = hier.expert_partition(e)
