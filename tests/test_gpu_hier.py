@@ -272,3 +272,32 @@ def test_hier_cfg4_full(binding):
     rep = _check(cfg, experts, w_router, offsets, x, out, hier.dense_forward(x), sample)
     print("\n[parity] hier cfg4 T=%d: %s" % (x.shape[0], rep), flush=True)
     hier.close()
+
+
+def test_hier_cfg4_full_on_the_hierarchy_the_library_builds(binding):
+    """The configuration the bench times: the Mixtral-8x7B-shaped layer restructured by cmoe_hier_build (profiling
+    on the device, every outer expert on the calibration tokens routed to it), 4096 tokens.  The analytically
+    built routers give skewed, ragged sub-expert segments, unlike an arbitrary partition.  Routing of every
+    token, outputs of 512 random tokens plus the last row tile of every group's segment."""
+    cfg = synth.CONFIGS[4]
+    w_router, offsets = synth.make_outer_router(cfg)
+    ws = [synth.make_outer_expert_weights(cfg, e) for e in range(cfg.n_outer)]
+    src = synth.make_token_source(cfg)
+    hier = binding.Hierarchy.build(cfg, cfg.outer_top_k, [w[0] for w in ws], [w[1] for w in ws], [w[2] for w in ws],
+                                   w_router, offsets, src.calibration(), on_gpu=True)
+    experts = []
+    for e in range(cfg.n_outer):
+        part = hier.expert_partition(e)
+        experts.append({"w_gate": ws[e][0], "w_up": ws[e][1], "w_down": ws[e][2], "neuron_order": part["neuron_order"],
+                        "rep_neuron": part["rep_neuron"]})
+    x = src.eval_batch(0)
+    out = hier.forward(x)
+    rng = np.random.Generator(np.random.PCG64(405))
+    gid = np.concatenate([out["outer"][:, :, None] * 8, out["outer"][:, :, None] * 8 + 1 + out["sub"]], axis=2)
+    sample = tail_tokens(gid.reshape(x.shape[0], -1), 64, rows=32, extra=rng.choice(x.shape[0], size=512, replace=False))
+    rep = _check(cfg, experts, w_router, offsets, x, out, hier.dense_forward(x), sample)
+    sub_load = np.bincount((out["outer"][:, :, None] * cfg.n_routed + out["sub"]).ravel(), minlength=cfg.n_outer * cfg.n_routed)
+    print("\n[parity] hier cfg4 (library build) T=%d: %s sub-expert rows min/max %d/%d" % (x.shape[0], rep, sub_load.min(), sub_load.max()),
+          flush=True)
+    hier.close()
+
