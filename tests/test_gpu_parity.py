@@ -589,6 +589,24 @@ def test_cfg1_on_the_partition_the_library_constructs(binding):
     layer.close()
 
 
+@pytest.mark.parametrize("ci", [2, 3])
+def test_cfg2_cfg3_on_the_partition_the_library_constructs(binding, ci):
+    """Configs 2 and 3 as the bench runs them: partition from cmoe_build_gpu on the calibration set, every
+    evaluation batch (4096 and 8192 tokens; 1, 32 and 4096 tokens), every token compared."""
+    cfg = synth.CONFIGS[ci]
+    weights = synth.make_weights(cfg)
+    src = synth.make_token_source(cfg)
+    layer = binding.Layer.build(cfg, *weights, src.calibration(), on_gpu=True)
+    part = layer.export_partition()
+    for bi in range(len(cfg.eval_batches)):
+        x = src.eval_batch(bi)
+        out = layer.forward(x)
+        rep = check_flat(cfg, weights, part, x, out)
+        rep["counts_min_max"] = (int(out["counts"].min()), int(out["counts"].max()))
+        _say("cfg%d library partition T=%d" % (ci, x.shape[0]), rep)
+    layer.close()
+
+
 def test_cfg1_mid_batches(binding):
     """Batch sizes between the decode path and the large-tile regime: the contraction kernels run their
     128x128 and 256x128 tile shapes at the layer's real depth."""
