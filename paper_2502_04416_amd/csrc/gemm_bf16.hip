@@ -342,7 +342,11 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
       for (int j = 0; j < NMS; ++j) {
         const int mi = j / NI, ni = j % NI;
         __builtin_amdgcn_sched_barrier(0);
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mi], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
+        // (down contraction: operands swapped, so that the accumulator block is the transpose: a lane then holds
+        // four consecutive output columns of one row instead of one column of sixteen rows, and the epilogue
+        // stages 8-byte pieces instead of single elements; same products, same order of accumulation)
+        if constexpr (MODE == 2) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
+        else acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][mi], bfr[cur][ni], acc[mi][ni], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         // fragments of the next sub-step, spread over this sub-step's MFMAs (several per MFMA only when
         // a sub-step has fewer MFMAs than fragments)
@@ -377,6 +381,27 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
   // consecutive columns of a row, so the stores are 128-byte segments ----
   if (p.k_split > 1) {
     float* slab = p.P + (int64_t)k_part * p.p_rows * p.ldp;
+    if constexpr (MODE == 2) {
+      // transposed accumulator blocks: element i of block (mi, ni) = row l32 of the row block, column
+      // (i / 4) * 8 + lh * 4 + i % 4 of the column block; four consecutive columns per 16-byte store
+      // (the slab's row stride is d, a multiple of 8)
+#pragma unroll
+      for (int mi = 0; mi < MI_ACT; ++mi) {
+        const int r = mt * BM + row_block(mi) * 32 + l32;
+        if (r >= cnt) continue;
+        float* prow = slab + (int64_t)(seg0 + r) * p.ldp;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int col = nt * BN + wn * TN + ni * 32 + q * 8 + lh * 4;
+            if (col < n_cols)
+              *reinterpret_cast<float4*>(prow + col) =
+                  make_float4(acc[mi][ni][4 * q], acc[mi][ni][4 * q + 1], acc[mi][ni][4 * q + 2], acc[mi][ni][4 * q + 3]);
+          }
+      }
+      return;
+    }
 #pragma unroll
     for (int mi = 0; mi < MI_ACT; ++mi)
 #pragma unroll
@@ -410,7 +435,7 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int rr = (i / 4) * 8 + lh * 4 + (i % 4);
-      if (MODE == 1) {
+      if constexpr (MODE == 1) {
 #pragma unroll
         for (int pi = 0; pi < NI / 2; ++pi) {
           const float gt = acc[mi][2 * pi][i], up = acc[mi][2 * pi + 1][i];
@@ -418,10 +443,22 @@ __attribute__((amdgpu_waves_per_eu(min_waves_per_simd(BM, BN, BKT, STAGES, WGM* 
           const float sg = gt * __frcp_rn(1.0f + __expf(-gt));
           strip[rr * LDO + pi * 32 + l32] = f32_to_bf16(sg * up);
         }
-      } else {
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) strip[rr * LDO + ni * 32 + l32] = f32_to_bf16(acc[mi][ni][i]);
       }
+    }
+    if constexpr (MODE == 2) {
+      // transposed blocks (see the MFMA above): this lane's row of the strip is l32, and every group of four
+      // accumulator elements is four consecutive columns: one 8-byte LDS write each
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          ushort4 v;
+          v.x = f32_to_bf16(acc[mi][ni][4 * q]);
+          v.y = f32_to_bf16(acc[mi][ni][4 * q + 1]);
+          v.z = f32_to_bf16(acc[mi][ni][4 * q + 2]);
+          v.w = f32_to_bf16(acc[mi][ni][4 * q + 3]);
+          *reinterpret_cast<ushort4*>(strip + l32 * LDO + ni * 32 + q * 8 + lh * 4) = v;
+        }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // the strip is private to this wave: no barrier
 #pragma unroll
